@@ -1,0 +1,172 @@
+/*
+ * keydiff.h -- C ABI of the MI355X (gfx950) KeyDiff block-prefill library.
+ *
+ * One call processes one prompt block of one transformer layer:
+ *   append the block's keys/values to a fixed-budget KV cache        (Eq. 5)
+ *   attention of the block over cache || block, causal in the block  (Eq. 1-2)
+ *   KeyDiff score of every one of the n = len + Bt keys per KV head:
+ *   cosine similarity to the anchor (the mean key)   (Method, "Efficient Variant";
+ *                                          appendix "FLOP count of KeyDiff")
+ *   keep the N keys with the lowest similarity, evict the rest       (Eq. 6-7, Fig. 3)
+ *   move the surviving K/V rows so the cache again occupies rows [0, N)  (Eq. 6, gather)
+ * in that order (Background, Fig. 1: attention precedes scoring and eviction).
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers unless a comment says "host".
+ *     The library never allocates or frees device memory: the caller owns the
+ *     cache, metadata and scratch buffers for the lifetime of the handle.
+ *   - Tensors are bf16, innermost dimension head_dim contiguous, 16-byte aligned:
+ *       q, out        [batch][n_q_heads ][Bt][head_dim]
+ *       k_new, v_new  [batch][n_kv_heads][Bt][head_dim]
+ *       k/v cache     [batch][n_kv_heads][budget_N + block_B][head_dim]
+ *     q and k arrive as the model produced them (rotary embedding already
+ *     applied by the caller); keys are scored exactly as they sit in the cache.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Every call enqueues its kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = default stream) and returns without synchronising.  Calls on
+ *     one handle must be issued in order on one stream.
+ *   - Return value: KEYDIFF_OK (0) or a negative error.  Argument, shape and
+ *     state errors are found before anything is enqueued and leave the cache
+ *     unchanged; KEYDIFF_EHIP (a failed launch) may leave part of the step
+ *     enqueued and the handle must then be discarded.  keydiff_last_error()
+ *     gives a thread-local message.  No exception crosses this boundary.
+ *   - Inputs must be finite.  Scores are IEEE double arithmetic on the bf16
+ *     data rounded once to float; the eviction decision is taken on that float
+ *     and ties keep the lower token position.
+ */
+#ifndef KEYDIFF_H
+#define KEYDIFF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KEYDIFF_VERSION 1
+#define KEYDIFF_API __attribute__((visibility("default")))
+
+enum {
+    KEYDIFF_OK = 0,
+    KEYDIFF_EINVAL = -1, /* null or misaligned pointer, bad enum value          */
+    KEYDIFF_ESHAPE = -2, /* unsupported or inconsistent sizes                  */
+    KEYDIFF_ESTATE = -3, /* call not valid in the handle's current state       */
+    KEYDIFF_EHIP = -4    /* a HIP runtime call or kernel launch failed         */
+};
+
+/* Which mean is the anchor (Method, "Efficient Variant of KeyDiff"). */
+enum {
+    KEYDIFF_ANCHOR_MEAN_KEY = 0,     /* mu(K): mean of the raw keys -- the variant the paper evaluates */
+    KEYDIFF_ANCHOR_MEAN_UNIT_KEY = 1 /* mu(K^): mean of the unit keys -- Eq. 7 as printed              */
+};
+
+/* Row order of the cache after an eviction (the paper's gather leaves it open;
+ * attention and the score do not depend on it). */
+enum {
+    KEYDIFF_LAYOUT_ORDERED = 0, /* survivors in ascending token position (stable shift)               */
+    KEYDIFF_LAYOUT_FILL = 1     /* survivors of rows [N, n) fill the evicted slots of rows [0, N), both
+                                   in ascending slot order: at most block_B rows move per head          */
+};
+
+typedef struct keydiff_cache keydiff_cache_t; /* opaque host handle (metadata only) */
+
+typedef struct {
+    int32_t batch;         /* independent sequences                                           */
+    int32_t n_q_heads;     /* multiple of n_kv_heads                                          */
+    int32_t n_kv_heads;
+    int32_t head_dim;      /* 64 or 128                                                       */
+    int32_t budget_N;      /* cache budget N (Background, "KV Cache Eviction Methods")        */
+    int32_t block_B;       /* largest block size B (Eq. 5); capacity is N + B rows per head   */
+    int32_t anchor_mode;   /* KEYDIFF_ANCHOR_*                                                */
+    int32_t window_W;      /* most recent tokens exempt from eviction (Method, "KeyDiff with
+                              Sliding Window"); 0 = plain KeyDiff; must be < budget_N          */
+    int32_t layout;        /* KEYDIFF_LAYOUT_*                                                */
+    float eps;             /* clamp of |mu||k| in the cosine; <= 0 selects 1e-8               */
+    float softmax_scale;   /* <= 0 selects 1/sqrt(head_dim) (Eq. 1)                            */
+} keydiff_config_t;
+
+/* Sizes (bytes) of the four device buffers the caller must provide for `cfg`.
+ * k_bytes == v_bytes: one K (or V) cache.  meta: token positions and status
+ * words (persistent state).  scratch: per-call temporaries (attention partials,
+ * anchor partial sums, scores, selection lists); its contents carry nothing
+ * between calls.  Host call, nothing is enqueued.                              */
+KEYDIFF_API int keydiff_workspace_bytes(const keydiff_config_t *cfg, size_t *k_bytes, size_t *v_bytes,
+                            size_t *meta_bytes, size_t *scratch_bytes);
+
+/* Create a handle over caller-owned device buffers of at least the sizes
+ * above (256-byte aligned).  The cache starts empty: C_0 = {} (Eq. 5).  Clears
+ * `meta` on `stream`.  *out receives the handle.                               */
+KEYDIFF_API int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache, void *meta,
+                       void *scratch, void *stream, keydiff_cache_t **out);
+
+/* One block step (Fig. 1 steps 2-4 after the append of Eq. 5).
+ *   Bt      rows in this block, 1 <= Bt <= block_B
+ *   pos0    prompt position of the block's first token; row j gets pos0 + j
+ *   out     attention output of the block, computed BEFORE eviction
+ *   scores_out  nullable; float [batch][n_kv_heads][len + Bt]: the score of every
+ *           row of the intermediate cache in row order before eviction
+ *           (cached rows, then the block)
+ * With len the rows cached before the call and n = len + Bt: if n <= N the block
+ * is only appended; otherwise exactly n - N rows per (sequence, KV head) are
+ * evicted and the cache length becomes N.                                      */
+KEYDIFF_API int keydiff_prefill_block(keydiff_cache_t *cache, const void *q, const void *k_new,
+                          const void *v_new, int32_t Bt, int64_t pos0, void *out,
+                          float *scores_out, void *stream);
+
+/* Generation phase: the block step with B = 1 (Background, block prompt
+ * processing).  q [batch][n_q_heads][1][head_dim] and so on.                   */
+KEYDIFF_API int keydiff_decode_step(keydiff_cache_t *cache, const void *q, const void *k_new,
+                        const void *v_new, int64_t pos, void *out, void *stream);
+
+/* KeyDiff scores of the rows currently cached, no mutation:
+ * scores_out float [batch][n_kv_heads][len], row order of the cache.
+ * ESTATE if the cache is empty.                                                */
+KEYDIFF_API int keydiff_scores(const keydiff_cache_t *cache, float *scores_out, void *stream);
+
+/* Rows currently cached per (sequence, KV head); host value, no sync. */
+KEYDIFF_API int keydiff_cache_len(const keydiff_cache_t *cache, int32_t *len);
+
+/* Token position of every cached row: pos_out int32 [batch][n_kv_heads][len] (device). */
+KEYDIFF_API int keydiff_cache_positions(const keydiff_cache_t *cache, int32_t *pos_out, void *stream);
+
+/* Replace the cache contents (resume / teacher forcing): k, v device
+ * [batch][n_kv_heads][len][head_dim] bf16, pos device int32 [batch][n_kv_heads][len],
+ * 0 <= len <= budget_N.  Positions must be unique per head (ascending if the
+ * layout is ORDERED).                                                           */
+KEYDIFF_API int keydiff_cache_load(keydiff_cache_t *cache, const void *k, const void *v, const int32_t *pos,
+                       int32_t len, void *stream);
+
+/* Device-side consistency word: synchronises `stream`, then *status_out (host)
+ * is 0 unless a kernel met an impossible state (for instance a selection whose
+ * evicted count differs from n - N, or an expired bounded wait).               */
+KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *status_out, void *stream);
+
+/* Per-kernel timing with HIP events recorded on the stream the kernels run on.
+ * enable != 0 starts recording around every kernel this handle launches;
+ * keydiff_profile_read synchronises, writes the summed milliseconds and launch
+ * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
+enum {
+    KEYDIFF_K_APPEND = 0,
+    KEYDIFF_K_ATTENTION = 1,
+    KEYDIFF_K_MERGE = 2,
+    KEYDIFF_K_ANCHOR = 3,
+    KEYDIFF_K_SCORE = 4,
+    KEYDIFF_K_SELECT = 5,
+    KEYDIFF_K_COMPACT = 6,
+    KEYDIFF_NKERNELS = 7
+};
+KEYDIFF_API int keydiff_profile_enable(keydiff_cache_t *cache, int32_t enable);
+KEYDIFF_API int keydiff_profile_read(keydiff_cache_t *cache, float *ms_out, int32_t *launches_out);
+
+KEYDIFF_API void keydiff_destroy_cache(keydiff_cache_t *cache);
+
+/* Message of the calling thread's last failed call ("" if none). */
+KEYDIFF_API const char *keydiff_last_error(void);
+
+KEYDIFF_API int keydiff_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KEYDIFF_H */

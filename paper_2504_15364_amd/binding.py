@@ -1,0 +1,216 @@
+"""ctypes binding of include/keydiff.h -- argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch appears only
+as the owner of device memory and streams.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkeydiff.so")
+
+OK, EINVAL, ESHAPE, ESTATE, EHIP = 0, -1, -2, -3, -4
+ANCHOR_MEAN_KEY, ANCHOR_MEAN_UNIT_KEY = 0, 1
+LAYOUT_ORDERED, LAYOUT_FILL = 0, 1
+KERNEL_NAMES = ("append", "attention", "merge", "anchor", "score", "select", "compact")
+
+EXPORTS = (
+    "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_decode_step",
+    "keydiff_scores", "keydiff_cache_len", "keydiff_cache_positions", "keydiff_cache_load",
+    "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
+    "keydiff_last_error", "keydiff_version",
+)
+
+
+class KeyDiffError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"keydiff error {code}: {message}")
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "budget_N", "block_B",
+                                         "anchor_mode", "window_W", "layout")] + \
+               [("eps", C.c_float), ("softmax_scale", C.c_float)]
+
+
+@dataclass
+class KeyDiffConfig:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    budget_N: int
+    block_B: int
+    anchor_mode: int = ANCHOR_MEAN_KEY
+    window_W: int = 0
+    layout: int = LAYOUT_ORDERED
+    eps: float = 0.0
+    softmax_scale: float = 0.0
+
+    def _c(self) -> _Config:
+        return _Config(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.budget_N, self.block_B,
+                       self.anchor_mode, self.window_W, self.layout, self.eps, self.softmax_scale)
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libkeydiff.so; there is no fallback if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_15364_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    szp = C.POINTER(C.c_size_t)
+    L.keydiff_workspace_bytes.argtypes = [C.POINTER(_Config), szp, szp, szp, szp]
+    L.keydiff_init_cache.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, C.POINTER(vp)]
+    L.keydiff_prefill_block.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    L.keydiff_decode_step.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+    L.keydiff_scores.argtypes = [vp, vp, vp]
+    L.keydiff_cache_len.argtypes = [vp, C.POINTER(i32)]
+    L.keydiff_cache_positions.argtypes = [vp, vp, vp]
+    L.keydiff_cache_load.argtypes = [vp, vp, vp, vp, i32, vp]
+    L.keydiff_cache_status.argtypes = [vp, C.POINTER(i32), vp]
+    L.keydiff_profile_enable.argtypes = [vp, i32]
+    L.keydiff_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
+    L.keydiff_destroy_cache.argtypes = [vp]
+    L.keydiff_destroy_cache.restype = None
+    L.keydiff_last_error.argtypes = []
+    L.keydiff_last_error.restype = C.c_char_p
+    L.keydiff_version.argtypes = []
+    for name in EXPORTS:
+        if name not in ("keydiff_destroy_cache", "keydiff_last_error"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise KeyDiffError(rc, load_library().keydiff_last_error().decode())
+
+
+def workspace_bytes(cfg: KeyDiffConfig):
+    k, v, m, s = (C.c_size_t() for _ in range(4))
+    c = cfg._c()
+    _check(load_library().keydiff_workspace_bytes(C.byref(c), C.byref(k), C.byref(v), C.byref(m), C.byref(s)))
+    return k.value, v.value, m.value, s.value
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+class KeyDiffCache:
+    """keydiff_cache_t over torch-owned device buffers.  Method names follow the C ABI."""
+
+    def __init__(self, cfg: KeyDiffConfig, device="cuda:0", stream=None):
+        import torch
+        self._L = load_library()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        kb, vb, mb, sb = workspace_bytes(cfg)
+        # the library never allocates device memory: torch owns these four buffers
+        self._k = torch.empty(kb, dtype=torch.uint8, device=self.device)
+        self._v = torch.empty(vb, dtype=torch.uint8, device=self.device)
+        self._meta = torch.empty(mb, dtype=torch.uint8, device=self.device)
+        self._scratch = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        c = cfg._c()
+        with torch.cuda.device(self.device):
+            _check(self._L.keydiff_init_cache(C.byref(c), self._k.data_ptr(), self._v.data_ptr(),
+                                              self._meta.data_ptr(), self._scratch.data_ptr(),
+                                              _stream_ptr(stream), C.byref(self._h)))
+        self.cap = cfg.budget_N + cfg.block_B
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.keydiff_destroy_cache(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # -- the calls of the C ABI ------------------------------------------------
+    def prefill_block(self, q, k_new, v_new, pos0: int, out=None, scores_out=None, stream=None):
+        """q [batch][Hq][Bt][d], k_new/v_new [batch][Hkv][Bt][d] bf16 device tensors."""
+        import torch
+        Bt = k_new.shape[-2]
+        for t in (q, k_new, v_new):
+            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
+        if out is None:
+            out = torch.empty_like(q)
+        _check(self._L.keydiff_prefill_block(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
+                                             int(pos0), out.data_ptr(),
+                                             scores_out.data_ptr() if scores_out is not None else None,
+                                             _stream_ptr(stream)))
+        return out
+
+    def decode_step(self, q, k_new, v_new, pos: int, out=None, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty_like(q)
+        _check(self._L.keydiff_decode_step(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), int(pos),
+                                           out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def scores(self, stream=None):
+        import torch
+        out = torch.empty((self.cfg.batch, self.cfg.n_kv_heads, self.len), dtype=torch.float32, device=self.device)
+        _check(self._L.keydiff_scores(self._h, out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    @property
+    def len(self) -> int:
+        n = C.c_int32()
+        _check(self._L.keydiff_cache_len(self._h, C.byref(n)))
+        return n.value
+
+    def positions(self, stream=None):
+        import torch
+        out = torch.empty((self.cfg.batch, self.cfg.n_kv_heads, self.len), dtype=torch.int32, device=self.device)
+        if self.len:
+            _check(self._L.keydiff_cache_positions(self._h, out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def load(self, k, v, pos, stream=None):
+        ln = k.shape[2]
+        _check(self._L.keydiff_cache_load(self._h, k.data_ptr(), v.data_ptr(), pos.data_ptr(), ln,
+                                          _stream_ptr(stream)))
+
+    def status(self, stream=None) -> int:
+        s = C.c_int32()
+        _check(self._L.keydiff_cache_status(self._h, C.byref(s), _stream_ptr(stream)))
+        return s.value
+
+    def profile_enable(self, on: bool):
+        _check(self._L.keydiff_profile_enable(self._h, int(on)))
+
+    def profile_read(self):
+        ms = (C.c_float * len(KERNEL_NAMES))()
+        cnt = (C.c_int32 * len(KERNEL_NAMES))()
+        _check(self._L.keydiff_profile_read(self._h, ms, cnt))
+        return {n: (ms[i], cnt[i]) for i, n in enumerate(KERNEL_NAMES)}
+
+    # -- views of the caller-owned buffers (tests, not the hot path) -------------
+    def key_rows(self):
+        """Cache keys as a [batch][Hkv][cap][d] bf16 view (rows >= len are stale)."""
+        import torch
+        c = self.cfg
+        n = c.batch * c.n_kv_heads * self.cap * c.head_dim
+        return self._k[:n * 2].view(torch.bfloat16).view(c.batch, c.n_kv_heads, self.cap, c.head_dim)
+
+    def value_rows(self):
+        import torch
+        c = self.cfg
+        n = c.batch * c.n_kv_heads * self.cap * c.head_dim
+        return self._v[:n * 2].view(torch.bfloat16).view(c.batch, c.n_kv_heads, self.cap, c.head_dim)

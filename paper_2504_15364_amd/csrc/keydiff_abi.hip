@@ -1,0 +1,449 @@
+// Host side of the C ABI declared in include/keydiff.h: argument validation,
+// the Eq. 5 state machine (len, positions) and the per-step kernel sequence.
+#include "../../include/keydiff.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kd_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t k_bytes, meta_bytes, scratch_bytes;
+    size_t off_pos, off_status;                                              // in meta
+    size_t off_part_o, off_part_ml, off_anchor, off_scores, off_dstmap;      // in scratch
+    int cap, max_chunks, max_part_rows;
+};
+
+constexpr int kTargetWorkgroups = 512;
+
+int check_config(const keydiff_config_t *c)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "config is null");
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->budget_N < 1 || c->block_B < 1)
+        return fail(KEYDIFF_ESHAPE, "batch, head counts, budget_N and block_B must be positive");
+    if (c->n_q_heads % c->n_kv_heads) return fail(KEYDIFF_ESHAPE, "n_q_heads must be a multiple of n_kv_heads");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(KEYDIFF_ESHAPE, "head_dim must be 64 or 128");
+    if ((long)c->budget_N + c->block_B > 32768) return fail(KEYDIFF_ESHAPE, "budget_N + block_B must not exceed 32768");
+    if (c->block_B > 16384) return fail(KEYDIFF_ESHAPE, "block_B must not exceed 16384");
+    if ((long)c->batch * c->n_kv_heads > 65535) return fail(KEYDIFF_ESHAPE, "batch * n_kv_heads must not exceed 65535");
+    if (c->anchor_mode != KEYDIFF_ANCHOR_MEAN_KEY && c->anchor_mode != KEYDIFF_ANCHOR_MEAN_UNIT_KEY)
+        return fail(KEYDIFF_EINVAL, "anchor_mode must be a KEYDIFF_ANCHOR_* value");
+    if (c->layout != KEYDIFF_LAYOUT_ORDERED && c->layout != KEYDIFF_LAYOUT_FILL)
+        return fail(KEYDIFF_EINVAL, "layout must be a KEYDIFF_LAYOUT_* value");
+    if (c->window_W < 0 || c->window_W >= c->budget_N)
+        return fail(KEYDIFF_ESHAPE, "window_W must lie in [0, budget_N)");
+    return KEYDIFF_OK;
+}
+
+Layout make_layout(const keydiff_config_t *c)
+{
+    Layout L{};
+    const size_t BH = (size_t)c->batch * c->n_kv_heads;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    const int D = c->head_dim;
+    L.cap = c->budget_N + c->block_B;
+    L.k_bytes = align256(BH * L.cap * D * 2);
+    L.off_pos = 0;
+    L.off_status = align256(BH * L.cap * 4);
+    L.meta_bytes = L.off_status + 256;
+    L.max_chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
+    // split-KV partial rows: splits * BH * G * Bt never exceeds this (see pick_splits)
+    const int max_mtiles = (G * c->block_B + 127) / 128;
+    const size_t by_tiles = (kTargetWorkgroups + BH * max_mtiles + BH) * 256;
+    const size_t by_rows = (kTargetWorkgroups + 2 * BH) * (size_t)G * c->block_B;
+    L.max_part_rows = (int)(by_tiles < by_rows ? by_tiles : by_rows);
+    size_t off = 0;
+    L.off_part_o = off;   off += align256((size_t)L.max_part_rows * D * 4);
+    L.off_part_ml = off;  off += align256((size_t)L.max_part_rows * 8);
+    L.off_anchor = off;   off += align256(BH * L.max_chunks * D * 8);
+    L.off_scores = off;   off += align256(BH * L.cap * 4);
+    L.off_dstmap = off;   off += align256(BH * L.cap * 4);
+    L.scratch_bytes = off;
+    return L;
+}
+
+struct ProfEvent {
+    int kind;
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct keydiff_cache {
+    keydiff_config_t cfg;
+    Layout L;
+    uint16_t *k, *v;
+    unsigned char *meta, *scratch;
+    int len;
+    double eps;
+    float scale_log2e;
+    bool contiguous;      // every block so far started where the previous one ended
+    int64_t next_pos;
+    bool profiling;
+    std::vector<ProfEvent> events;
+    std::vector<hipEvent_t> pool;
+};
+
+namespace {
+
+struct ProfScope {
+    keydiff_cache *c;
+    hipStream_t s;
+    ProfEvent ev;
+    bool on;
+    ProfScope(keydiff_cache *c_, int kind, hipStream_t s_) : c(c_), s(s_), on(c_->profiling)
+    {
+        if (!on) return;
+        ev.kind = kind;
+        for (hipEvent_t *e : {&ev.a, &ev.b}) {
+            if (!c->pool.empty()) {
+                *e = c->pool.back();
+                c->pool.pop_back();
+            } else if (hipEventCreate(e) != hipSuccess) {
+                on = false;
+                return;
+            }
+        }
+        (void)hipEventRecord(ev.a, s);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(ev.b, s);
+        c->events.push_back(ev);
+    }
+};
+
+struct AttnPlan {
+    int NQ, mtiles, ntiles, splits;
+};
+
+AttnPlan plan_attention(const keydiff_cache *c, int Bt, int n)
+{
+    AttnPlan a;
+    const int BH = c->cfg.batch * c->cfg.n_kv_heads;
+    const int G = c->cfg.n_q_heads / c->cfg.n_kv_heads;
+    const int Mtot = G * Bt;
+    a.NQ = (Mtot % 256 == 0 || Mtot >= 512) ? 2 : 1;
+    const int TM = 128 * a.NQ;
+    a.mtiles = (Mtot + TM - 1) / TM;
+    a.ntiles = (n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
+    const int target = a.NQ == 2 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+    int splits = (target + BH * a.mtiles - 1) / (BH * a.mtiles);
+    if (splits > a.ntiles) splits = a.ntiles;
+    if (splits < 1) splits = 1;
+    // partial rows must fit the scratch sized at init
+    while (splits > 1 && (long)splits * BH * Mtot > c->L.max_part_rows) --splits;
+    a.splits = splits;
+    return a;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(KEYDIFF_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define KD_LAUNCH(expr, what)                                  \
+    do {                                                       \
+        hipError_t e__ = (expr);                               \
+        if (e__ != hipSuccess) return hip_fail(e__, what);     \
+    } while (0)
+
+kd::EvictParams evict_params(const keydiff_cache *c, int n)
+{
+    kd::EvictParams p{};
+    p.k = c->k;
+    p.v = c->v;
+    p.pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
+    p.anchor_part = reinterpret_cast<double *>(c->scratch + c->L.off_anchor);
+    p.scores = reinterpret_cast<float *>(c->scratch + c->L.off_scores);
+    p.dstmap = reinterpret_cast<int32_t *>(c->scratch + c->L.off_dstmap);
+    p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
+    p.BH = c->cfg.batch * c->cfg.n_kv_heads;
+    p.cap = c->L.cap;
+    p.D = c->cfg.head_dim;
+    p.n = n;
+    p.N = c->cfg.budget_N;
+    p.nchunks = (n + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
+    p.anchor_mode = c->cfg.anchor_mode;
+    p.layout = c->cfg.layout;
+    p.window_W = c->cfg.window_W;
+    p.window_pos_min = 0;
+    p.eps = c->eps;
+    return p;
+}
+
+int score_rows(keydiff_cache *c, int n, hipStream_t s)
+{
+    kd::EvictParams p = evict_params(c, n);
+    {
+        ProfScope ps(c, KEYDIFF_K_ANCHOR, s);
+        KD_LAUNCH(kd::launch_anchor(p, s), "anchor kernel");
+    }
+    {
+        ProfScope ps(c, KEYDIFF_K_SCORE, s);
+        KD_LAUNCH(kd::launch_score(p, s), "score kernel");
+    }
+    return KEYDIFF_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int keydiff_version(void) { return KEYDIFF_VERSION; }
+
+const char *keydiff_last_error(void) { return g_err; }
+
+int keydiff_workspace_bytes(const keydiff_config_t *cfg, size_t *k_bytes, size_t *v_bytes, size_t *meta_bytes,
+                            size_t *scratch_bytes)
+{
+    if (int rc = check_config(cfg)) return rc;
+    if (!k_bytes || !v_bytes || !meta_bytes || !scratch_bytes) return fail(KEYDIFF_EINVAL, "null output pointer");
+    const Layout L = make_layout(cfg);
+    *k_bytes = L.k_bytes;
+    *v_bytes = L.k_bytes;
+    *meta_bytes = L.meta_bytes;
+    *scratch_bytes = L.scratch_bytes;
+    return KEYDIFF_OK;
+}
+
+int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache, void *meta, void *scratch,
+                       void *stream, keydiff_cache_t **out)
+{
+    if (int rc = check_config(cfg)) return rc;
+    if (!k_cache || !v_cache || !meta || !scratch || !out) return fail(KEYDIFF_EINVAL, "null pointer");
+    for (const void *p : {k_cache, v_cache, meta, scratch})
+        if (reinterpret_cast<uintptr_t>(p) & 255) return fail(KEYDIFF_EINVAL, "buffers must be 256-byte aligned");
+    keydiff_cache *c = new (std::nothrow) keydiff_cache();
+    if (!c) return fail(KEYDIFF_EINVAL, "out of host memory");
+    c->cfg = *cfg;
+    c->L = make_layout(cfg);
+    c->k = static_cast<uint16_t *>(k_cache);
+    c->v = static_cast<uint16_t *>(v_cache);
+    c->meta = static_cast<unsigned char *>(meta);
+    c->scratch = static_cast<unsigned char *>(scratch);
+    c->len = 0;  // C_0 is empty
+    c->eps = cfg->eps > 0.f ? (double)cfg->eps : 1e-8;
+    const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
+    c->scale_log2e = (float)(scale * 1.4426950408889634);
+    c->contiguous = true;
+    c->next_pos = -1;
+    c->profiling = false;
+    hipError_t e = kd::launch_zero_words(reinterpret_cast<int32_t *>(meta), c->L.meta_bytes / 4,
+                                         static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        delete c;
+        return hip_fail(e, "clearing metadata");
+    }
+    *out = c;
+    return KEYDIFF_OK;
+}
+
+void keydiff_destroy_cache(keydiff_cache_t *c)
+{
+    if (!c) return;
+    for (auto &ev : c->events) {
+        (void)hipEventDestroy(ev.a);
+        (void)hipEventDestroy(ev.b);
+    }
+    for (auto &e : c->pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+int keydiff_cache_len(const keydiff_cache_t *c, int32_t *len)
+{
+    if (!c || !len) return fail(KEYDIFF_EINVAL, "null pointer");
+    *len = c->len;
+    return KEYDIFF_OK;
+}
+
+int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
+                          int64_t pos0, void *out, float *scores_out, void *stream)
+{
+    if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
+        return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
+    if (Bt < 1 || Bt > c->cfg.block_B) return fail(KEYDIFF_ESHAPE, "Bt must lie in [1, block_B], got %d", Bt);
+    if (pos0 < 0 || pos0 + Bt > 0x7fffffffLL) return fail(KEYDIFF_ESHAPE, "positions must fit in int32");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const keydiff_config_t &cf = c->cfg;
+    const int BH = cf.batch * cf.n_kv_heads, D = cf.head_dim;
+    const int len = c->len, n = len + Bt, N = cf.budget_N;
+    const bool contiguous = c->contiguous && (c->next_pos < 0 || c->next_pos == pos0);
+    if (cf.window_W > 0 && n > N && !contiguous)
+        return fail(KEYDIFF_ESTATE, "the sliding window needs consecutive token positions across calls");
+
+    int32_t *pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
+    {
+        ProfScope ps(c, KEYDIFF_K_APPEND, s);
+        KD_LAUNCH(kd::launch_append(static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), c->k,
+                                    c->v, pos, BH, c->L.cap, D, len, Bt, (int32_t)pos0, s),
+                  "append kernel");
+    }
+
+    const AttnPlan plan = plan_attention(c, Bt, n);
+    kd::AttnParams ap{};
+    ap.q = static_cast<const uint16_t *>(q);
+    ap.k = c->k;
+    ap.v = c->v;
+    ap.out = static_cast<uint16_t *>(out);
+    ap.part_o = reinterpret_cast<float *>(c->scratch + c->L.off_part_o);
+    ap.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
+    ap.batch = cf.batch;
+    ap.hq = cf.n_q_heads;
+    ap.hkv = cf.n_kv_heads;
+    ap.G = cf.n_q_heads / cf.n_kv_heads;
+    ap.Bt = Bt;
+    ap.len = len;
+    ap.n = n;
+    ap.cap = c->L.cap;
+    ap.splits = plan.splits;
+    ap.mtiles = plan.mtiles;
+    ap.ntiles = plan.ntiles;
+    ap.scale_log2e = c->scale_log2e;
+    {
+        ProfScope ps(c, KEYDIFF_K_ATTENTION, s);
+        KD_LAUNCH(kd::launch_attention(ap, D, plan.NQ, s), "attention kernel");
+    }
+    if (plan.splits > 1) {
+        ProfScope ps(c, KEYDIFF_K_MERGE, s);
+        KD_LAUNCH(kd::launch_merge(ap, D, s), "merge kernel");
+    }
+
+    const bool evict = n > N;
+    if (evict || scores_out) {
+        if (int rc = score_rows(c, n, s)) return rc;
+        if (scores_out)
+            KD_LAUNCH(kd::launch_copy_scores(reinterpret_cast<const float *>(c->scratch + c->L.off_scores), scores_out,
+                                             BH, c->L.cap, n, s),
+                      "score copy");
+    }
+    if (evict) {
+        kd::EvictParams p = evict_params(c, n);
+        if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
+        {
+            ProfScope ps(c, KEYDIFF_K_SELECT, s);
+            KD_LAUNCH(kd::launch_select(p, s), "select kernel");
+        }
+        if (cf.layout == KEYDIFF_LAYOUT_ORDERED) {
+            ProfScope ps(c, KEYDIFF_K_COMPACT, s);
+            KD_LAUNCH(kd::launch_compact_ordered(p, s), "compaction kernel");
+        }
+    }
+    c->len = evict ? N : n;
+    c->contiguous = contiguous;
+    c->next_pos = pos0 + Bt;
+    return KEYDIFF_OK;
+}
+
+int keydiff_decode_step(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int64_t pos,
+                        void *out, void *stream)
+{
+    return keydiff_prefill_block(c, q, k_new, v_new, 1, pos, out, nullptr, stream);
+}
+
+int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
+{
+    if (!cc || !scores_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (cc->len == 0) return fail(KEYDIFF_ESTATE, "the cache is empty");
+    keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch and profiling events only
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (int rc = score_rows(c, c->len, s)) return rc;
+    KD_LAUNCH(kd::launch_copy_scores(reinterpret_cast<const float *>(c->scratch + c->L.off_scores), scores_out,
+                                     c->cfg.batch * c->cfg.n_kv_heads, c->L.cap, c->len, s),
+              "score copy");
+    return KEYDIFF_OK;
+}
+
+int keydiff_cache_positions(const keydiff_cache_t *c, int32_t *pos_out, void *stream)
+{
+    if (!c || !pos_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    KD_LAUNCH(kd::launch_load_pos(reinterpret_cast<const int32_t *>(c->meta + c->L.off_pos), pos_out,
+                                  c->cfg.batch * c->cfg.n_kv_heads, c->L.cap, c->len, 0,
+                                  static_cast<hipStream_t>(stream)),
+              "position copy");
+    return KEYDIFF_OK;
+}
+
+int keydiff_cache_load(keydiff_cache_t *c, const void *k, const void *v, const int32_t *pos, int32_t len,
+                       void *stream)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (len < 0 || len > c->cfg.budget_N) return fail(KEYDIFF_ESHAPE, "len must lie in [0, budget_N]");
+    if (len > 0 && (!k || !v || !pos)) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (len > 0 && (misaligned(k) || misaligned(v))) return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int BH = c->cfg.batch * c->cfg.n_kv_heads, D = c->cfg.head_dim;
+    KD_LAUNCH(kd::launch_load_rows(static_cast<const uint16_t *>(k), c->k, BH, c->L.cap, D, len, s), "cache load");
+    KD_LAUNCH(kd::launch_load_rows(static_cast<const uint16_t *>(v), c->v, BH, c->L.cap, D, len, s), "cache load");
+    KD_LAUNCH(kd::launch_load_pos(pos, reinterpret_cast<int32_t *>(c->meta + c->L.off_pos), BH, c->L.cap, len, 1, s),
+              "cache load");
+    c->len = len;
+    c->contiguous = false;  // the loaded positions are the caller's
+    c->next_pos = -1;
+    return KEYDIFF_OK;
+}
+
+int keydiff_cache_status(const keydiff_cache_t *c, int32_t *status_out, void *stream)
+{
+    if (!c || !status_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(status_out, c->meta + c->L.off_status, 4, hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "status copy");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "stream synchronize");
+    return KEYDIFF_OK;
+}
+
+int keydiff_profile_enable(keydiff_cache_t *c, int32_t enable)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    c->profiling = enable != 0;
+    return KEYDIFF_OK;
+}
+
+int keydiff_profile_read(keydiff_cache_t *c, float *ms_out, int32_t *launches_out)
+{
+    if (!c || !ms_out || !launches_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    for (int i = 0; i < KEYDIFF_NKERNELS; ++i) {
+        ms_out[i] = 0.f;
+        launches_out[i] = 0;
+    }
+    for (auto &ev : c->events) {
+        hipError_t e = hipEventSynchronize(ev.b);
+        if (e != hipSuccess) return hip_fail(e, "event synchronize");
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        if (e != hipSuccess) return hip_fail(e, "event elapsed time");
+        ms_out[ev.kind] += ms;
+        launches_out[ev.kind] += 1;
+        c->pool.push_back(ev.a);
+        c->pool.push_back(ev.b);
+    }
+    c->events.clear();
+    return KEYDIFF_OK;
+}
+
+}  // extern "C"

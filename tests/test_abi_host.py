@@ -1,0 +1,45 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and validates configurations."""
+import os
+import re
+
+import pytest
+
+from paper_2504_15364_amd import binding as kd
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "keydiff.h")
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kd.load_library()
+    text = open(HEADER).read()
+    declared = set(re.findall(r"KEYDIFF_API[^;(]*?\b(keydiff_\w+)\s*\(", text))
+    assert declared == set(kd.EXPORTS) and len(declared) >= 10
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.keydiff_version() == 1
+
+
+def test_workspace_sizes():
+    cfg = kd.KeyDiffConfig(1, 32, 8, 128, 8192, 128)
+    k, v, meta, scratch = kd.workspace_bytes(cfg)
+    assert k == v == 8 * (8192 + 128) * 128 * 2
+    assert meta >= 8 * (8192 + 128) * 4
+    assert scratch > 8 * (8192 + 128) * 4
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_q_heads=5), kd.ESHAPE),            # not a multiple of the KV heads
+    (dict(head_dim=96), kd.ESHAPE),
+    (dict(budget_N=0), kd.ESHAPE),
+    (dict(budget_N=40000), kd.ESHAPE),
+    (dict(anchor_mode=7), kd.EINVAL),
+    (dict(layout=9), kd.EINVAL),
+    (dict(window_W=256), kd.ESHAPE),           # the window must leave room in the budget
+])
+def test_bad_configs_are_rejected_with_a_message(kw, code):
+    base = dict(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, budget_N=256, block_B=32)
+    base.update(kw)
+    with pytest.raises(kd.KeyDiffError) as e:
+        kd.workspace_bytes(kd.KeyDiffConfig(**base))
+    assert e.value.code == code and len(str(e.value)) > 20

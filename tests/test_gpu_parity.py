@@ -1,0 +1,192 @@
+"""HIP path vs oracle, element by element, through the C ABI (needs an MI355X).
+
+Bars: attention within 2e-2 absolute (bf16 I/O, fp32 softmax against the fp64
+oracle); scores within 1e-5 relative; retained position sets and the K/V row
+behind every retained position bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2504_15364_amd as kd
+from helpers import (ATTN_ATOL, SCORE_ATOL, SCORE_RTOL, bf16_out_to_f32, blocks, rows_by_position, to_dev)
+from synth import f32_to_bf16_bits, get_config, make_layer
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def make_pair(w, N, B, batch=1, **kw):
+    cfg = kd.KeyDiffConfig(batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, **kw)
+    okw = {k: v for k, v in kw.items() if k != "layout"}
+    return kd.KeyDiffCache(cfg), oracle.OracleCache(batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, **okw)
+
+
+def check_state(cache, oc, where):
+    pos, K, V = rows_by_position(cache)
+    assert cache.len == oc.len, where
+    assert np.array_equal(pos, oc.positions()), f"retained positions differ {where}"
+    assert np.array_equal(K, oc.keys()), f"K rows differ {where}"
+    assert np.array_equal(V, oc.values()), f"V rows differ {where}"
+    if cache.cfg.layout == kd.LAYOUT_ORDERED:
+        raw = cache.positions().cpu().numpy()
+        assert np.all(np.diff(raw, axis=-1) > 0), f"ORDERED layout not ascending {where}"
+
+
+def run_prompt(w, data, N, B, T=None, check_scores=True, **kw):
+    cache, oc = make_pair(w, N, B, **kw)
+    worst = 0.0
+    for t, Bt, q, k, v in blocks(data, B, T):
+        n = cache.len + Bt
+        pos_before = np.concatenate(
+            [cache.positions().cpu().numpy(), np.broadcast_to(np.arange(t, t + Bt, dtype=np.int32), (1, w.n_kv_heads, Bt))],
+            axis=-1)
+        sc = torch.empty((1, w.n_kv_heads, n), dtype=torch.float32, device="cuda") if check_scores else None
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t, scores_out=sc)
+        ref, osc, ev = oc.prefill_block(q, k, v, t, want_scores=True)
+        err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+        worst = max(worst, err)
+        assert err <= ATTN_ATOL, f"attention error {err} in block at token {t}"
+        if check_scores and ev > 0:
+            # the oracle lists rows by ascending position; map the HIP row order onto it
+            order = np.argsort(pos_before, axis=-1, kind="stable")
+            got = np.take_along_axis(sc.cpu().numpy(), order, axis=-1)
+            assert np.allclose(got, osc, rtol=SCORE_RTOL, atol=SCORE_ATOL), f"scores differ at token {t}"
+        check_state(cache, oc, f"after the block at token {t}")
+    assert cache.status() == 0
+    cache.close()
+    return worst
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+def test_toy_config_whole_prompt(layout):
+    w = get_config("toy")
+    data = make_layer(w, seed=1)
+    run_prompt(w, data, w.budget_N, w.block_B, layout=layout)
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+@pytest.mark.parametrize("hq,hkv,d,N,B,T", [
+    (6, 2, 128, 200, 48, 500),     # G = 3, tiles ragged in keys and rows, ragged last block
+    (8, 2, 64, 130, 100, 650),     # first eviction evicts fewer rows than the block holds
+    (14, 2, 128, 320, 64, 448),    # G = 7 (Qwen-style group)
+    (4, 4, 128, 70, 7, 120),       # tiny blocks, budget below one key tile
+])
+def test_ragged_shapes(layout, hq, hkv, d, N, B, T):
+    w = get_config("llama32_3b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
+    data = make_layer(w, seed=100 + hq + N)
+    run_prompt(w, data, N, B, layout=layout)
+
+
+def test_two_query_sets_per_wave_and_split_merge():
+    # G * B = 512 rows per KV head takes the 64-rows-per-wave kernel and several key splits
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1536)
+    data = make_layer(w, seed=5)
+    run_prompt(w, data, 768, 128, layout=kd.LAYOUT_FILL)
+
+
+def test_budget_not_reached_only_appends():
+    w = get_config("toy").small(prompt_T=96)
+    data = make_layer(w, seed=2)
+    cache, oc = make_pair(w, 128, 32)
+    for t, Bt, q, k, v in blocks(data, 32):
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.prefill_block(q, k, v, t)
+        assert ev == 0 and np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
+    assert cache.len == 96
+    check_state(cache, oc, "no eviction")
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+def test_decode_steps_batch(layout):
+    # B = 1 is the generation phase: several independent sequences, one eviction per step
+    w = get_config("decode_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=200, batch=3)
+    N = 150
+    seqs = [make_layer(w, seed=9, seq=s) for s in range(w.batch)]
+    cache, oc = make_pair(w, N, 1, batch=w.batch, layout=layout)
+    for t in range(w.prompt_T):
+        q, k, v = (np.stack([s[x][t][:, None, :] for s in seqs]) for x in ("q", "k", "v"))
+        out = cache.decode_step(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.decode_step(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
+        assert ev == (1 if t >= N else 0)
+        if t % 25 == 0 or t > 190:
+            check_state(cache, oc, f"decode step {t}")
+    check_state(cache, oc, "end of decode")
+    assert cache.status() == 0
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+def test_ties_keep_the_lower_position(layout):
+    # identical keys: every score is equal, so each step must evict the highest positions
+    hq, hkv, d, N, B = 2, 1, 64, 96, 32
+    w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=256)
+    data = make_layer(w, seed=3)
+    same = f32_to_bf16_bits(np.tile(np.linspace(-1, 2, d, dtype=np.float32), (256, hkv, 1)))
+    data = dict(data, k=same)
+    cache, oc = make_pair(w, N, B, layout=layout)
+    for t, Bt, q, k, v in blocks(data, B):
+        cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        oc.prefill_block(q, k, v, t)
+        check_state(cache, oc, f"ties, token {t}")
+    assert np.array_equal(np.sort(cache.positions().cpu().numpy())[0, 0], np.arange(N))
+
+
+def test_zero_key_and_tiny_keys_hit_the_eps_clamp():
+    hq, hkv, d, N, B = 2, 1, 64, 40, 16
+    w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=64)
+    data = make_layer(w, seed=4)
+    k = data["k"].copy()
+    k[5] = 0                                    # a zero key: score 0 by the clamp
+    k[9] = f32_to_bf16_bits(np.full((hkv, d), 2.0 ** -40, dtype=np.float32))
+    data = dict(data, k=k)
+    run_prompt(w, data, N, B, layout=kd.LAYOUT_FILL)
+
+
+def test_scores_entry_point_matches_oracle_and_leaves_the_cache_alone():
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, prompt_T=300)
+    data = make_layer(w, seed=6)
+    cache, oc = make_pair(w, 256, 50, layout=kd.LAYOUT_FILL)
+    for t, Bt, q, k, v in blocks(data, 50):
+        cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        oc.prefill_block(q, k, v, t)
+    before = rows_by_position(cache)
+    got = cache.scores().cpu().numpy()
+    order = np.argsort(cache.positions().cpu().numpy(), axis=-1, kind="stable")
+    assert np.allclose(np.take_along_axis(got, order, -1), oc.scores(), rtol=SCORE_RTOL, atol=SCORE_ATOL)
+    after = rows_by_position(cache)
+    assert all(np.array_equal(a, b) for a, b in zip(before, after))
+
+
+def test_cache_load_resumes_from_an_oracle_state():
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, prompt_T=400)
+    data = make_layer(w, seed=8)
+    N, B = 192, 64
+    oc = oracle.OracleCache(1, 6, 2, 128, N, B)
+    it = list(blocks(data, B))
+    for t, Bt, q, k, v in it[:4]:
+        oc.prefill_block(q, k, v, t)
+    cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, 6, 2, 128, N, B, layout=kd.LAYOUT_ORDERED))
+    cache.load(to_dev(oc.keys()), to_dev(oc.values()), torch.from_numpy(oc.positions()).cuda())
+    check_state(cache, oc, "after load")
+    for t, Bt, q, k, v in it[4:]:
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, _ = oc.prefill_block(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
+        check_state(cache, oc, f"resumed, token {t}")
+
+
+def test_argument_errors_enqueue_nothing():
+    w = get_config("toy")
+    cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, 4, 1, 64, 64, 16))
+    q = torch.zeros((1, 4, 32, 64), dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros((1, 1, 32, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(kd.KeyDiffError) as e:
+        cache.prefill_block(q, kv, kv, 0)          # Bt = 32 > block_B = 16
+    assert e.value.code == kd.binding.ESHAPE and cache.len == 0
+    with pytest.raises(kd.KeyDiffError) as e:
+        cache.scores()                              # empty cache
+    assert e.value.code == kd.binding.ESTATE
+    lib = kd.load_library()
+    assert lib.keydiff_prefill_block(cache._h, None, None, None, 1, 0, None, None, None) == kd.binding.EINVAL
+    assert cache.len == 0 and cache.status() == 0
