@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the KeyDiff block-prefill step on one MI355X.
+
+One bench *step* = one steady-state block step (cache full at N, B new tokens:
+append, attention, anchor, score, select, compact) through every layer of the
+workload, each layer on its own cache with its own seeded data.  The metric is
+prompt tokens/s per layer: B / (time of one layer's block step).
+
+Prints ONE JSON line (see the keys below) and nothing else on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from synth import get_config, make_layer  # noqa: E402
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # dense bf16, MI355X
+PEAK_HBM_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def to_blocks(bits: np.ndarray, B: int):
+    """token-major [T][H][d] uint16 -> torch bf16 [T/B][1][H][B][d] on the GPU."""
+    import torch
+    T, H, d = bits.shape
+    t = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return t.view(T // B, B, H, d).permute(0, 2, 1, 3).contiguous().unsqueeze(1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="llama31_8b")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the workload's layer count")
+    ap.add_argument("--layout", choices=["fill", "ordered"], default="fill")
+    ap.add_argument("--profile-steps", type=int, default=8, help="extra steps timed per kernel with HIP events")
+    ap.add_argument("--seed", type=int, default=20250415)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    w = get_config(args.workload)
+    L = args.layers or w.n_layers
+    B, N, D, Hq, Hkv = w.block_B, w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads
+    fill_blocks = N // B
+    n_steps = args.warmup + args.steps + args.profile_steps
+    T_need = (fill_blocks + n_steps) * B
+    if T_need > w.prompt_T:
+        sys.exit(f"--warmup + --steps + --profile-steps = {n_steps} exceeds the {w.prompt_T // B - fill_blocks} "
+                 f"evicting steps of a {w.prompt_T}-token prompt")
+
+    # ---- seeded host data, one fresh seed per layer (threads: numpy releases the GIL)
+    t0 = time.time()
+    workers = min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(workers) as ex:
+        layers = list(ex.map(lambda l: make_layer(w, seed=args.seed + 100 * 3 + l, layer=l, t1=T_need), range(L)))
+    log(f"[bench] generated {L} layers x {T_need} tokens in {time.time() - t0:.1f}s")
+
+    import torch
+
+    import paper_2504_15364_amd as kd
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    layout = kd.LAYOUT_FILL if args.layout == "fill" else kd.LAYOUT_ORDERED
+    caches, dq, dk, dv, outs = [], [], [], [], []
+    for l in range(L):
+        caches.append(kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=layout)))
+        dq.append(to_blocks(layers[l]["q"], B))
+        dk.append(to_blocks(layers[l]["k"], B))
+        dv.append(to_blocks(layers[l]["v"], B))
+        outs.append(torch.empty_like(dq[l][0]))
+
+    def run_block(i):
+        for l in range(L):
+            caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
+
+    def load_first_N(cache, l):
+        # while n <= N nothing is evicted, so after the first N tokens the cache IS those tokens in
+        # order: load that state directly, so every attention launch of this process is a
+        # steady-state one (the rocprofv3 average and the live HIP-event average then cover the
+        # same launches)
+        k0 = dk[l][:fill_blocks, 0].permute(1, 0, 2, 3).reshape(1, Hkv, N, D).contiguous()
+        v0 = dv[l][:fill_blocks, 0].permute(1, 0, 2, 3).reshape(1, Hkv, N, D).contiguous()
+        p0 = torch.arange(N, dtype=torch.int32, device="cuda").repeat(1, Hkv, 1).contiguous()
+        cache.load(k0, v0, p0)
+
+    # ---- untimed: bring every cache to the budget, then warm up in steady state
+    for l in range(L):
+        load_first_N(caches[l], l)
+    torch.cuda.synchronize()
+    assert all(c.len == N for c in caches)
+    i = fill_blocks
+    for _ in range(args.warmup):
+        run_block(i)
+        i += 1
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        run_block(i)
+        i += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    us_per_layer_step = elapsed / (args.steps * L) * 1e6
+    tokens_per_s_per_layer = B / (elapsed / (args.steps * L))
+
+    # ---- per-kernel durations, HIP events recorded by the library on its launch stream
+    kernels = {}
+    if args.profile_steps > 0:
+        for c in caches:
+            c.profile_enable(True)
+        for _ in range(args.profile_steps):
+            run_block(i)
+            i += 1
+        torch.cuda.synchronize()
+        tot = {}
+        for c in caches:
+            for name, (ms, cnt) in c.profile_read().items():
+                a = tot.setdefault(name, [0.0, 0])
+                a[0] += ms
+                a[1] += cnt
+            c.profile_enable(False)
+        kernels = {k: {"avg_us": v[0] / v[1] * 1e3, "launches": v[1]} for k, v in tot.items() if v[1]}
+    assert all(c.status() == 0 for c in caches)
+
+    # algorithmic work of one steady-state block step of one layer
+    n = N + B
+    flops_attn = 4.0 * Hq * B * D * (N + B / 2.0)
+    bytes_step = (2 * Hkv * n * D * 2 + 2 * Hq * B * D * 2 + 2 * Hkv * B * D * 2 + Hkv * n * 4
+                  + 2 * 2 * Hkv * B * D * 2)        # K+V once, Q in/O out, new rows, scores, <= B moved rows r+w
+    roofline = None
+    if "attention" in kernels:
+        t_attn = kernels["attention"]["avg_us"] * 1e-6
+        achieved = flops_attn / t_attn / 1e12
+        roofline = {"bound": "mfma", "kernel": "attn_kernel", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                    "flops_per_launch": flops_attn, "avg_launch_us": kernels["attention"]["avg_us"]}
+    t_min = max(flops_attn / (PEAK_BF16_MFMA_TFLOPS * 1e12), bytes_step / (PEAK_HBM_GBPS * 1e9))
+    step_frac = t_min / (us_per_layer_step * 1e-6)
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from synth import bf16_bits_to_f32, block_of
+        data = layers[0]
+        oc = oracle.OracleCache(1, Hq, Hkv, D, N, B)
+        for b in range(fill_blocks):          # reach the steady state without attention (keys decide the trace)
+            oc.prefill_block(None, block_of(data["k"], b * B, B)[None], block_of(data["v"], b * B, B)[None], b * B)
+        tc, worst = 0.0, 0.0
+        ref_cache = kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=layout))
+        load_first_N(ref_cache, 0)
+        for s in range(args.cpu_steps):
+            b = fill_blocks + s
+            q, k, v = (block_of(data[x], b * B, B)[None] for x in ("q", "k", "v"))
+            t1 = time.perf_counter()
+            ref, _, _ = oc.prefill_block(q, k, v, b * B)
+            tc += time.perf_counter() - t1
+            got = ref_cache.prefill_block(dq[0][b], dk[0][b], dv[0][b], b * B)
+            got = bf16_bits_to_f32(got.view(torch.int16).cpu().numpy().view(np.uint16))
+            worst = max(worst, float(np.abs(got - ref).max()))
+            same = np.array_equal(np.sort(ref_cache.positions().cpu().numpy(), axis=-1), oc.positions())
+            assert same, "retained set differs from the oracle"
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": B * args.cpu_steps / tc, "unit": "tokens/s/layer", "cores": threads, "kind": "oracle",
+               "sample": f"{args.cpu_steps} steady-state block steps of layer 0 (fp64, OpenMP over heads x rows)",
+               "us_per_step": tc / args.cpu_steps * 1e6, "max_abs_attention_diff_vs_gpu": worst,
+               "retained_sets_identical": True}
+
+    print(json.dumps({
+        "metric": "prompt tokens/sec per layer (KeyDiff block prefill) at N=8K"
+                  if N == 8192 else f"prompt tokens/sec per layer (KeyDiff block prefill) at N={N}",
+        "value": tokens_per_s_per_layer, "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "budget_N": N,
+                   "block_B": B, "layers": L, "layout": args.layout, "tokens_per_step": B,
+                   "step": "one steady-state block step through every layer"},
+        "us_per_layer_step": us_per_layer_step,
+        "step_roofline": {"binding": "mfma" if flops_attn / 2.5e15 > bytes_step / 8e12 else "hbm",
+                          "t_min_us": t_min * 1e6, "frac": step_frac, "flops": flops_attn, "bytes": bytes_step},
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }))
+
+
+if __name__ == "__main__":
+    main()

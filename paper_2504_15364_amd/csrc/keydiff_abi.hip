@@ -366,8 +366,9 @@ int keydiff_decode_step(keydiff_cache_t *c, const void *q, const void *k_new, co
 
 int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
 {
-    if (!cc || !scores_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (!cc) return fail(KEYDIFF_EINVAL, "null pointer");
     if (cc->len == 0) return fail(KEYDIFF_ESTATE, "the cache is empty");
+    if (!scores_out) return fail(KEYDIFF_EINVAL, "null pointer");
     keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch and profiling events only
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (int rc = score_rows(c, c->len, s)) return rc;
