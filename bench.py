@@ -147,12 +147,13 @@ def main():
     bytes_step = (2 * Hkv * n * D * 2 + 2 * Hq * B * D * 2 + 2 * Hkv * B * D * 2 + Hkv * n * 4
                   + 2 * 2 * Hkv * B * D * 2)        # K+V once, Q in/O out, new rows, scores, <= B moved rows r+w
     roofline = None
-    if "attention" in kernels:
-        t_attn = kernels["attention"]["avg_us"] * 1e-6
+    if "step_main" in kernels:
+        t_attn = kernels["step_main"]["avg_us"] * 1e-6
         achieved = flops_attn / t_attn / 1e12
-        roofline = {"bound": "mfma", "kernel": "attn_kernel", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
-                    "flops_per_launch": flops_attn, "avg_launch_us": kernels["attention"]["avg_us"]}
+        roofline = {"bound": "mfma", "kernel": "step_main_kernel", "achieved": achieved,
+                    "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
+                    "traffic": None, "flops_per_launch": flops_attn,
+                    "avg_launch_us": kernels["step_main"]["avg_us"]}
     t_min = max(flops_attn / (PEAK_BF16_MFMA_TFLOPS * 1e12), bytes_step / (PEAK_HBM_GBPS * 1e9))
     step_frac = t_min / (us_per_layer_step * 1e-6)
 

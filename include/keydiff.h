@@ -87,10 +87,11 @@ typedef struct {
 } keydiff_config_t;
 
 /* Sizes (bytes) of the four device buffers the caller must provide for `cfg`.
- * k_bytes == v_bytes: one K (or V) cache.  meta: token positions and status
- * words (persistent state).  scratch: per-call temporaries (attention partials,
- * anchor partial sums, scores, selection lists); its contents carry nothing
- * between calls.  Host call, nothing is enqueued.                              */
+ * k_bytes == v_bytes: one K (or V) cache.  meta: persistent state (token
+ * positions, the running key sum the anchor is derived from, the score
+ * histogram and counters that are kept clean between steps, a status word).
+ * scratch: per-call temporaries (attention partials, scores, selection lists);
+ * its contents carry nothing between calls.  Host call, nothing is enqueued.   */
 KEYDIFF_API int keydiff_workspace_bytes(const keydiff_config_t *cfg, size_t *k_bytes, size_t *v_bytes,
                             size_t *meta_bytes, size_t *scratch_bytes);
 
@@ -147,14 +148,11 @@ KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *stat
  * keydiff_profile_read synchronises, writes the summed milliseconds and launch
  * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
 enum {
-    KEYDIFF_K_APPEND = 0,
-    KEYDIFF_K_ATTENTION = 1,
-    KEYDIFF_K_MERGE = 2,
-    KEYDIFF_K_ANCHOR = 3,
-    KEYDIFF_K_SCORE = 4,
-    KEYDIFF_K_SELECT = 5,
-    KEYDIFF_K_COMPACT = 6,
-    KEYDIFF_NKERNELS = 7
+    KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key-sum update          */
+    KEYDIFF_K_POST = 1,    /* step_post: partial merge || score, selection, compaction         */
+    KEYDIFF_K_COMPACT = 2, /* stable in-place row shift (ORDERED layout only)                  */
+    KEYDIFF_K_AUX = 3,     /* cache load helpers                                               */
+    KEYDIFF_NKERNELS = 4
 };
 KEYDIFF_API int keydiff_profile_enable(keydiff_cache_t *cache, int32_t enable);
 KEYDIFF_API int keydiff_profile_read(keydiff_cache_t *cache, float *ms_out, int32_t *launches_out);

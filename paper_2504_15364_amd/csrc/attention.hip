@@ -1,37 +1,40 @@
-// Block attention over cache || block (Eq. 1-2 of the paper) for gfx950.
+// step_main: append + block attention over cache || block (Eq. 5, Eq. 1-2) for gfx950.
 //
-// Flash-style: the attention matrix is never materialised (the paper's point in
-// Method, "Efficient Variant": KeyDiff needs no attention weights).  bf16 MFMA
-// 32x32x16 for both contractions, fp32 online softmax, K/V tiles staged in LDS.
+// Flash-style: the attention matrix is never materialised (Method, "Efficient
+// Variant": KeyDiff needs no attention weights).  bf16 MFMA 32x32x16 for both
+// contractions, fp32 online softmax, K/V tiles double-buffered in LDS.
 //
 // Work decomposition.  All G * Bt query rows that share one KV head form the M
-// dimension (GQA packing): a workgroup of 4 waves owns 128 * NQ of them and a
-// contiguous range of 64-key tiles (split-KV); partial results of the splits are
-// merged by log-sum-exp in merge_kernel.  Workgroup ids map KV heads round-robin
-// so that all workgroups of one head land on the same XCD and share its L2.
+// dimension (GQA packing): a workgroup of NW waves owns 32 * NW of them and a
+// contiguous range of 64-key tiles (split-KV); the splits are merged by
+// log-sum-exp in step_post.  Workgroup ids map KV heads round-robin so that the
+// workgroups of one head share an XCD and its L2.
 //
 // Both contractions are computed transposed so that softmax statistics are
 // per-lane scalars and P never leaves registers:
 //   S^T = K Q^T   A = K tile rows (LDS, row-major), B = Q^T (registers)
-//                 -> lane holds query column (lane % 32), 16 keys
-//   O^T = V^T P^T A = V^T (LDS, stored transposed at tile load), B = P^T
-//                 -> the accumulator layout of S^T is already the B-operand
-//                    layout of the second MFMA once the 16 keys of a k-chunk are
-//                    enumerated in accumulator order; V^T is stored with the
-//                    matching key permutation.
+//                 -> a lane holds one query column (lane % 32) and 16 keys
+//   O^T = V^T P^T A = V^T (LDS, transposed while staging), B = P^T: the S^T
+//                 accumulator layout already is the B-operand layout once the 16
+//                 keys of a k-chunk are enumerated in accumulator order; V^T is
+//                 stored with the matching key permutation.
+//
+// The block's own rows are read straight from k_new / v_new; every workgroup
+// copies a slice of them into the cache (the append) and adds that slice to the
+// running key sum the anchor is derived from.
 #include "kd_kernels.h"
 
 namespace kd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
-{
-    return __builtin_bit_cast(bf16x8, v);
-}
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+constexpr float RESCALE_SLACK = 8.f;  // the running reference max may lag the true max by 2^8
 
 // Key permutation inside a 16-key chunk of V^T.  An S^T accumulator of lane
 // half h holds keys 8j + 4h + r (j = 0..3, r = 0..3) of its 32-key group; the
@@ -39,16 +42,21 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v)
 // 16c + 8a + 4h + r (a = 0,1).  Its 8 k-slots per half must be contiguous in
 // LDS: key (c, a, h, r) is stored at slot 16c + 8h + 4a + r.
 
-template <int D, int NQ>
-__global__ __launch_bounds__(256) void attn_kernel(AttnParams p)
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 {
+    constexpr int NT = 64 * NW;  // threads; each wave owns 32 query rows
     constexpr int UPR = D / 8;   // 16-byte units per K/V row
     constexpr int NC = D / 16;   // k-chunks of the first MFMA
     constexpr int NDB = D / 32;  // 32-wide d blocks of the output
-    constexpr int KLOADS = (TILE_KEYS * UPR) / 256;
+    constexpr int KLOADS = (TILE_KEYS * UPR) / NT;
+    constexpr int TILE_ELEMS = TILE_KEYS * D;
+    static_assert(KLOADS >= 1, "tile staging needs at least one K unit per thread");
 
-    __shared__ __attribute__((aligned(16))) uint16_t sK[TILE_KEYS * D];
-    __shared__ __attribute__((aligned(16))) uint16_t sVT[D * TILE_KEYS];
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t *sK = smem;                    // [2][TILE_KEYS][D]   swizzled rows
+    uint16_t *sVT = smem + 2 * TILE_ELEMS;  // [2][D][TILE_KEYS]   transposed, permuted, swizzled
+    __shared__ double red[NW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -63,71 +71,109 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnParams p)
     const int t0 = (int)(((long)sp * p.ntiles) / p.splits);
     const int t1 = (int)(((long)(sp + 1) * p.ntiles) / p.splits);
 
-    const uint16_t *kbase = p.k + (size_t)bh * p.cap * D;
-    const uint16_t *vbase = p.v + (size_t)bh * p.cap * D;
+    const uint16_t *kcache = p.k + (size_t)bh * p.cap * D;
+    const uint16_t *vcache = p.v + (size_t)bh * p.cap * D;
+    const uint16_t *knew = p.k_new + (size_t)bh * p.Bt * D;
+    const uint16_t *vnew = p.v_new + (size_t)bh * p.Bt * D;
 
-    // ---- query rows of this lane: B operand of S^T = K Q^T, kept in registers
-    int mrow[NQ], vis[NQ];
-    bf16x8 qreg[NQ][NC];
+    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and the key sum
+    {
+        const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
+        const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
+        const int rows = j1 - j0;
+        for (int u = tid; u < rows * UPR * 2; u += NT) {
+            const int which = u / (rows * UPR), rem = u % (rows * UPR);
+            const int j = j0 + rem / UPR, unit = rem % UPR;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
+            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
+        }
+        for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
+        double acc = 0.0;
+        for (int j = j0; j < j1; ++j) {
+            double x = 0.0;
+            if (tid < D) x = (double)__uint_as_float((uint32_t)knew[(size_t)j * D + tid] << 16);
+            if (p.anchor_mode == 1) {  // unit keys (Eq. 7): x / |k_j|, a zero key adds nothing
+                double k2 = x * x;
 #pragma unroll
-    for (int s = 0; s < NQ; ++s) {
-        const int m = mt * (128 * NQ) + wave * (32 * NQ) + s * 32 + l32;
-        const bool valid = m < Mtot;
-        const int g = valid ? m / p.Bt : 0, j = valid ? m % p.Bt : 0;
-        mrow[s] = valid ? m : -1;
-        vis[s] = p.len + j + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
-        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D;
+                for (int off = 1; off < 64; off <<= 1) {
+                    int lo = __shfl_xor(__double2loint(k2), off), hi = __shfl_xor(__double2hiint(k2), off);
+                    k2 += __hiloint2double(hi, lo);
+                }
+                __syncthreads();
+                if (lane == 0) red[wave] = k2;
+                __syncthreads();
+                double tot = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tot += red[w];
+                const double nk = sqrt(tot);
+                x = nk > 0.0 ? x * (1.0 / nk) : 0.0;
+            }
+            acc += x;
+        }
+        if (tid < D && rows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
+    }
+
+    // ---- query row of this lane: B operand of S^T = K Q^T, kept in registers
+    const int m = mt * (32 * NW) + wave * 32 + l32;
+    const bool valid = m < Mtot;
+    const int qg = valid ? m / p.Bt : 0, qj = valid ? m % p.Bt : 0;
+    const int vis = p.len + qj + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
+    bf16x8 qreg[NC];
+    {
+        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             u32x4 z = {0u, 0u, 0u, 0u};
             if (valid) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
-            qreg[s][c] = as_bf16x8(z);
+            qreg[c] = as_bf16x8(z);
         }
     }
 
-    f32x16 oacc[NQ][NDB];
-    float mrun[NQ], lrun[NQ];
+    f32x16 oacc[NDB];
+    float mref = -INFINITY, lrun = 0.f;
 #pragma unroll
-    for (int s = 0; s < NQ; ++s) {
-        mrun[s] = -INFINITY;
-        lrun[s] = 0.f;
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[s][db][e] = 0.f;
-    }
+        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
 
-    // ---- tile staging: global -> registers (prefetch) -> LDS
+    // ---- tile staging: global -> registers (prefetch) -> LDS (double buffered)
     u32x4 kpre[KLOADS], vpre[4];
     const int v_db = tid % UPR, v_kq = tid / UPR;  // V item: 4 consecutive keys x one 16-byte unit
     const bool v_active = tid < 16 * UPR;
+
+    auto row_ptr = [&](const uint16_t *cache, const uint16_t *fresh, int row) -> const uint16_t * {
+        return row < p.len ? cache + (size_t)row * D : fresh + (size_t)(row - p.len) * D;
+    };
 
     auto prefetch = [&](int t) {
         const int r0 = t * TILE_KEYS;
 #pragma unroll
         for (int pp = 0; pp < KLOADS; ++pp) {
-            const int idx = tid + 256 * pp;
-            const int row = idx / UPR, unit = idx % UPR;
+            const int idx = tid + NT * pp;
+            const int row = r0 + idx / UPR, unit = idx % UPR;
             u32x4 z = {0u, 0u, 0u, 0u};
-            if (r0 + row < p.n) z = *reinterpret_cast<const u32x4 *>(kbase + (size_t)(r0 + row) * D + unit * 8);
+            if (row < p.n) z = *reinterpret_cast<const u32x4 *>(row_ptr(kcache, knew, row) + unit * 8);
             kpre[pp] = z;
         }
+        if (v_active) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = r0 + 4 * v_kq + i;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (v_active && row < p.n) z = *reinterpret_cast<const u32x4 *>(vbase + (size_t)row * D + v_db * 8);
-            vpre[i] = z;
+            for (int i = 0; i < 4; ++i) {
+                const int row = r0 + 4 * v_kq + i;
+                u32x4 z = {0u, 0u, 0u, 0u};
+                if (row < p.n) z = *reinterpret_cast<const u32x4 *>(row_ptr(vcache, vnew, row) + v_db * 8);
+                vpre[i] = z;
+            }
         }
     };
 
-    auto stage = [&]() {
+    auto stage = [&](int buf) {
+        uint16_t *dK = sK + buf * TILE_ELEMS, *dV = sVT + buf * TILE_ELEMS;
 #pragma unroll
         for (int pp = 0; pp < KLOADS; ++pp) {
-            const int idx = tid + 256 * pp;
+            const int idx = tid + NT * pp;
             const int row = idx / UPR, unit = idx % UPR;
             const int su = unit ^ (row & 7);
-            *reinterpret_cast<u32x4 *>(sK + row * D + su * 8) = kpre[pp];
+            *reinterpret_cast<u32x4 *>(dK + row * D + su * 8) = kpre[pp];
         }
         if (v_active) {
             const int c = v_kq >> 2, q4 = v_kq & 3, a = q4 >> 1, hh = q4 & 1;
@@ -147,191 +193,156 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnParams p)
                     }
                     const int su = unit ^ ((R ^ (R >> 3)) & 7);
                     u32x2 val = {lo, hi};
-                    *reinterpret_cast<u32x2 *>(sVT + R * TILE_KEYS + su * 8 + a * 4) = val;
+                    *reinterpret_cast<u32x2 *>(dV + R * TILE_KEYS + su * 8 + a * 4) = val;
                 }
             }
         }
     };
 
-    if (t0 < t1) prefetch(t0);
+    if (t0 < t1) {
+        prefetch(t0);
+        stage(0);
+        if (t0 + 1 < t1) prefetch(t0 + 1);
+    }
+    int cur = 0;
     for (int t = t0; t < t1; ++t) {
-        __syncthreads();  // everyone finished reading the previous tile
-        stage();
-        __syncthreads();
-        if (t + 1 < t1) prefetch(t + 1);  // loads fly while this tile is computed
+        __syncthreads();  // tile t is staged; the other buffer is no longer read
+        if (t + 1 < t1) {
+            stage(cur ^ 1);
+            if (t + 2 < t1) prefetch(t + 2);  // in flight during this tile and the next staging
+        }
+        const uint16_t *tK = sK + cur * TILE_ELEMS, *tV = sVT + cur * TILE_ELEMS;
+        cur ^= 1;
 
         const int r0 = t * TILE_KEYS;
-        // ---- S^T = K Q^T
-        f32x16 sacc[NQ][2];
-#pragma unroll
-        for (int s = 0; s < NQ; ++s)
-#pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[s][kg][e] = 0.f;
+        const bool need_mask = r0 + TILE_KEYS > p.len;
+
+        // ---- per 32-key group: S^T = K Q^T, online softmax (per lane = per query column),
+        //      then O^T += V^T P^T
 #pragma unroll
         for (int kg = 0; kg < 2; ++kg) {
-            const int row = 32 * kg + l32;
+            f32x16 sacc;
+            {
+                const int row = 32 * kg + l32;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int su = (2 * c + h) ^ (row & 7);
-                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(sK + row * D + su * 8));
-#pragma unroll
-                for (int s = 0; s < NQ; ++s)
-                    sacc[s][kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s][c], sacc[s][kg], 0, 0, 0);
+                for (int c = 0; c < NC; ++c) {
+                    const int su = (2 * c + h) ^ (row & 7);
+                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(tK + row * D + su * 8));
+                    if (c == 0) {
+                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], zero, 0, 0, 0);
+                    } else {
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], sacc, 0, 0, 0);
+                    }
+                }
             }
-        }
-
-        // ---- online softmax, per lane = per query column
-        const bool need_mask = r0 + TILE_KEYS > p.len;
-        bf16x8 pk[NQ][4];
-#pragma unroll
-        for (int s = 0; s < NQ; ++s) {
             float mloc = -INFINITY;
 #pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float x = sacc[s][kg][e] * p.scale_log2e;
-                    if (need_mask) {
-                        const int key = r0 + 32 * kg + 8 * (e >> 2) + 4 * h + (e & 3);
-                        x = key < vis[s] ? x : -INFINITY;
-                    }
-                    sacc[s][kg][e] = x;
-                    mloc = fmaxf(mloc, x);
+            for (int e = 0; e < 16; ++e) {
+                float x = sacc[e];
+                if (need_mask) {
+                    const int key = r0 + 32 * kg + 8 * (e >> 2) + 4 * h + (e & 3);
+                    x = key < vis ? x : -INFINITY;
+                    sacc[e] = x;
                 }
+                mloc = fmaxf(mloc, x);
+            }
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            const float mnew = fmaxf(mrun[s], mloc);
-            const float muse = mnew == -INFINITY ? 0.f : mnew;
-            const float alpha = __builtin_amdgcn_exp2f(mrun[s] - muse);
-            mrun[s] = mnew;
-            float lsum = 0.f;
+            const float mtile = mloc * p.scale_log2e;
+            // lazy rescale: the reference max only moves when the tile max exceeds it by 2^SLACK
+            const bool need = mtile > mref + RESCALE_SLACK;
+            if (__builtin_amdgcn_ballot_w64(need) != 0) {
+                const float alpha = need ? __builtin_amdgcn_exp2f(mref - mtile) : 1.f;
+                mref = need ? mtile : mref;
+                lrun *= alpha;
 #pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+            }
+            const float nmuse = mref == -INFINITY ? 0.f : -mref;
+            float lsum = 0.f;
+            bf16x8 pk[2];
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                bf16x8 v;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
+                    lsum += pe;
+                    v[i] = (__bf16)pe;
+                }
+                pk[cc] = v;
+            }
+            lrun += lsum;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const int R = 32 * db + l32;
 #pragma unroll
                 for (int cc = 0; cc < 2; ++cc) {
-                    bf16x8 v;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float pe = __builtin_amdgcn_exp2f(sacc[s][kg][8 * cc + i] - muse);
-                        lsum += pe;
-                        v[i] = (__bf16)pe;
-                    }
-                    pk[s][2 * kg + cc] = v;
+                    const int su = (2 * (2 * kg + cc) + h) ^ ((R ^ (R >> 3)) & 7);
+                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(tV + R * TILE_KEYS + su * 8));
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pk[cc], oacc[db], 0, 0, 0);
                 }
-            lrun[s] = lrun[s] * alpha + lsum;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[s][db][e] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const int R = 32 * db + l32;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int su = (2 * c + h) ^ ((R ^ (R >> 3)) & 7);
-                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(sVT + R * TILE_KEYS + su * 8));
-#pragma unroll
-                for (int s = 0; s < NQ; ++s)
-                    oacc[s][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pk[s][c], oacc[s][db], 0, 0, 0);
             }
         }
     }
 
     // ---- epilogue: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
+    const float ltot = lrun + __shfl_xor(lrun, 32);
+    if (!valid) return;
+    if (p.splits == 1) {
+        uint16_t *op = p.out + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
+        const float inv = 1.f / ltot;
 #pragma unroll
-    for (int s = 0; s < NQ; ++s) {
-        const float ltot = lrun[s] + __shfl_xor(lrun[s], 32);
-        const int m = mrow[s];
-        if (m < 0) continue;
-        if (p.splits == 1) {
-            const int g = m / p.Bt, j = m % p.Bt;
-            uint16_t *op = p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D;
-            const float inv = 1.f / ltot;
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+            for (int jj = 0; jj < 4; ++jj) {
+                bf16x4 o;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                    bf16x4 o;
+                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[db][4 * jj + r] * inv);
+                *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * jj + 4 * h) = o;
+            }
+    } else {
+        const size_t row = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + m;
+        float *po = p.part_o + row * D;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[s][db][4 * jj + r] * inv);
-                    *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * jj + 4 * h) = o;
-                }
-        } else {
-            const size_t row = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + m;
-            float *po = p.part_o + row * D;
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    float4 o = make_float4(oacc[s][db][4 * jj], oacc[s][db][4 * jj + 1],
-                                           oacc[s][db][4 * jj + 2], oacc[s][db][4 * jj + 3]);
-                    *reinterpret_cast<float4 *>(po + 32 * db + 8 * jj + 4 * h) = o;
-                }
-            if (h == 0) p.part_ml[row] = make_float2(mrun[s], ltot);
-        }
+            for (int jj = 0; jj < 4; ++jj) {
+                float4 o = make_float4(oacc[db][4 * jj], oacc[db][4 * jj + 1], oacc[db][4 * jj + 2],
+                                       oacc[db][4 * jj + 3]);
+                *reinterpret_cast<float4 *>(po + 32 * db + 8 * jj + 4 * h) = o;
+            }
+        if (h == 0) p.part_ml[row] = make_float2(mref, ltot);
     }
 }
 
-// Log-sum-exp merge of the split-KV partials: one thread per (row, 4 outputs).
-template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
+static size_t main_lds_bytes(int D) { return (size_t)4 * TILE_KEYS * D * 2; }
+
+hipError_t configure_main_kernels()
 {
-    const int BH = p.batch * p.hkv;
-    const int Mtot = p.G * p.Bt;
-    const size_t rows = (size_t)BH * Mtot;
-    const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int d4 = (int)(gid % (D / 4));
-    const size_t row = gid / (D / 4);
-    if (row >= rows) return;
-    float mx = -INFINITY;
-    for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, p.part_ml[(size_t)s * rows + row].x);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float L = 0.f;
-    for (int s = 0; s < p.splits; ++s) {
-        const float2 ml = p.part_ml[(size_t)s * rows + row];
-        const float w = ml.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml.x - mx);
-        const float4 o = *reinterpret_cast<const float4 *>(p.part_o + ((size_t)s * rows + row) * D + 4 * d4);
-        acc.x += w * o.x;
-        acc.y += w * o.y;
-        acc.z += w * o.z;
-        acc.w += w * o.w;
-        L += w * ml.y;
-    }
-    const float inv = 1.f / L;
-    const int bh = (int)(row / Mtot), m = (int)(row % Mtot);
-    const int b = bh / p.hkv, kvh = bh % p.hkv;
-    const int g = m / p.Bt, j = m % p.Bt;
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-    bf16x4 o;
-    o[0] = (__bf16)(acc.x * inv);
-    o[1] = (__bf16)(acc.y * inv);
-    o[2] = (__bf16)(acc.z * inv);
-    o[3] = (__bf16)(acc.w * inv);
-    *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
+    hipError_t e;
+#define KD_SET(fn, D)                                                                              \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                            (int)main_lds_bytes(D));                                               \
+    if (e != hipSuccess) return e;
+    KD_SET((step_main_kernel<128, 8>), 128)
+    KD_SET((step_main_kernel<128, 4>), 128)
+    KD_SET((step_main_kernel<64, 8>), 64)
+    KD_SET((step_main_kernel<64, 4>), 64)
+#undef KD_SET
+    return hipSuccess;
 }
 
-hipError_t launch_attention(const AttnParams &p, int D, int NQ, hipStream_t s)
+hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 {
     const int grid = p.batch * p.hkv * p.mtiles * p.splits;
-    if (D == 128 && NQ == 2) hipLaunchKernelGGL((attn_kernel<128, 2>), dim3(grid), dim3(256), 0, s, p);
-    else if (D == 128 && NQ == 1) hipLaunchKernelGGL((attn_kernel<128, 1>), dim3(grid), dim3(256), 0, s, p);
-    else if (D == 64 && NQ == 2) hipLaunchKernelGGL((attn_kernel<64, 2>), dim3(grid), dim3(256), 0, s, p);
-    else if (D == 64 && NQ == 1) hipLaunchKernelGGL((attn_kernel<64, 1>), dim3(grid), dim3(256), 0, s, p);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-hipError_t launch_merge(const AttnParams &p, int D, hipStream_t s)
-{
-    const size_t threads = (size_t)p.batch * p.hkv * p.G * p.Bt * (D / 4);
-    const int grid = (int)((threads + 255) / 256);
-    if (D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, s, p);
-    else if (D == 64) hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, s, p);
+    const size_t lds = main_lds_bytes(p.D);
+    if (p.D == 128 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<128, 8>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 128 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<128, 4>), dim3(grid), dim3(256), lds, s, p);
+    else if (p.D == 64 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<64, 8>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 64 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<64, 4>), dim3(grid), dim3(256), lds, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

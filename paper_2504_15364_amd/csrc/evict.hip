@@ -1,18 +1,29 @@
-// Append, anchor, cosine score, selection and compaction kernels for gfx950.
+// step_post: cosine score, selection and compaction (Eq. 6-7, appendix "FLOP count
+// of KeyDiff"), running next to the log-sum-exp merge of the attention partials.
 //
 // The score that decides an eviction is IEEE double arithmetic on the bf16 data,
-// rounded once to float (appendix "FLOP count of KeyDiff":
-// s_i = mu.k_i / max(|mu||k_i|, eps)).  These passes are bandwidth bound, so the
-// double FMAs cost nothing; in exchange the retained set does not depend on
-// summation order beyond the last bit of a double.
+// rounded once to float: s_i = mu.k_i / max(|mu||k_i|, eps) with mu = ksum / n.
+// The pass is bandwidth bound, so the double FMAs are free; in exchange the
+// retained set does not depend on summation order beyond the last bit of a double.
+//
+// Selection.  Every score also lands in a 4096-bin histogram of its head (a
+// monotone map of the float).  The workgroup that finishes a head's scores last
+// (fence + counter, nobody waits) scans the histogram for the bin that holds the
+// E-th largest score, evicts everything above that bin and ranks the few rows
+// inside it exactly by (score bits, position): equal scores keep the lower
+// position.  It then compacts the cache and takes the evicted keys out of ksum.
 #include "kd_kernels.h"
 
 namespace kd {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ double bf16_to_f64(uint16_t b) { return (double)__uint_as_float((uint32_t)b << 16); }
 
 __device__ __forceinline__ double shfl_xor_f64(double x, int m)
 {
@@ -22,152 +33,34 @@ __device__ __forceinline__ double shfl_xor_f64(double x, int m)
     return __hiloint2double(hi, lo);
 }
 
-// ------------------------------------------------------------------- append (Eq. 5)
-__global__ __launch_bounds__(256) void append_kernel(const uint16_t *k_new, const uint16_t *v_new,
-                                                     uint16_t *k, uint16_t *v, int32_t *pos, int cap,
-                                                     int D, int len, int Bt, int32_t pos0)
-{
-    const int bh = blockIdx.y;
-    const int units = Bt * (D / 8);
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < units) {
-        const size_t src = (size_t)bh * Bt * D + (size_t)i * 8;
-        const size_t dst = ((size_t)bh * cap + len) * D + (size_t)i * 8;
-        *reinterpret_cast<u32x4 *>(k + dst) = *reinterpret_cast<const u32x4 *>(k_new + src);
-        *reinterpret_cast<u32x4 *>(v + dst) = *reinterpret_cast<const u32x4 *>(v_new + src);
-    }
-    if (i < Bt) pos[(size_t)bh * cap + len + i] = pos0 + i;
-}
-
-// ------------------------------------------------------------------ anchor partial sums
-// Column sums of CHUNK_ROWS rows in double.  mode 1 sums unit keys (Eq. 7): each
-// row is scaled by 1/|k| first (a zero key contributes nothing).
-template <int D>
-__global__ __launch_bounds__(256) void anchor_kernel(EvictParams p)
-{
-    constexpr int UPR = D / 8;
-    constexpr int RL = 256 / UPR;  // rows in flight per pass
-    __shared__ double red[RL][D];
-    const int bh = blockIdx.y, chunk = blockIdx.x;
-    const int u = threadIdx.x % UPR, rl = threadIdx.x / UPR;
-    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
-    double acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-    const int r0 = chunk * CHUNK_ROWS;
-    for (int r = rl; r < CHUNK_ROWS; r += RL) {
-        const int row = r0 + r;
-        double x[8];
-        if (row < p.n) {
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x[2 * i] = bf16_lo(w[i]);
-                x[2 * i + 1] = bf16_hi(w[i]);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = 0.0;
-        }
-        double inv = 1.0;
-        if (p.anchor_mode == 1) {
-            double k2 = 0.0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
-#pragma unroll
-            for (int m = 1; m < UPR; m <<= 1) k2 += shfl_xor_f64(k2, m);
-            const double nk = sqrt(k2);
-            inv = nk > 0.0 ? 1.0 / nk : 0.0;
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) red[rl][u * 8 + i] = acc[i];
-    __syncthreads();
-    if (threadIdx.x < D) {
-        double s = 0.0;
-        for (int r = 0; r < RL; ++r) s += red[r][threadIdx.x];
-        p.anchor_part[((size_t)bh * p.nchunks + chunk) * D + threadIdx.x] = s;
-    }
-}
-
-// ------------------------------------------------------------------------- score
-template <int D>
-__global__ __launch_bounds__(256) void score_kernel(EvictParams p)
-{
-    constexpr int UPR = D / 8;
-    constexpr int RL = 256 / UPR;
-    __shared__ double mu[D];
-    __shared__ double wsum[4];
-    const int bh = blockIdx.y, chunk = blockIdx.x;
-    const int tid = threadIdx.x;
-    // anchor = (sum of the chunk partials, fixed order) / n
-    double m = 0.0;
-    if (tid < D) {
-        const double *ap = p.anchor_part + (size_t)bh * p.nchunks * D + tid;
-        for (int c = 0; c < p.nchunks; ++c) m += ap[(size_t)c * D];
-        m /= (double)p.n;
-        mu[tid] = m;
-    }
-    // |mu|^2: every thread with tid >= D contributes zero
-    double sq = m * m;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) sq += shfl_xor_f64(sq, off);
-    if ((tid & 63) == 0) wsum[tid >> 6] = sq;
-    __syncthreads();
-    const double nmu = sqrt(wsum[0] + wsum[1] + wsum[2] + wsum[3]);
-
-    const int u = tid % UPR, rl = tid / UPR;
-    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
-    double mreg[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) mreg[i] = mu[u * 8 + i];
-    const int r0 = chunk * CHUNK_ROWS;
-    for (int r = rl; r < CHUNK_ROWS; r += RL) {
-        const int row = r0 + r;
-        double dot = 0.0, k2 = 0.0;
-        if (row < p.n) {
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const double a = bf16_lo(w[i]), b = bf16_hi(w[i]);
-                dot += mreg[2 * i] * a;
-                k2 += a * a;
-                dot += mreg[2 * i + 1] * b;
-                k2 += b * b;
-            }
-        }
-#pragma unroll
-        for (int mk = 1; mk < UPR; mk <<= 1) {
-            dot += shfl_xor_f64(dot, mk);
-            k2 += shfl_xor_f64(k2, mk);
-        }
-        if (u == 0 && row < p.n) {
-            double den = nmu * sqrt(k2);
-            if (den < p.eps) den = p.eps;
-            const float s = (float)(dot / den) + 0.0f;  // +0 folds -0 into +0
-            p.scores[(size_t)bh * p.cap + row] = s;
-        }
-    }
-}
-
-// ------------------------------------------------------------------------ select
-// One workgroup per (sequence, KV head).  Finds the E = n - N rows with the
-// largest (score, position) -- these are evicted; everything else is retained,
-// so equal scores keep the lower position -- by an MSB-first 8-bit radix select
-// over the 64-bit key (orderable score bits : position).  Positions are unique,
-// so the threshold is exact and there are no ties left to break.
+// float -> unsigned key with the same order
 __device__ __forceinline__ uint32_t orderable(float s)
 {
     const uint32_t b = __float_as_uint(s);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-struct SelectShared {
-    uint32_t hist[256];
+// monotone non-decreasing map of a score onto [0, HIST_BINS)
+__device__ __forceinline__ int score_bin(float s)
+{
+    const float f = floorf((s + 1.0f) * (float)(HIST_BINS / 2));
+    return (int)fminf(fmaxf(f, 0.f), (float)(HIST_BINS - 1));
+}
+
+struct PostShared {
+    double mu[128];
+    double red[16];
+    double colsum[POST_THREADS];
     uint32_t wave_tot[16];
-    uint32_t sel_bin, sel_rank, sel_cnt, total_evicted;
+    uint32_t radix_hist[256];
+    uint32_t sel_bin, sel_rank, sel_cnt;
+    int tb;               // threshold bin
+    uint32_t need;        // rows to evict from the threshold bin
+    uint32_t ncand;
+    uint32_t is_last;
+    uint32_t cand_slot[CAND_MAX];
+    uint32_t cand_key[CAND_MAX];
+    int32_t cand_pos[CAND_MAX];
 };
 
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
@@ -193,65 +86,112 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
     return base + inc - v;
 }
 
-__global__ __launch_bounds__(SELECT_THREADS) void select_kernel(EvictParams p)
+// ------------------------------------------------------------------------ scores
+// Rows [row0, row1) of head bh; D/8 lanes per row, each lane one 16-byte unit.
+template <int D>
+__device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, int bh, int row0, int row1)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __shared__ SelectShared sh;
-    uint32_t *skey = reinterpret_cast<uint32_t *>(smem_raw);  // [n] orderable scores
-    const int E = p.n - p.N;
-    int32_t *lists = reinterpret_cast<int32_t *>(skey + p.n);  // FILL: holes[E], movers[E]
-
-    const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-    const float *sc = p.scores + (size_t)bh * p.cap;
-    int32_t *pos = p.pos + (size_t)bh * p.cap;
-
-    for (int i = tid; i < p.n; i += SELECT_THREADS) {
-        uint32_t key = orderable(sc[i]);
-        if (p.window_W > 0 && pos[i] >= p.window_pos_min) key = 0u;  // exempt: never a candidate
-        skey[i] = key;
+    constexpr int UPR = D / 8;
+    constexpr int RPP = POST_THREADS / UPR;  // rows per pass
+    const int tid = threadIdx.x;
+    // anchor = ksum / n (Method, "Efficient Variant"); |mu| by a fixed-shape reduction
+    double m = 0.0;
+    if (tid < D) {
+        m = p.ksum[(size_t)bh * D + tid] / (double)p.n;
+        sh.mu[tid] = m;
     }
-    // contiguous ownership: thread t owns rows [t*S, t*S + S); S odd keeps LDS reads conflict free
-    int S = (p.n + SELECT_THREADS - 1) / SELECT_THREADS;
-    S |= 1;
-    const int own0 = tid * S;
-    const int own1 = min(p.n, own0 + S);
+    double sq = m * m;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) sq += shfl_xor_f64(sq, off);
+    if ((tid & 63) == 0) sh.red[tid >> 6] = sq;
+    __syncthreads();
+    double mu2 = 0.0;
+#pragma unroll
+    for (int w = 0; w < POST_THREADS / 64; ++w) mu2 += sh.red[w];
+    const double nmu = sqrt(mu2);
 
-    uint64_t prefix = 0;  // resolved high bits of the threshold
-    uint32_t rank = (uint32_t)E;
-    int resolved = 0;  // number of resolved bits
+    const int u = tid % UPR, rl = tid / UPR;
+    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    double mreg[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mreg[i] = sh.mu[u * 8 + i];
+    const int npass = (row1 - row0 + RPP - 1) / RPP;  // uniform trip count: the shuffles need every lane
+    for (int ps = 0; ps < npass; ++ps) {
+        const int row = row0 + ps * RPP + rl;
+        double dot = 0.0, k2 = 0.0;
+        const bool live = row < row1;
+        if (live) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const double a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+                dot += mreg[2 * i] * a;
+                k2 += a * a;
+                dot += mreg[2 * i + 1] * b;
+                k2 += b * b;
+            }
+        }
+#pragma unroll
+        for (int mk = 1; mk < UPR; mk <<= 1) {
+            dot += shfl_xor_f64(dot, mk);
+            k2 += shfl_xor_f64(k2, mk);
+        }
+        if (u == 0 && live) {
+            double den = nmu * sqrt(k2);
+            if (den < p.eps) den = p.eps;
+            const float s = (float)(dot / den) + 0.0f;  // +0 folds -0 into +0
+            p.scores[(size_t)bh * p.cap + row] = s;
+            if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = s;
+            if (p.do_evict) {
+                const bool exempt = p.window_W > 0 && p.pos[(size_t)bh * p.cap + row] >= p.window_pos_min;
+                if (!exempt) atomicAdd(p.hist + (size_t)bh * HIST_BINS + score_bin(s), 1u);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------- slow path: radix select in a bin
+// More than CAND_MAX rows share the threshold bin (near-identical keys).  MSB-first
+// 8-bit radix select over the 64-bit key (orderable score : position) restricted to
+// that bin; reads scores and positions from memory on every pass.  Marks the
+// `need` largest in the evict bitmap.
+__device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const float *sc, const int32_t *pos,
+                                    uint32_t *evbits, int tb, uint32_t need)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint64_t prefix = 0;
+    uint32_t rank = need;
+    int resolved = 0;
     for (int pass = 0; pass < 8; ++pass) {
         const int shift = 56 - 8 * pass;
-        for (int i = tid; i < 256; i += SELECT_THREADS) sh.hist[i] = 0;
+        for (int i = tid; i < 256; i += POST_THREADS) sh.radix_hist[i] = 0;
         __syncthreads();
-        for (int i = own0; i < own0 + S; ++i) {
+        for (int i0 = 0; i0 < p.n; i0 += POST_THREADS) {
+            const int i = i0 + tid;
             bool part = false;
             uint32_t digit = 0;
-            if (i < own1) {
-                const uint32_t hi = skey[i];
-                if (pass < 4) {
-                    part = pass == 0 || (hi >> (32 - 8 * pass)) == (uint32_t)(prefix);
-                    digit = (hi >> (24 - 8 * pass)) & 255u;
-                } else if (hi == (uint32_t)(prefix >> (8 * (pass - 4)))) {
-                    const uint64_t key = ((uint64_t)hi << 32) | (uint32_t)pos[i];
-                    part = (key >> (shift + 8)) == prefix;
+            if (i < p.n) {
+                const float s = sc[i];
+                const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
+                if (!exempt && score_bin(s) == tb) {
+                    const uint64_t key = ((uint64_t)orderable(s) << 32) | (uint32_t)pos[i];
+                    part = pass == 0 || (key >> (shift + 8)) == prefix;
                     digit = (uint32_t)(key >> shift) & 255u;
                 }
             }
-            // one aggregated add for the leader's digit (clustered scores), plain adds for the rest
             const uint64_t active = __ballot(part);
             if (active) {
                 const int leader = __ffsll((unsigned long long)active) - 1;
                 const uint32_t ld = __shfl(digit, leader);
                 const uint64_t same = __ballot(part && digit == ld);
-                if (lane == leader) atomicAdd(&sh.hist[ld], (uint32_t)__popcll(same));
-                else if (part && digit != ld) atomicAdd(&sh.hist[digit], 1u);
+                if (lane == leader) atomicAdd(&sh.radix_hist[ld], (uint32_t)__popcll(same));
+                else if (part && digit != ld) atomicAdd(&sh.radix_hist[digit], 1u);
             }
         }
         __syncthreads();
         if (tid < 64) {
-            // bins 4*lane .. 4*lane+3; suffix sums from the top bin down
-            const uint32_t c0 = sh.hist[4 * lane], c1 = sh.hist[4 * lane + 1], c2 = sh.hist[4 * lane + 2],
-                           c3 = sh.hist[4 * lane + 3];
+            const uint32_t c0 = sh.radix_hist[4 * lane], c1 = sh.radix_hist[4 * lane + 1],
+                           c2 = sh.radix_hist[4 * lane + 2], c3 = sh.radix_hist[4 * lane + 3];
             const uint32_t mine = c0 + c1 + c2 + c3;
             uint32_t suf = mine;
 #pragma unroll
@@ -260,10 +200,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(EvictParams p)
                 if (lane + off < 64) suf += t;
             }
             const uint64_t reach = __ballot(suf >= rank);
-            const int owner = 63 - __clzll((unsigned long long)reach);  // highest lane whose suffix reaches rank
+            const int owner = reach ? 63 - __clzll((unsigned long long)reach) : 0;
             if (lane == owner) {
-                uint32_t above = suf - mine;
-                uint32_t bin, cnt;
+                uint32_t above = suf - mine, bin, cnt;
                 if (above + c3 >= rank) { bin = 3; cnt = c3; }
                 else if ((above += c3) + c2 >= rank) { bin = 2; cnt = c2; }
                 else if ((above += c2) + c1 >= rank) { bin = 1; cnt = c1; }
@@ -277,77 +216,196 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(EvictParams p)
         prefix = (prefix << 8) | sh.sel_bin;
         rank = sh.sel_rank;
         resolved = 8 * (pass + 1);
-        const bool done = sh.sel_cnt == rank;  // every key left in the bin is evicted
+        const bool done = sh.sel_cnt == rank;
         __syncthreads();
         if (done) break;
     }
-
-    // evicted <=> top `resolved` bits of the key >= prefix
-    uint64_t evmask = 0;
-    uint32_t nev = 0;
-    for (int i = own0; i < own1; ++i) {
-        const uint32_t hi = skey[i];
-        bool ev;
-        if (resolved <= 32) ev = (hi >> (32 - resolved)) >= (uint32_t)prefix;
-        else {
-            const uint64_t key = ((uint64_t)hi << 32) | (uint32_t)pos[i];
-            ev = (key >> (64 - resolved)) >= prefix;
-        }
-        if (ev) {
-            evmask |= 1ull << (i - own0);
-            ++nev;
+    for (int i = tid; i < p.n; i += POST_THREADS) {
+        const float s = sc[i];
+        const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
+        if (!exempt && score_bin(s) == tb) {
+            const uint64_t key = ((uint64_t)orderable(s) << 32) | (uint32_t)pos[i];
+            if ((key >> (64 - resolved)) >= prefix) atomicOr(&evbits[i >> 5], 1u << (i & 31));
         }
     }
+    __syncthreads();
+}
 
+// ------------------------------------------------------------- select + compaction
+template <int D>
+__device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int bh)
+{
+    constexpr int UPR = D / 8;
+    const int tid = threadIdx.x;
+    const int E = p.n - p.N;
+    const float *sc = p.scores + (size_t)bh * p.cap;
+    int32_t *pos = p.pos + (size_t)bh * p.cap;
+    uint32_t *hist = p.hist + (size_t)bh * HIST_BINS;
+    int32_t *lists = p.lists + (size_t)bh * 3 * p.B;  // scratch: evicted | holes | movers, E entries each
+
+    // ---- 1. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
+    const int nwords = (p.n + 31) / 32;
+    for (int i = tid; i < nwords; i += POST_THREADS) evbits[i] = 0;
+    if (tid == 0) {
+        sh.ncand = 0;
+        sh.tb = 0;
+        sh.need = 0;
+    }
+    uint32_t cnt[HIST_BINS / POST_THREADS];
+    uint32_t mine = 0;
+    const int top = HIST_BINS - 1 - (HIST_BINS / POST_THREADS) * tid;
+#pragma unroll
+    for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
+        cnt[j] = hist[top - j];
+        hist[top - j] = 0;  // left clean for the next step
+        mine += cnt[j];
+    }
+    uint32_t total;
+    uint32_t above = block_exclusive_scan(mine, sh.wave_tot, &total);
+    if (above < (uint32_t)E && above + mine >= (uint32_t)E) {
+#pragma unroll
+        for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
+            if (above + cnt[j] >= (uint32_t)E) {
+                sh.tb = top - j;
+                sh.need = (uint32_t)E - above;
+                break;
+            }
+            above += cnt[j];
+        }
+    }
+    if (tid == 0 && total < (uint32_t)E) atomicOr(p.status, STATUS_SELECT_COUNT);  // corrupted histogram
+    __syncthreads();
+    const int tb = sh.tb;
+    const uint32_t need = sh.need;
+
+    // ---- 2. one pass over the scores: above the bin -> evicted, inside it -> candidate
+    for (int i = tid; i < p.n; i += POST_THREADS) {
+        const float s = sc[i];
+        const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
+        if (exempt) continue;
+        const int bin = score_bin(s);
+        if (bin > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
+        else if (bin == tb) {
+            const uint32_t c = atomicAdd(&sh.ncand, 1u);
+            if (c < CAND_MAX) {
+                sh.cand_slot[c] = (uint32_t)i;
+                sh.cand_key[c] = orderable(s);
+                sh.cand_pos[c] = pos[i];
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t ncand = sh.ncand;
+
+    // ---- 3. exact ranking inside the bin by (score bits, position), largest first
+    if (ncand <= CAND_MAX) {
+        for (uint32_t c = tid; c < ncand; c += POST_THREADS) {
+            const uint32_t key = sh.cand_key[c];
+            const int32_t ps = sh.cand_pos[c];
+            uint32_t rank = 0;
+            for (uint32_t o = 0; o < ncand; ++o) {
+                const uint32_t ok = sh.cand_key[o];
+                rank += (ok > key) || (ok == key && sh.cand_pos[o] > ps);
+            }
+            if (rank < need) {
+                const uint32_t i = sh.cand_slot[c];
+                atomicOr(&evbits[i >> 5], 1u << (i & 31));
+            }
+        }
+        __syncthreads();
+    } else {
+        radix_select_in_bin(p, sh, sc, pos, evbits, tb, need);
+    }
+
+    // ---- 4. ordered lists by contiguous ownership: thread t owns rows [t*S, t*S + S)
+    const int S = (p.n + POST_THREADS - 1) / POST_THREADS;
+    const int own0 = min(p.n, tid * S), own1 = min(p.n, own0 + S);
+    uint32_t nev = 0, nh = 0, nm = 0;
+    for (int i = own0; i < own1; ++i) {
+        const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
+        nev += ev;
+        nh += ev && i < p.N;
+        nm += !ev && i >= p.N;
+    }
+    uint32_t tot_ev, tot_hm;
+    uint32_t eb = block_exclusive_scan(nev, sh.wave_tot, &tot_ev);
+    const uint32_t hm = block_exclusive_scan(nh | (nm << 16), sh.wave_tot, &tot_hm);
+    const uint32_t nholes = tot_hm & 0xFFFFu, nmov = tot_hm >> 16;
+    // an impossible count is reported and nothing is moved (keeps every index in range)
+    const bool sane = tot_ev == (uint32_t)E && nholes == nmov && (uint32_t)E <= 0xFFFFu;
+    if (!sane) {
+        if (tid == 0) atomicOr(p.status, STATUS_SELECT_COUNT);
+        return;
+    }
+    int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E;
+    {
+        uint32_t hb = hm & 0xFFFFu, mb = hm >> 16, e2 = eb;
+        for (int i = own0; i < own1; ++i) {
+            const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
+            if (ev) evlist[e2++] = i;
+            if (ev && i < p.N) holes[hb++] = i;
+            if (!ev && i >= p.N) movers[mb++] = i;
+        }
+    }
+    __syncthreads();
+
+    // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten)
+    uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    uint16_t *vb = p.v + (size_t)bh * p.cap * D;
+    {
+        const int c = tid % D, g = tid / D;  // D columns x (1024 / D) row groups
+        constexpr int NG = POST_THREADS / D;
+        double acc = 0.0;
+        for (int rb = 0; rb < E; rb += NG) {  // uniform trip count: barriers and shuffles inside
+            const int r = rb + g;
+            const bool live = r < E;
+            double x = live ? bf16_to_f64(kb[(size_t)evlist[r] * D + c]) : 0.0;
+            if (p.anchor_mode == 1) {  // unit key: x / |k|, reduced over the D threads of the group
+                double k2 = x * x;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) k2 += shfl_xor_f64(k2, off);
+                if (D == 128) {  // a row group spans two waves
+                    if ((tid & 63) == 0) sh.red[tid >> 6] = k2;
+                    __syncthreads();
+                    k2 = sh.red[(tid >> 6) & ~1] + sh.red[(tid >> 6) | 1];
+                    __syncthreads();
+                }
+                const double nk = sqrt(k2);
+                x = nk > 0.0 ? x * (1.0 / nk) : 0.0;
+            }
+            acc += x;
+        }
+        sh.colsum[g * D + c] = acc;
+        __syncthreads();
+        if (tid < D) {
+            double s = 0.0;
+            for (int gg = 0; gg < NG; ++gg) s += sh.colsum[gg * D + tid];
+            p.ksum[(size_t)bh * D + tid] -= s;
+        }
+        __syncthreads();
+    }
+
+    // ---- 6. compaction
     if (p.layout == 1) {
         // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N)
-        uint32_t nh = 0, nm = 0;
-        for (int i = own0; i < own1; ++i) {
-            const bool ev = (evmask >> (i - own0)) & 1;
-            if (ev && i < p.N) ++nh;
-            if (!ev && i >= p.N) ++nm;
-        }
-        uint32_t total;
-        uint32_t base = block_exclusive_scan(nh | (nm << 16) | 0u, sh.wave_tot, &total);
-        uint32_t tot_ev;
-        (void)block_exclusive_scan(nev, sh.wave_tot, &tot_ev);
-        uint32_t hb = base & 0xFFFFu, mb = base >> 16;
-        int32_t *holes = lists, *movers = lists + E;
-        const uint32_t nholes = total & 0xFFFFu, nmov = total >> 16;
-        // an impossible count is reported and nothing is moved (keeps every index in range)
-        const bool sane = tot_ev == (uint32_t)E && nholes == nmov && nholes <= (uint32_t)E;
-        if (sane)
-            for (int i = own0; i < own1; ++i) {
-                const bool ev = (evmask >> (i - own0)) & 1;
-                if (ev && i < p.N) holes[hb++] = i;
-                if (!ev && i >= p.N) movers[mb++] = i;
-            }
-        __syncthreads();
-        if (tid == 0 && !sane) atomicOr(p.status, STATUS_SELECT_COUNT);
-        const int nmove = sane ? (int)nholes : 0;
-        const int UPR = p.D / 8;
-        uint16_t *kb = p.k + (size_t)bh * p.cap * p.D;
-        uint16_t *vb = p.v + (size_t)bh * p.cap * p.D;
-        for (int w = tid; w < nmove * UPR * 2; w += SELECT_THREADS) {
+        const int nmove = (int)nholes;
+        for (int w = tid; w < nmove * UPR * 2; w += POST_THREADS) {
             const int r = w / (UPR * 2), rem = w % (UPR * 2);
             const int u = rem % UPR;
             uint16_t *base_ptr = rem < UPR ? kb : vb;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(base_ptr + (size_t)movers[r] * p.D + u * 8);
-            *reinterpret_cast<u32x4 *>(base_ptr + (size_t)holes[r] * p.D + u * 8) = val;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(base_ptr + (size_t)movers[r] * D + u * 8);
+            *reinterpret_cast<u32x4 *>(base_ptr + (size_t)holes[r] * D + u * 8) = val;
         }
-        for (int r = tid; r < nmove; r += SELECT_THREADS) pos[holes[r]] = pos[movers[r]];
+        for (int r = tid; r < nmove; r += POST_THREADS) pos[holes[r]] = pos[movers[r]];
     } else {
-        // ORDERED: kept row i moves to i - (evicted rows before i)
-        uint32_t tot_ev;
-        uint32_t eb = block_exclusive_scan(nev, sh.wave_tot, &tot_ev);
-        if (tid == 0 && tot_ev != (uint32_t)E) atomicOr(p.status, STATUS_SELECT_COUNT);
+        // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here
+        // (all reads precede all writes), the K/V rows by compact_ordered_kernel.
+        int32_t mypos[(MAX_CAP + POST_THREADS - 1) / POST_THREADS];
         int32_t *dst = p.dstmap + (size_t)bh * p.cap;
-        int32_t mypos[33];
-        // positions are compacted here: all reads of pos precede all writes
         for (int i = own0, j = 0; i < own1; ++i, ++j) mypos[j] = pos[i];
         __syncthreads();
         for (int i = own0, j = 0; i < own1; ++i, ++j) {
-            const bool ev = (evmask >> (i - own0)) & 1;
+            const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
             if (ev) {
                 dst[i] = -1;
                 ++eb;
@@ -359,12 +417,78 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(EvictParams p)
     }
 }
 
-// --------------------------------------------------------------- ordered compaction
+// ------------------------------------------------------------------------ merge
+template <int D>
+__device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
+{
+    const int BH = p.batch * p.hkv;
+    const int Mtot = p.G * p.Bt;
+    const size_t rows = (size_t)BH * Mtot;
+    const int d4 = (int)(gid % (D / 4));
+    const size_t row = gid / (D / 4);
+    if (row >= rows) return;
+    float mx = -INFINITY;
+    for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, p.part_ml[(size_t)s * rows + row].x);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float L = 0.f;
+    for (int s = 0; s < p.splits; ++s) {
+        const float2 ml = p.part_ml[(size_t)s * rows + row];
+        const float w = ml.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml.x - mx);
+        const float4 o = *reinterpret_cast<const float4 *>(p.part_o + ((size_t)s * rows + row) * D + 4 * d4);
+        acc.x += w * o.x;
+        acc.y += w * o.y;
+        acc.z += w * o.z;
+        acc.w += w * o.w;
+        L += w * ml.y;
+    }
+    const float inv = 1.f / L;
+    const int bh = (int)(row / Mtot), m = (int)(row % Mtot);
+    const int b = bh / p.hkv, kvh = bh % p.hkv;
+    const int g = m / p.Bt, j = m % p.Bt;
+    bf16x4 o;
+    o[0] = (__bf16)(acc.x * inv);
+    o[1] = (__bf16)(acc.y * inv);
+    o[2] = (__bf16)(acc.z * inv);
+    o[3] = (__bf16)(acc.w * inv);
+    *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
+}
+
+template <int D>
+__global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __shared__ PostShared sh;
+    const int BH = p.batch * p.hkv;
+    const int n_score = p.do_score ? BH * p.score_chunks : 0;
+    if ((int)blockIdx.x >= n_score) {
+        merge_rows<D>(p, (size_t)(blockIdx.x - n_score) * POST_THREADS + threadIdx.x);
+        return;
+    }
+    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
+    const int row0 = chunk * SCORE_ROWS, row1 = min(p.n, row0 + SCORE_ROWS);
+    score_rows<D>(p, sh, bh, row0, row1);
+    if (!p.do_evict) return;
+    // the workgroup that completes a head's scores last selects and compacts that head
+    __threadfence();  // this thread's scores and histogram adds are visible device-wide ...
+    __syncthreads();  // ... before the workgroup announces itself
+    if (threadIdx.x == 0) {
+        const uint32_t old = atomicAdd(p.arrive + bh, 1u);
+        const bool last = old == (uint32_t)p.score_chunks - 1;
+        if (last) p.arrive[bh] = 0;  // left clean for the next step
+        sh.is_last = last;
+    }
+    __syncthreads();
+    if (!sh.is_last) return;
+    __threadfence();  // the other workgroups' results are visible to every thread here
+    select_and_compact<D>(p, sh, reinterpret_cast<uint32_t *>(smem_raw), bh);
+}
+
+// ------------------------------------------------------------- ordered compaction
 // Stable in-place shift.  One workgroup per (sequence, KV head) walks the rows in
 // ascending chunks: a chunk's surviving rows are read into LDS, then written to
 // their destinations, which lie at or before their sources, so nothing unread is
 // overwritten.
-__global__ __launch_bounds__(1024) void compact_ordered_kernel(EvictParams p)
+__global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const int bh = blockIdx.x, tid = threadIdx.x;
@@ -397,6 +521,66 @@ __global__ __launch_bounds__(1024) void compact_ordered_kernel(EvictParams p)
     }
 }
 
+// --------------------------------------------------- key sum from scratch (cache load)
+// Column sums of CHUNK_ROWS rows in double; unit keys for anchor mode 1.
+template <int D>
+__global__ __launch_bounds__(256) void ksum_partial_kernel(StepParams p, double *partials, int nchunks)
+{
+    constexpr int UPR = D / 8;
+    constexpr int RL = 256 / UPR;
+    __shared__ double red[RL][D];
+    const int bh = blockIdx.y, chunk = blockIdx.x;
+    const int u = threadIdx.x % UPR, rl = threadIdx.x / UPR;
+    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    double acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    const int r0 = chunk * CHUNK_ROWS;
+    for (int r = rl; r < CHUNK_ROWS; r += RL) {
+        const int row = r0 + r;
+        double x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = 0.0;
+        if (row < p.n) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = bf16_lo(w[i]);
+                x[2 * i + 1] = bf16_hi(w[i]);
+            }
+        }
+        double inv = 1.0;
+        if (p.anchor_mode == 1) {
+            double k2 = 0.0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
+#pragma unroll
+            for (int m = 1; m < UPR; m <<= 1) k2 += shfl_xor_f64(k2, m);
+            const double nk = sqrt(k2);
+            inv = nk > 0.0 ? 1.0 / nk : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[rl][u * 8 + i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < D) {
+        double s = 0.0;
+        for (int r = 0; r < RL; ++r) s += red[r][threadIdx.x];
+        partials[((size_t)bh * nchunks + chunk) * D + threadIdx.x] = s;
+    }
+}
+
+__global__ void ksum_final_kernel(const double *partials, double *ksum, int nchunks, int D)
+{
+    const int bh = blockIdx.x, c = threadIdx.x;
+    if (c >= D) return;
+    double s = 0.0;
+    for (int k = 0; k < nchunks; ++k) s += partials[((size_t)bh * nchunks + k) * D + c];
+    ksum[(size_t)bh * D + c] = s;
+}
+
 // ------------------------------------------------------------------ small helpers
 __global__ void zero_words_kernel(int32_t *p, size_t n)
 {
@@ -426,67 +610,52 @@ __global__ void load_pos_kernel(const int32_t *src, int32_t *dst, int cap, int l
     }
 }
 
-__global__ void copy_scores_kernel(const float *src, float *dst, int cap, int n)
-{
-    const int bh = blockIdx.y;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) dst[(size_t)bh * n + i] = src[(size_t)bh * cap + i];
-}
-
 // ---------------------------------------------------------------------- launchers
-hipError_t launch_append(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k, uint16_t *v,
-                         int32_t *pos, int BH, int cap, int D, int len, int Bt, int32_t pos0,
-                         hipStream_t s)
+size_t post_lds_bytes(int n, int /*N*/) { return (size_t)((n + 31) / 32) * 4 + 16; }
+
+static size_t compact_lds_bytes(int D) { return (size_t)2 * CHUNK_ROWS * (D / 8) * 16; }
+
+hipError_t configure_main_kernels();
+
+hipError_t configure_kernels()
 {
-    const int units = Bt * (D / 8);
-    hipLaunchKernelGGL(append_kernel, dim3((units + 255) / 256, BH), dim3(256), 0, s, k_new, v_new, k, v, pos,
-                       cap, D, len, Bt, pos0);
-    return hipGetLastError();
+    hipError_t e = configure_main_kernels();
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(compact_ordered_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)compact_lds_bytes(128));
+    return e;
 }
 
-hipError_t launch_anchor(const EvictParams &p, hipStream_t s)
+hipError_t launch_step_post(const StepParams &p, hipStream_t s)
 {
-    dim3 grid(p.nchunks, p.BH);
-    if (p.D == 128) hipLaunchKernelGGL((anchor_kernel<128>), grid, dim3(256), 0, s, p);
-    else if (p.D == 64) hipLaunchKernelGGL((anchor_kernel<64>), grid, dim3(256), 0, s, p);
+    const int n_score = p.do_score ? p.batch * p.hkv * p.score_chunks : 0;
+    const int grid = n_score + p.merge_wgs;
+    if (grid == 0) return hipSuccess;
+    const size_t lds = post_lds_bytes(p.n, p.N);
+    if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 64) hipLaunchKernelGGL((step_post_kernel<64>), dim3(grid), dim3(POST_THREADS), lds, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_score(const EvictParams &p, hipStream_t s)
+hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s)
 {
-    dim3 grid(p.nchunks, p.BH);
-    if (p.D == 128) hipLaunchKernelGGL((score_kernel<128>), grid, dim3(256), 0, s, p);
-    else if (p.D == 64) hipLaunchKernelGGL((score_kernel<64>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(compact_ordered_kernel, dim3(p.batch * p.hkv), dim3(1024), compact_lds_bytes(p.D), s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s)
+{
+    const int BH = p.batch * p.hkv;
+    if (p.n == 0) return launch_zero_words(reinterpret_cast<int32_t *>(p.ksum), (size_t)BH * p.D * 2, s);
+    const int nchunks = (p.n + CHUNK_ROWS - 1) / CHUNK_ROWS;
+    dim3 grid(nchunks, BH);
+    if (p.D == 128) hipLaunchKernelGGL((ksum_partial_kernel<128>), grid, dim3(256), 0, s, p, partials, nchunks);
+    else if (p.D == 64) hipLaunchKernelGGL((ksum_partial_kernel<64>), grid, dim3(256), 0, s, p, partials, nchunks);
     else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-size_t select_lds_bytes(int n, int N)
-{
-    const int E = n - N > 0 ? n - N : 0;
-    return (size_t)n * 4 + (size_t)E * 8 + 16;
-}
-
-size_t compact_lds_bytes(int D) { return (size_t)2 * CHUNK_ROWS * (D / 8) * 16; }
-
-hipError_t launch_select(const EvictParams &p, hipStream_t s)
-{
-    const size_t lds = select_lds_bytes(p.n, p.N);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(select_kernel, dim3(p.BH), dim3(SELECT_THREADS), lds, s, p);
-    return hipGetLastError();
-}
-
-hipError_t launch_compact_ordered(const EvictParams &p, hipStream_t s)
-{
-    const size_t lds = compact_lds_bytes(p.D);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(compact_ordered_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(compact_ordered_kernel, dim3(p.BH), dim3(1024), lds, s, p);
+    hipLaunchKernelGGL(ksum_final_kernel, dim3(BH), dim3(128), 0, s, partials, p.ksum, nchunks, p.D);
     return hipGetLastError();
 }
 
@@ -512,12 +681,6 @@ hipError_t launch_load_pos(const int32_t *src, int32_t *dst, int BH, int cap, in
     if (len == 0) return hipSuccess;
     hipLaunchKernelGGL(load_pos_kernel, dim3((len + 255) / 256, BH), dim3(256), 0, s, src, dst, cap, len,
                        to_cache);
-    return hipGetLastError();
-}
-
-hipError_t launch_copy_scores(const float *src, float *dst, int BH, int cap, int n, hipStream_t s)
-{
-    hipLaunchKernelGGL(copy_scores_kernel, dim3((n + 255) / 256, BH), dim3(256), 0, s, src, dst, cap, n);
     return hipGetLastError();
 }
 

@@ -1,59 +1,70 @@
 // Internal launcher interface between the C-ABI host layer and the gfx950 kernels.
+//
+// One block step is two launches:
+//   step_main  append (Eq. 5) + split-KV flash attention partials (Eq. 1-2)
+//              + running key sum S += sum of the block's keys (the anchor is S / n)
+//   step_post  merge of the attention partials  ||  cosine score of every row,
+//              then, in the workgroup that finishes a head's scores last, the
+//              selection of the rows to evict and the compaction (Eq. 6-7)
+// plus, for the ORDERED layout only, a third launch that shifts rows in place.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace kd {
 
-constexpr int TILE_KEYS = 64;      // keys per attention K/V tile
-constexpr int CHUNK_ROWS = 128;    // rows per workgroup in the anchor / score passes
-constexpr int SELECT_THREADS = 1024;
+constexpr int TILE_KEYS = 64;       // keys per attention K/V tile
+constexpr int POST_THREADS = 1024;  // workgroup size of step_post
+constexpr int SCORE_ROWS = 512;     // rows scored per workgroup in step_post
+constexpr int HIST_BINS = 4096;     // score histogram resolution (bins over [-1, 1])
+constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
+constexpr int MAX_CAP = 32768;      // budget_N + block_B limit (selection bitmaps, ownership)
 
 // status bits kernels may raise (device word in the metadata buffer)
-constexpr int STATUS_SELECT_COUNT = 1;   // selection evicted a number of rows other than n - N
-constexpr int STATUS_WAIT_EXPIRED = 2;   // a bounded wait ran out
+constexpr int STATUS_SELECT_COUNT = 1;  // selection evicted a number of rows other than n - N
 
-struct AttnParams {
-    const uint16_t *q;        // [batch][hq][Bt][D]
-    const uint16_t *k, *v;    // caches [batch][hkv][cap][D], block already appended
-    uint16_t *out;            // [batch][hq][Bt][D]
-    float *part_o;            // [splits][BH * G * Bt][D]   unnormalised partial outputs
-    float2 *part_ml;          // [splits][BH * G * Bt]      (running max in log2 units, row sum)
-    int batch, hq, hkv, G, Bt, len, n, cap;
-    int splits, mtiles, ntiles;
-    float scale_log2e;        // softmax scale * log2(e)
-};
-
-struct EvictParams {
-    uint16_t *k, *v;          // caches
-    int32_t *pos;             // [BH][cap]
-    double *anchor_part;      // [BH][nchunks][D]
-    float *scores;            // [BH][cap]
-    int32_t *dstmap;          // [BH][cap]   ORDERED layout: destination row or -1
-    int32_t *status;          // device status word
-    int BH, cap, D, n, N, nchunks;
+struct StepParams {
+    // tensors of the call
+    const uint16_t *q;               // [batch][hq][Bt][D]
+    const uint16_t *k_new, *v_new;   // [batch][hkv][Bt][D]
+    uint16_t *out;                   // [batch][hq][Bt][D]
+    float *scores_out;               // nullable [BH][n]
+    // caller-owned state
+    uint16_t *k, *v;                 // caches [BH][cap][D]
+    int32_t *pos;                    // [BH][cap] token position of every row
+    double *ksum;                    // [BH][D] running sum of the (raw or unit) keys in the cache
+    int32_t *status;
+    // scratch
+    float *part_o;                   // [splits][BH * G * Bt][D] unnormalised partial outputs
+    float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
+    float *scores;                   // [BH][cap]
+    uint32_t *hist;                  // [BH][HIST_BINS] zero between steps
+    uint32_t *arrive;                // [BH] zero between steps
+    int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
+    int32_t *lists;                  // [BH][3 * B] evicted rows | holes | movers of this step
+    // sizes
+    int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
+    int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
+    int score_chunks;                // score workgroups per head in step_post
+    int merge_wgs;                   // merge workgroups in step_post (0 when splits == 1)
+    int do_score, do_evict;
     int anchor_mode, layout, window_W;
-    int32_t window_pos_min;   // rows with pos >= this are exempt when window_W > 0
+    int32_t pos0, window_pos_min;
+    float scale_log2e;
     double eps;
 };
 
-hipError_t launch_append(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k, uint16_t *v,
-                         int32_t *pos, int BH, int cap, int D, int len, int Bt, int32_t pos0,
-                         hipStream_t s);
-hipError_t launch_attention(const AttnParams &p, int D, int NQ, hipStream_t s);
-hipError_t launch_merge(const AttnParams &p, int D, hipStream_t s);
-hipError_t launch_anchor(const EvictParams &p, hipStream_t s);
-hipError_t launch_score(const EvictParams &p, hipStream_t s);
-hipError_t launch_select(const EvictParams &p, hipStream_t s);
-hipError_t launch_compact_ordered(const EvictParams &p, hipStream_t s);
+hipError_t configure_kernels();      // one-time function attributes (dynamic LDS sizes)
+hipError_t launch_step_main(const StepParams &p, hipStream_t s);
+hipError_t launch_step_post(const StepParams &p, hipStream_t s);
+hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s);
+hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s);
 hipError_t launch_zero_words(int32_t *p, size_t nwords, hipStream_t s);
 hipError_t launch_load_rows(const uint16_t *src, uint16_t *dst, int BH, int cap, int D, int len,
                             hipStream_t s);
 hipError_t launch_load_pos(const int32_t *src, int32_t *dst, int BH, int cap, int len, int to_cache,
                            hipStream_t s);
-hipError_t launch_copy_scores(const float *src, float *dst, int BH, int cap, int n, hipStream_t s);
 
-size_t select_lds_bytes(int n, int N);
-size_t compact_lds_bytes(int D);
+size_t post_lds_bytes(int n, int N);
 
 }  // namespace kd

@@ -28,9 +28,9 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
     size_t k_bytes, meta_bytes, scratch_bytes;
-    size_t off_pos, off_status;                                              // in meta
-    size_t off_part_o, off_part_ml, off_anchor, off_scores, off_dstmap;      // in scratch
-    int cap, max_chunks, max_part_rows;
+    size_t off_pos, off_ksum, off_hist, off_arrive, off_status;                       // in meta
+    size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part;  // in scratch
+    int cap, max_part_rows;
 };
 
 constexpr int kTargetWorkgroups = 512;
@@ -42,8 +42,8 @@ int check_config(const keydiff_config_t *c)
         return fail(KEYDIFF_ESHAPE, "batch, head counts, budget_N and block_B must be positive");
     if (c->n_q_heads % c->n_kv_heads) return fail(KEYDIFF_ESHAPE, "n_q_heads must be a multiple of n_kv_heads");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(KEYDIFF_ESHAPE, "head_dim must be 64 or 128");
-    if ((long)c->budget_N + c->block_B > 32768) return fail(KEYDIFF_ESHAPE, "budget_N + block_B must not exceed 32768");
-    if (c->block_B > 16384) return fail(KEYDIFF_ESHAPE, "block_B must not exceed 16384");
+    if ((long)c->budget_N + c->block_B > kd::MAX_CAP)
+        return fail(KEYDIFF_ESHAPE, "budget_N + block_B must not exceed %d", kd::MAX_CAP);
     if ((long)c->batch * c->n_kv_heads > 65535) return fail(KEYDIFF_ESHAPE, "batch * n_kv_heads must not exceed 65535");
     if (c->anchor_mode != KEYDIFF_ANCHOR_MEAN_KEY && c->anchor_mode != KEYDIFF_ANCHOR_MEAN_UNIT_KEY)
         return fail(KEYDIFF_EINVAL, "anchor_mode must be a KEYDIFF_ANCHOR_* value");
@@ -62,21 +62,26 @@ Layout make_layout(const keydiff_config_t *c)
     const int D = c->head_dim;
     L.cap = c->budget_N + c->block_B;
     L.k_bytes = align256(BH * L.cap * D * 2);
-    L.off_pos = 0;
-    L.off_status = align256(BH * L.cap * 4);
-    L.meta_bytes = L.off_status + 256;
-    L.max_chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
-    // split-KV partial rows: splits * BH * G * Bt never exceeds this (see pick_splits)
+    size_t off = 0;
+    L.off_pos = off;     off += align256(BH * L.cap * 4);
+    L.off_ksum = off;    off += align256(BH * D * 8);
+    L.off_hist = off;    off += align256(BH * kd::HIST_BINS * 4);
+    L.off_arrive = off;  off += align256(BH * 4);
+    L.off_status = off;  off += 256;
+    L.meta_bytes = off;
+    // split-KV partial rows: splits * BH * G * Bt never exceeds this (see plan_attention)
     const int max_mtiles = (G * c->block_B + 127) / 128;
     const size_t by_tiles = (kTargetWorkgroups + BH * max_mtiles + BH) * 256;
     const size_t by_rows = (kTargetWorkgroups + 2 * BH) * (size_t)G * c->block_B;
     L.max_part_rows = (int)(by_tiles < by_rows ? by_tiles : by_rows);
-    size_t off = 0;
-    L.off_part_o = off;   off += align256((size_t)L.max_part_rows * D * 4);
-    L.off_part_ml = off;  off += align256((size_t)L.max_part_rows * 8);
-    L.off_anchor = off;   off += align256(BH * L.max_chunks * D * 8);
-    L.off_scores = off;   off += align256(BH * L.cap * 4);
-    L.off_dstmap = off;   off += align256(BH * L.cap * 4);
+    const size_t chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
+    off = 0;
+    L.off_part_o = off;     off += align256((size_t)L.max_part_rows * D * 4);
+    L.off_part_ml = off;    off += align256((size_t)L.max_part_rows * 8);
+    L.off_scores = off;     off += align256(BH * L.cap * 4);
+    L.off_dstmap = off;     off += align256(BH * L.cap * 4);
+    L.off_lists = off;      off += align256(BH * 3 * (size_t)c->block_B * 4);
+    L.off_ksum_part = off;  off += align256(BH * chunks * D * 8);
     L.scratch_bytes = off;
     return L;
 }
@@ -133,30 +138,6 @@ struct ProfScope {
     }
 };
 
-struct AttnPlan {
-    int NQ, mtiles, ntiles, splits;
-};
-
-AttnPlan plan_attention(const keydiff_cache *c, int Bt, int n)
-{
-    AttnPlan a;
-    const int BH = c->cfg.batch * c->cfg.n_kv_heads;
-    const int G = c->cfg.n_q_heads / c->cfg.n_kv_heads;
-    const int Mtot = G * Bt;
-    a.NQ = (Mtot % 256 == 0 || Mtot >= 512) ? 2 : 1;
-    const int TM = 128 * a.NQ;
-    a.mtiles = (Mtot + TM - 1) / TM;
-    a.ntiles = (n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
-    const int target = a.NQ == 2 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
-    int splits = (target + BH * a.mtiles - 1) / (BH * a.mtiles);
-    if (splits > a.ntiles) splits = a.ntiles;
-    if (splits < 1) splits = 1;
-    // partial rows must fit the scratch sized at init
-    while (splits > 1 && (long)splits * BH * Mtot > c->L.max_part_rows) --splits;
-    a.splits = splits;
-    return a;
-}
-
 int hip_fail(hipError_t e, const char *what)
 {
     return fail(KEYDIFF_EHIP, "%s: %s", what, hipGetErrorString(e));
@@ -168,42 +149,60 @@ int hip_fail(hipError_t e, const char *what)
         if (e__ != hipSuccess) return hip_fail(e__, what);     \
     } while (0)
 
-kd::EvictParams evict_params(const keydiff_cache *c, int n)
+// Pointers and sizes every kernel of a step shares; the attention plan is filled in by plan_attention.
+kd::StepParams base_params(const keydiff_cache *c, int n)
 {
-    kd::EvictParams p{};
+    kd::StepParams p{};
+    const keydiff_config_t &cf = c->cfg;
     p.k = c->k;
     p.v = c->v;
     p.pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
-    p.anchor_part = reinterpret_cast<double *>(c->scratch + c->L.off_anchor);
+    p.ksum = reinterpret_cast<double *>(c->meta + c->L.off_ksum);
+    p.hist = reinterpret_cast<uint32_t *>(c->meta + c->L.off_hist);
+    p.arrive = reinterpret_cast<uint32_t *>(c->meta + c->L.off_arrive);
+    p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
+    p.part_o = reinterpret_cast<float *>(c->scratch + c->L.off_part_o);
+    p.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
     p.scores = reinterpret_cast<float *>(c->scratch + c->L.off_scores);
     p.dstmap = reinterpret_cast<int32_t *>(c->scratch + c->L.off_dstmap);
-    p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
-    p.BH = c->cfg.batch * c->cfg.n_kv_heads;
-    p.cap = c->L.cap;
-    p.D = c->cfg.head_dim;
+    p.lists = reinterpret_cast<int32_t *>(c->scratch + c->L.off_lists);
+    p.batch = cf.batch;
+    p.hq = cf.n_q_heads;
+    p.hkv = cf.n_kv_heads;
+    p.G = cf.n_q_heads / cf.n_kv_heads;
+    p.D = cf.head_dim;
     p.n = n;
-    p.N = c->cfg.budget_N;
-    p.nchunks = (n + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
-    p.anchor_mode = c->cfg.anchor_mode;
-    p.layout = c->cfg.layout;
-    p.window_W = c->cfg.window_W;
-    p.window_pos_min = 0;
+    p.N = cf.budget_N;
+    p.B = cf.block_B;
+    p.cap = c->L.cap;
+    p.splits = 1;
+    p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
+    p.anchor_mode = cf.anchor_mode;
+    p.layout = cf.layout;
+    p.window_W = cf.window_W;
+    p.scale_log2e = c->scale_log2e;
     p.eps = c->eps;
     return p;
 }
 
-int score_rows(keydiff_cache *c, int n, hipStream_t s)
+// M tiling (GQA-packed rows per KV head) and the number of key splits that fills the chip
+void plan_attention(const keydiff_cache *c, kd::StepParams &p)
 {
-    kd::EvictParams p = evict_params(c, n);
-    {
-        ProfScope ps(c, KEYDIFF_K_ANCHOR, s);
-        KD_LAUNCH(kd::launch_anchor(p, s), "anchor kernel");
-    }
-    {
-        ProfScope ps(c, KEYDIFF_K_SCORE, s);
-        KD_LAUNCH(kd::launch_score(p, s), "score kernel");
-    }
-    return KEYDIFF_OK;
+    const int BH = p.batch * p.hkv;
+    const int Mtot = p.G * p.Bt;
+    p.NW = (Mtot % 256 == 0 || Mtot > 512) ? 8 : 4;
+    const int TM = 32 * p.NW;
+    p.mtiles = (Mtot + TM - 1) / TM;
+    p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
+    const int target = p.NW == 8 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+    int splits = (target + BH * p.mtiles - 1) / (BH * p.mtiles);
+    if (splits > p.ntiles) splits = p.ntiles;
+    if (splits < 1) splits = 1;
+    // partial rows must fit the scratch sized at init
+    while (splits > 1 && (long)splits * BH * Mtot > c->L.max_part_rows) --splits;
+    p.splits = splits;
+    const size_t merge_threads = (size_t)BH * Mtot * (p.D / 4);
+    p.merge_wgs = splits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
@@ -251,11 +250,14 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->contiguous = true;
     c->next_pos = -1;
     c->profiling = false;
-    hipError_t e = kd::launch_zero_words(reinterpret_cast<int32_t *>(meta), c->L.meta_bytes / 4,
-                                         static_cast<hipStream_t>(stream));
+    static hipError_t configured = kd::configure_kernels();  // once per process
+    hipError_t e = configured;
+    if (e == hipSuccess)
+        e = kd::launch_zero_words(reinterpret_cast<int32_t *>(meta), c->L.meta_bytes / 4,
+                                  static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
         delete c;
-        return hip_fail(e, "clearing metadata");
+        return hip_fail(e, "kernel setup / clearing metadata");
     }
     *out = c;
     return KEYDIFF_OK;
@@ -295,62 +297,33 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
     if (cf.window_W > 0 && n > N && !contiguous)
         return fail(KEYDIFF_ESTATE, "the sliding window needs consecutive token positions across calls");
 
-    int32_t *pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
-    {
-        ProfScope ps(c, KEYDIFF_K_APPEND, s);
-        KD_LAUNCH(kd::launch_append(static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), c->k,
-                                    c->v, pos, BH, c->L.cap, D, len, Bt, (int32_t)pos0, s),
-                  "append kernel");
-    }
-
-    const AttnPlan plan = plan_attention(c, Bt, n);
-    kd::AttnParams ap{};
-    ap.q = static_cast<const uint16_t *>(q);
-    ap.k = c->k;
-    ap.v = c->v;
-    ap.out = static_cast<uint16_t *>(out);
-    ap.part_o = reinterpret_cast<float *>(c->scratch + c->L.off_part_o);
-    ap.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
-    ap.batch = cf.batch;
-    ap.hq = cf.n_q_heads;
-    ap.hkv = cf.n_kv_heads;
-    ap.G = cf.n_q_heads / cf.n_kv_heads;
-    ap.Bt = Bt;
-    ap.len = len;
-    ap.n = n;
-    ap.cap = c->L.cap;
-    ap.splits = plan.splits;
-    ap.mtiles = plan.mtiles;
-    ap.ntiles = plan.ntiles;
-    ap.scale_log2e = c->scale_log2e;
-    {
-        ProfScope ps(c, KEYDIFF_K_ATTENTION, s);
-        KD_LAUNCH(kd::launch_attention(ap, D, plan.NQ, s), "attention kernel");
-    }
-    if (plan.splits > 1) {
-        ProfScope ps(c, KEYDIFF_K_MERGE, s);
-        KD_LAUNCH(kd::launch_merge(ap, D, s), "merge kernel");
-    }
-
     const bool evict = n > N;
-    if (evict || scores_out) {
-        if (int rc = score_rows(c, n, s)) return rc;
-        if (scores_out)
-            KD_LAUNCH(kd::launch_copy_scores(reinterpret_cast<const float *>(c->scratch + c->L.off_scores), scores_out,
-                                             BH, c->L.cap, n, s),
-                      "score copy");
+    kd::StepParams p = base_params(c, n);
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.out = static_cast<uint16_t *>(out);
+    p.scores_out = scores_out;
+    p.Bt = Bt;
+    p.len = len;
+    p.pos0 = (int32_t)pos0;
+    p.do_evict = evict;
+    p.do_score = evict || scores_out != nullptr;
+    if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
+    plan_attention(c, p);
+    (void)BH;
+    (void)D;
+    {
+        ProfScope ps(c, KEYDIFF_K_MAIN, s);
+        KD_LAUNCH(kd::launch_step_main(p, s), "step_main kernel");
     }
-    if (evict) {
-        kd::EvictParams p = evict_params(c, n);
-        if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
-        {
-            ProfScope ps(c, KEYDIFF_K_SELECT, s);
-            KD_LAUNCH(kd::launch_select(p, s), "select kernel");
-        }
-        if (cf.layout == KEYDIFF_LAYOUT_ORDERED) {
-            ProfScope ps(c, KEYDIFF_K_COMPACT, s);
-            KD_LAUNCH(kd::launch_compact_ordered(p, s), "compaction kernel");
-        }
+    if (p.do_score || p.merge_wgs > 0) {
+        ProfScope ps(c, KEYDIFF_K_POST, s);
+        KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
+    }
+    if (evict && cf.layout == KEYDIFF_LAYOUT_ORDERED) {
+        ProfScope ps(c, KEYDIFF_K_COMPACT, s);
+        KD_LAUNCH(kd::launch_compact_ordered(p, s), "ordered compaction kernel");
     }
     c->len = evict ? N : n;
     c->contiguous = contiguous;
@@ -371,10 +344,13 @@ int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
     if (!scores_out) return fail(KEYDIFF_EINVAL, "null pointer");
     keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch and profiling events only
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (int rc = score_rows(c, c->len, s)) return rc;
-    KD_LAUNCH(kd::launch_copy_scores(reinterpret_cast<const float *>(c->scratch + c->L.off_scores), scores_out,
-                                     c->cfg.batch * c->cfg.n_kv_heads, c->L.cap, c->len, s),
-              "score copy");
+    kd::StepParams p = base_params(c, c->len);
+    p.scores_out = scores_out;
+    p.do_score = 1;
+    p.do_evict = 0;
+    p.merge_wgs = 0;
+    ProfScope ps(c, KEYDIFF_K_POST, s);
+    KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (scores)");
     return KEYDIFF_OK;
 }
 
@@ -401,6 +377,12 @@ int keydiff_cache_load(keydiff_cache_t *c, const void *k, const void *v, const i
     KD_LAUNCH(kd::launch_load_rows(static_cast<const uint16_t *>(v), c->v, BH, c->L.cap, D, len, s), "cache load");
     KD_LAUNCH(kd::launch_load_pos(pos, reinterpret_cast<int32_t *>(c->meta + c->L.off_pos), BH, c->L.cap, len, 1, s),
               "cache load");
+    {
+        kd::StepParams p = base_params(c, len);
+        ProfScope ps(c, KEYDIFF_K_AUX, s);
+        KD_LAUNCH(kd::launch_ksum_rebuild(p, reinterpret_cast<double *>(c->scratch + c->L.off_ksum_part), s),
+                  "key sum rebuild");
+    }
     c->len = len;
     c->contiguous = false;  // the loaded positions are the caller's
     c->next_pos = -1;
