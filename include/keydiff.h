@@ -149,10 +149,11 @@ KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *stat
  * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
 enum {
     KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key-sum update          */
-    KEYDIFF_K_POST = 1,    /* step_post: partial merge || score, selection, compaction         */
-    KEYDIFF_K_COMPACT = 2, /* stable in-place row shift (ORDERED layout only)                  */
-    KEYDIFF_K_AUX = 3,     /* cache load helpers                                               */
-    KEYDIFF_NKERNELS = 4
+    KEYDIFF_K_SCORE = 1,   /* step_score: cosine scores + per-head histogram                   */
+    KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction             */
+    KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
+    KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */
+    KEYDIFF_NKERNELS = 5
 };
 KEYDIFF_API int keydiff_profile_enable(keydiff_cache_t *cache, int32_t enable);
 KEYDIFF_API int keydiff_profile_read(keydiff_cache_t *cache, float *ms_out, int32_t *launches_out);

@@ -1,5 +1,5 @@
-// step_post: cosine score, selection and compaction (Eq. 6-7, appendix "FLOP count
-// of KeyDiff"), running next to the log-sum-exp merge of the attention partials.
+// step_score and step_post: cosine score (appendix "FLOP count of KeyDiff"), then selection
+// and compaction (Eq. 6-7) running next to the log-sum-exp merge of the attention partials.
 //
 // The score that decides an eviction is IEEE double arithmetic on the bf16 data,
 // rounded once to float: s_i = mu.k_i / max(|mu||k_i|, eps) with mu = ksum / n.
@@ -7,11 +7,11 @@
 // retained set does not depend on summation order beyond the last bit of a double.
 //
 // Selection.  Every score also lands in a 4096-bin histogram of its head (a
-// monotone map of the float).  The workgroup that finishes a head's scores last
-// (fence + counter, nobody waits) scans the histogram for the bin that holds the
-// E-th largest score, evicts everything above that bin and ranks the few rows
-// inside it exactly by (score bits, position): equal scores keep the lower
-// position.  It then compacts the cache and takes the evicted keys out of ksum.
+// monotone map of the float).  In the next launch one workgroup per head scans the
+// histogram for the bin that holds the E-th largest score, evicts everything above
+// that bin and ranks the few rows inside it exactly by (score bits, position):
+// equal scores keep the lower position.  It then compacts the cache and takes the
+// evicted keys out of ksum.
 #include "kd_kernels.h"
 
 namespace kd {
@@ -20,10 +20,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
+constexpr int NWAVES = POST_THREADS / 64;
 
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
-__device__ __forceinline__ double bf16_to_f64(uint16_t b) { return (double)__uint_as_float((uint32_t)b << 16); }
 
 __device__ __forceinline__ double shfl_xor_f64(double x, int m)
 {
@@ -31,6 +31,29 @@ __device__ __forceinline__ double shfl_xor_f64(double x, int m)
     lo = __shfl_xor(lo, m);
     hi = __shfl_xor(hi, m);
     return __hiloint2double(hi, lo);
+}
+
+// x + (x of another lane of the same 16-lane row), by a DPP control word
+template <int CTRL>
+__device__ __forceinline__ double dpp_add_f64(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+    return x + __hiloint2double(hi, lo);
+}
+
+// sum over the LANES (8 or 16) consecutive lanes that share one key row; every lane gets the
+// total.  Quad exchanges, then mirrors inside the half row and the row: each step pairs a lane
+// with one that holds the sum of a different, equally sized group.
+template <int LANES>
+__device__ __forceinline__ double row_allreduce_f64(double x)
+{
+    static_assert(LANES == 8 || LANES == 16, "a key row spans 8 or 16 lanes");
+    x = dpp_add_f64<0xB1>(x);                    // quad_perm [1,0,3,2]
+    x = dpp_add_f64<0x4E>(x);                    // quad_perm [2,3,0,1]
+    x = dpp_add_f64<0x141>(x);                   // row_half_mirror: lane i <-> 7 - i
+    if (LANES == 16) x = dpp_add_f64<0x140>(x);  // row_mirror: lane i <-> 15 - i
+    return x;
 }
 
 // float -> unsigned key with the same order
@@ -49,18 +72,25 @@ __device__ __forceinline__ int score_bin(float s)
 
 struct PostShared {
     double mu[128];
-    double red[16];
-    double colsum[POST_THREADS];
-    uint32_t wave_tot[16];
+    double red[NWAVES];
+    uint32_t wave_tot[NWAVES];
     uint32_t radix_hist[256];
     uint32_t sel_bin, sel_rank, sel_cnt;
-    int tb;               // threshold bin
-    uint32_t need;        // rows to evict from the threshold bin
+    int tb;           // threshold bin
+    uint32_t need;    // rows to evict from the threshold bin
     uint32_t ncand;
-    uint32_t is_last;
-    uint32_t cand_slot[CAND_MAX];
-    uint32_t cand_key[CAND_MAX];
-    int32_t cand_pos[CAND_MAX];
+    union {
+        struct {  // scoring: per-wave staging of (dot, |k|^2) so that sqrt and divide run on full waves
+            double dot[NWAVES][64];
+            double k2[NWAVES][64];
+        } fin;
+        struct {  // selection
+            uint32_t cand_slot[CAND_MAX];
+            uint32_t cand_key[CAND_MAX];
+            int32_t cand_pos[CAND_MAX];
+            double colsum[NWAVES][128];
+        } sel;
+    };
 };
 
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
@@ -76,8 +106,8 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
     uint32_t base = 0, tot = 0;
-    const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) {
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
         const uint32_t t = wave_tot[w];
         if (w < wave) base += t;
         tot += t;
@@ -87,13 +117,15 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
 }
 
 // ------------------------------------------------------------------------ scores
-// Rows [row0, row1) of head bh; D/8 lanes per row, each lane one 16-byte unit.
+// Rows [row0, row1) of head bh.  D/8 lanes share a row (one 16-byte unit each); a
+// wave takes 64 consecutive rows per round, 64 / (D/8) ... rows per pass, stages
+// (mu.k, |k|^2) of each row in LDS and then lane i finishes row i of the round.
 template <int D>
 __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, int bh, int row0, int row1)
 {
     constexpr int UPR = D / 8;
-    constexpr int RPP = POST_THREADS / UPR;  // rows per pass
-    const int tid = threadIdx.x;
+    constexpr int RPW = 64 / UPR;  // rows per wave per pass
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // anchor = ksum / n (Method, "Efficient Variant"); |mu| by a fixed-shape reduction
     double m = 0.0;
     if (tid < D) {
@@ -103,40 +135,52 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
     double sq = m * m;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) sq += shfl_xor_f64(sq, off);
-    if ((tid & 63) == 0) sh.red[tid >> 6] = sq;
+    if (lane == 0) sh.red[wave] = sq;
     __syncthreads();
     double mu2 = 0.0;
 #pragma unroll
-    for (int w = 0; w < POST_THREADS / 64; ++w) mu2 += sh.red[w];
+    for (int w = 0; w < NWAVES; ++w) mu2 += sh.red[w];
     const double nmu = sqrt(mu2);
 
-    const int u = tid % UPR, rl = tid / UPR;
+    const int u = lane % UPR, rl = lane / UPR;
     const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     double mreg[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) mreg[i] = sh.mu[u * 8 + i];
-    const int npass = (row1 - row0 + RPP - 1) / RPP;  // uniform trip count: the shuffles need every lane
-    for (int ps = 0; ps < npass; ++ps) {
-        const int row = row0 + ps * RPP + rl;
-        double dot = 0.0, k2 = 0.0;
-        const bool live = row < row1;
-        if (live) {
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+    // a round = 64 rows per wave; rounds are spread over the waves
+    for (int base = row0 + wave * 64; base < row1; base += NWAVES * 64) {
+        u32x4 w[UPR];  // the round's loads are issued together
+#pragma unroll
+        for (int ps = 0; ps < UPR; ++ps) {
+            const int row = base + ps * RPW + rl;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (row < row1) z = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+            w[ps] = z;
+        }
+#pragma unroll
+        for (int ps = 0; ps < UPR; ++ps) {
+            double dot = 0.0, k2 = 0.0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const double a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+                const double a = bf16_lo(w[ps][i]), b = bf16_hi(w[ps][i]);
                 dot += mreg[2 * i] * a;
                 k2 += a * a;
                 dot += mreg[2 * i + 1] * b;
                 k2 += b * b;
             }
+            dot = row_allreduce_f64<UPR>(dot);
+            k2 = row_allreduce_f64<UPR>(k2);
+            if (u == 0) {
+                sh.fin.dot[wave][ps * RPW + rl] = dot;
+                sh.fin.k2[wave][ps * RPW + rl] = k2;
+            }
         }
-#pragma unroll
-        for (int mk = 1; mk < UPR; mk <<= 1) {
-            dot += shfl_xor_f64(dot, mk);
-            k2 += shfl_xor_f64(k2, mk);
-        }
-        if (u == 0 && live) {
+        // same wave wrote and reads: the LDS accesses of one wave complete in order; the fence only
+        // keeps the compiler from moving the reads above the writes
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const int row = base + lane;
+        if (row < row1) {
+            const double dot = sh.fin.dot[wave][lane], k2 = sh.fin.k2[wave][lane];
             double den = nmu * sqrt(k2);
             if (den < p.eps) den = p.eps;
             const float s = (float)(dot / den) + 0.0f;  // +0 folds -0 into +0
@@ -147,6 +191,7 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
                 if (!exempt) atomicAdd(p.hist + (size_t)bh * HIST_BINS + score_bin(s), 1u);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
 }
 
@@ -232,16 +277,17 @@ __device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const f
 }
 
 // ------------------------------------------------------------- select + compaction
+// `lists` holds three arrays of E row indices (evicted | holes | movers): in LDS when
+// they fit, else in the scratch buffer.
 template <int D>
-__device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int bh)
+__device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int32_t *lists, int bh)
 {
     constexpr int UPR = D / 8;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = p.n - p.N;
     const float *sc = p.scores + (size_t)bh * p.cap;
     int32_t *pos = p.pos + (size_t)bh * p.cap;
     uint32_t *hist = p.hist + (size_t)bh * HIST_BINS;
-    int32_t *lists = p.lists + (size_t)bh * 3 * p.B;  // scratch: evicted | holes | movers, E entries each
 
     // ---- 1. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
     const int nwords = (p.n + 31) / 32;
@@ -255,8 +301,9 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     uint32_t mine = 0;
     const int top = HIST_BINS - 1 - (HIST_BINS / POST_THREADS) * tid;
 #pragma unroll
+    for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) cnt[j] = hist[top - j];
+#pragma unroll
     for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
-        cnt[j] = hist[top - j];
         hist[top - j] = 0;  // left clean for the next step
         mine += cnt[j];
     }
@@ -279,18 +326,27 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     const uint32_t need = sh.need;
 
     // ---- 2. one pass over the scores: above the bin -> evicted, inside it -> candidate
-    for (int i = tid; i < p.n; i += POST_THREADS) {
-        const float s = sc[i];
-        const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
-        if (exempt) continue;
-        const int bin = score_bin(s);
-        if (bin > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
-        else if (bin == tb) {
-            const uint32_t c = atomicAdd(&sh.ncand, 1u);
-            if (c < CAND_MAX) {
-                sh.cand_slot[c] = (uint32_t)i;
-                sh.cand_key[c] = orderable(s);
-                sh.cand_pos[c] = pos[i];
+    for (int i0 = 0; i0 < p.n; i0 += 4 * POST_THREADS) {
+        float sv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = i0 + k * POST_THREADS + tid;
+            sv[k] = i < p.n ? sc[i] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = i0 + k * POST_THREADS + tid;
+            if (i >= p.n) continue;
+            if (p.window_W > 0 && pos[i] >= p.window_pos_min) continue;  // exempt
+            const int bin = score_bin(sv[k]);
+            if (bin > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
+            else if (bin == tb) {
+                const uint32_t c = atomicAdd(&sh.ncand, 1u);
+                if (c < CAND_MAX) {
+                    sh.sel.cand_slot[c] = (uint32_t)i;
+                    sh.sel.cand_key[c] = orderable(sv[k]);
+                    sh.sel.cand_pos[c] = pos[i];
+                }
             }
         }
     }
@@ -300,15 +356,15 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     // ---- 3. exact ranking inside the bin by (score bits, position), largest first
     if (ncand <= CAND_MAX) {
         for (uint32_t c = tid; c < ncand; c += POST_THREADS) {
-            const uint32_t key = sh.cand_key[c];
-            const int32_t ps = sh.cand_pos[c];
+            const uint32_t key = sh.sel.cand_key[c];
+            const int32_t ps = sh.sel.cand_pos[c];
             uint32_t rank = 0;
             for (uint32_t o = 0; o < ncand; ++o) {
-                const uint32_t ok = sh.cand_key[o];
-                rank += (ok > key) || (ok == key && sh.cand_pos[o] > ps);
+                const uint32_t ok = sh.sel.cand_key[o];
+                rank += (ok > key) || (ok == key && sh.sel.cand_pos[o] > ps);
             }
             if (rank < need) {
-                const uint32_t i = sh.cand_slot[c];
+                const uint32_t i = sh.sel.cand_slot[c];
                 atomicOr(&evbits[i >> 5], 1u << (i & 31));
             }
         }
@@ -349,40 +405,58 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     }
     __syncthreads();
 
-    // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten)
+    // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
+    // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
     uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     uint16_t *vb = p.v + (size_t)bh * p.cap * D;
     {
-        const int c = tid % D, g = tid / D;  // D columns x (1024 / D) row groups
-        constexpr int NG = POST_THREADS / D;
-        double acc = 0.0;
-        for (int rb = 0; rb < E; rb += NG) {  // uniform trip count: barriers and shuffles inside
-            const int r = rb + g;
-            const bool live = r < E;
-            double x = live ? bf16_to_f64(kb[(size_t)evlist[r] * D + c]) : 0.0;
-            if (p.anchor_mode == 1) {  // unit key: x / |k|, reduced over the D threads of the group
-                double k2 = x * x;
+        constexpr int RPW = 64 / UPR;
+        const int u = lane % UPR, rl = lane / UPR;
+        double acc[8];
 #pragma unroll
-                for (int off = 1; off < 64; off <<= 1) k2 += shfl_xor_f64(k2, off);
-                if (D == 128) {  // a row group spans two waves
-                    if ((tid & 63) == 0) sh.red[tid >> 6] = k2;
-                    __syncthreads();
-                    k2 = sh.red[(tid >> 6) & ~1] + sh.red[(tid >> 6) | 1];
-                    __syncthreads();
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+        for (int rb = wave * RPW; rb < E; rb += NWAVES * RPW) {  // uniform per wave
+            const int r = rb + rl;
+            double x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = 0.0;
+            if (r < E) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)evlist[r] * D + u * 8);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[2 * i] = bf16_lo(w[i]);
+                    x[2 * i + 1] = bf16_hi(w[i]);
                 }
-                const double nk = sqrt(k2);
-                x = nk > 0.0 ? x * (1.0 / nk) : 0.0;
             }
-            acc += x;
+            double inv = 1.0;
+            if (p.anchor_mode == 1) {  // unit key: x / |k|
+                double k2 = 0.0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
+                k2 = row_allreduce_f64<UPR>(k2);
+                const double nk = sqrt(k2);
+                inv = nk > 0.0 ? 1.0 / nk : 0.0;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
         }
-        sh.colsum[g * D + c] = acc;
+        // fold the rows of the wave (lanes with equal u), then the waves
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+#pragma unroll
+            for (int off = UPR; off < 64; off <<= 1) acc[i] += shfl_xor_f64(acc[i], off);
+        }
+        if (rl == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sh.sel.colsum[wave][u * 8 + i] = acc[i];
+        }
         __syncthreads();
         if (tid < D) {
             double s = 0.0;
-            for (int gg = 0; gg < NG; ++gg) s += sh.colsum[gg * D + tid];
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) s += sh.sel.colsum[w][tid];
             p.ksum[(size_t)bh * D + tid] -= s;
         }
-        __syncthreads();
     }
 
     // ---- 6. compaction
@@ -453,34 +527,35 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
 }
 
+// step_score: every workgroup scores score_rows rows of one head and adds them to the head's
+// histogram.  The launch boundary after it makes scores and histogram visible to step_post.
+template <int D>
+__global__ __launch_bounds__(POST_THREADS) void step_score_kernel(StepParams p)
+{
+    __shared__ PostShared sh;
+    const int BH = p.batch * p.hkv;
+    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
+    const int row0 = chunk * p.score_rows, row1 = min(p.n, row0 + p.score_rows);
+    score_rows<D>(p, sh, bh, row0, row1);
+}
+
+// step_post: workgroups [0, BH) select and compact one head each (when this step evicts); the
+// rest merge the attention partials.
 template <int D>
 __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __shared__ PostShared sh;
-    const int BH = p.batch * p.hkv;
-    const int n_score = p.do_score ? BH * p.score_chunks : 0;
-    if ((int)blockIdx.x >= n_score) {
-        merge_rows<D>(p, (size_t)(blockIdx.x - n_score) * POST_THREADS + threadIdx.x);
+    const int n_select = p.do_evict ? p.batch * p.hkv : 0;
+    if ((int)blockIdx.x >= n_select) {
+        merge_rows<D>(p, (size_t)(blockIdx.x - n_select) * POST_THREADS + threadIdx.x);
         return;
     }
-    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
-    const int row0 = chunk * SCORE_ROWS, row1 = min(p.n, row0 + SCORE_ROWS);
-    score_rows<D>(p, sh, bh, row0, row1);
-    if (!p.do_evict) return;
-    // the workgroup that completes a head's scores last selects and compacts that head
-    __threadfence();  // this thread's scores and histogram adds are visible device-wide ...
-    __syncthreads();  // ... before the workgroup announces itself
-    if (threadIdx.x == 0) {
-        const uint32_t old = atomicAdd(p.arrive + bh, 1u);
-        const bool last = old == (uint32_t)p.score_chunks - 1;
-        if (last) p.arrive[bh] = 0;  // left clean for the next step
-        sh.is_last = last;
-    }
-    __syncthreads();
-    if (!sh.is_last) return;
-    __threadfence();  // the other workgroups' results are visible to every thread here
-    select_and_compact<D>(p, sh, reinterpret_cast<uint32_t *>(smem_raw), bh);
+    const int bh = blockIdx.x;
+    uint32_t *evbits = reinterpret_cast<uint32_t *>(smem_raw);
+    int32_t *lists = p.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (p.n + 31) / 32)
+                                    : p.lists + (size_t)bh * 3 * p.B;
+    select_and_compact<D>(p, sh, evbits, lists, bh);
 }
 
 // ------------------------------------------------------------- ordered compaction
@@ -611,7 +686,16 @@ __global__ void load_pos_kernel(const int32_t *src, int32_t *dst, int cap, int l
 }
 
 // ---------------------------------------------------------------------- launchers
-size_t post_lds_bytes(int n, int /*N*/) { return (size_t)((n + 31) / 32) * 4 + 16; }
+constexpr size_t LISTS_LDS_MAX = 48 * 1024;
+
+bool lists_fit_lds(int n, int N) { return n > N && (size_t)(n - N) * 12 <= LISTS_LDS_MAX; }
+
+size_t post_lds_bytes(int n, int N)
+{
+    size_t b = (size_t)((n + 31) / 32) * 4;
+    if (lists_fit_lds(n, N)) b += (size_t)(n - N) * 12;
+    return b + 16;
+}
 
 static size_t compact_lds_bytes(int D) { return (size_t)2 * CHUNK_ROWS * (D / 8) * 16; }
 
@@ -623,13 +707,28 @@ hipError_t configure_kernels()
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(compact_ordered_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)compact_lds_bytes(128));
+    if (e != hipSuccess) return e;
+    const int post_max = (int)(MAX_CAP / 8 + LISTS_LDS_MAX + 16);
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_post_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_post_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
     return e;
+}
+
+hipError_t launch_step_score(const StepParams &p, hipStream_t s)
+{
+    const int grid = p.batch * p.hkv * p.score_chunks;
+    if (p.D == 128) hipLaunchKernelGGL((step_score_kernel<128>), dim3(grid), dim3(POST_THREADS), 0, s, p);
+    else if (p.D == 64) hipLaunchKernelGGL((step_score_kernel<64>), dim3(grid), dim3(POST_THREADS), 0, s, p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 hipError_t launch_step_post(const StepParams &p, hipStream_t s)
 {
-    const int n_score = p.do_score ? p.batch * p.hkv * p.score_chunks : 0;
-    const int grid = n_score + p.merge_wgs;
+    const int grid = (p.do_evict ? p.batch * p.hkv : 0) + p.merge_wgs;
     if (grid == 0) return hipSuccess;
     const size_t lds = post_lds_bytes(p.n, p.N);
     if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128>), dim3(grid), dim3(POST_THREADS), lds, s, p);

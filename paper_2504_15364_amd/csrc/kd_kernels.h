@@ -1,12 +1,12 @@
 // Internal launcher interface between the C-ABI host layer and the gfx950 kernels.
 //
-// One block step is two launches:
+// One block step is three launches:
 //   step_main  append (Eq. 5) + split-KV flash attention partials (Eq. 1-2)
 //              + running key sum S += sum of the block's keys (the anchor is S / n)
-//   step_post  merge of the attention partials  ||  cosine score of every row,
-//              then, in the workgroup that finishes a head's scores last, the
-//              selection of the rows to evict and the compaction (Eq. 6-7)
-// plus, for the ORDERED layout only, a third launch that shifts rows in place.
+//   step_score cosine score of every row + per-head score histogram
+//   step_post  merge of the attention partials  ||  selection of the rows to evict
+//              and compaction, one workgroup per head (Eq. 6-7)
+// plus, for the ORDERED layout only, one more launch that shifts rows in place.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -15,7 +15,6 @@ namespace kd {
 
 constexpr int TILE_KEYS = 64;       // keys per attention K/V tile
 constexpr int POST_THREADS = 1024;  // workgroup size of step_post
-constexpr int SCORE_ROWS = 512;     // rows scored per workgroup in step_post
 constexpr int HIST_BINS = 4096;     // score histogram resolution (bins over [-1, 1])
 constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
 constexpr int MAX_CAP = 32768;      // budget_N + block_B limit (selection bitmaps, ownership)
@@ -39,13 +38,13 @@ struct StepParams {
     float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
     uint32_t *hist;                  // [BH][HIST_BINS] zero between steps
-    uint32_t *arrive;                // [BH] zero between steps
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
     int32_t *lists;                  // [BH][3 * B] evicted rows | holes | movers of this step
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
-    int score_chunks;                // score workgroups per head in step_post
+    int score_chunks, score_rows;    // score workgroups per head in step_post and rows each takes
+    int lists_in_lds;                // selection lists live in LDS (else in `lists`)
     int merge_wgs;                   // merge workgroups in step_post (0 when splits == 1)
     int do_score, do_evict;
     int anchor_mode, layout, window_W;
@@ -56,6 +55,7 @@ struct StepParams {
 
 hipError_t configure_kernels();      // one-time function attributes (dynamic LDS sizes)
 hipError_t launch_step_main(const StepParams &p, hipStream_t s);
+hipError_t launch_step_score(const StepParams &p, hipStream_t s);
 hipError_t launch_step_post(const StepParams &p, hipStream_t s);
 hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s);
 hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s);
@@ -66,5 +66,6 @@ hipError_t launch_load_pos(const int32_t *src, int32_t *dst, int BH, int cap, in
                            hipStream_t s);
 
 size_t post_lds_bytes(int n, int N);
+bool lists_fit_lds(int n, int N);
 
 }  // namespace kd
