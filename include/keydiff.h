@@ -88,8 +88,7 @@ typedef struct {
 
 /* Sizes (bytes) of the four device buffers the caller must provide for `cfg`.
  * k_bytes == v_bytes: one K (or V) cache.  meta: persistent state (token
- * positions, the running key sum the anchor is derived from, the score
- * histogram and counters that are kept clean between steps, a status word).
+ * positions, the running key sum the anchor is derived from, a status word).
  * scratch: per-call temporaries (attention partials, scores, selection lists);
  * its contents carry nothing between calls.  Host call, nothing is enqueued.   */
 KEYDIFF_API int keydiff_workspace_bytes(const keydiff_config_t *cfg, size_t *k_bytes, size_t *v_bytes,
@@ -149,7 +148,7 @@ KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *stat
  * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
 enum {
     KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key-sum update          */
-    KEYDIFF_K_SCORE = 1,   /* step_score: cosine scores + per-head histogram                   */
+    KEYDIFF_K_SCORE = 1,   /* step_score: cosine score of every row                            */
     KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction             */
     KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
     KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */

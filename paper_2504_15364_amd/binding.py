@@ -64,9 +64,10 @@ def load_library() -> C.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_15364_amd.build`")
-    L = C.CDLL(LIB_PATH)
+    path = os.environ.get("KEYDIFF_LIBRARY", LIB_PATH)   # override: another build of the same ABI
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2504_15364_amd.build`")
+    L = C.CDLL(path)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     szp = C.POINTER(C.c_size_t)
     L.keydiff_workspace_bytes.argtypes = [C.POINTER(_Config), szp, szp, szp, szp]

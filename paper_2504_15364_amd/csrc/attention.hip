@@ -2,7 +2,7 @@
 //
 // Flash-style: the attention matrix is never materialised (Method, "Efficient
 // Variant": KeyDiff needs no attention weights).  bf16 MFMA 32x32x16 for both
-// contractions, fp32 online softmax, K/V tiles double-buffered in LDS.
+// contractions, fp32 online softmax.
 //
 // Work decomposition.  All G * Bt query rows that share one KV head form the M
 // dimension (GQA packing): a workgroup of NW waves owns 32 * NW of them and a
@@ -10,52 +10,90 @@
 // log-sum-exp in step_post.  Workgroup ids map KV heads round-robin so that the
 // workgroups of one head share an XCD and its L2.
 //
+// Data path.  K and V tiles stream global -> LDS asynchronously
+// (global_load_lds_dwordx4: lane i's 16 bytes land at LDS base + 16 i, no VGPRs)
+// through a ring of STAGES buffers, so several tiles are in flight per CU while
+// one is computed.  Both tiles are stored row-major with a 16-byte-unit XOR swizzle
+// applied on the global side (a lane fetches the unit that belongs in its LDS slot).
+//
 // Both contractions are computed transposed so that softmax statistics are
 // per-lane scalars and P never leaves registers:
-//   S^T = K Q^T   A = K tile rows (LDS, row-major), B = Q^T (registers)
+//   S^T = K Q^T   A = K rows (ds_read_b128), B = Q^T (registers)
 //                 -> a lane holds one query column (lane % 32) and 16 keys
-//   O^T = V^T P^T A = V^T (LDS, transposed while staging), B = P^T: the S^T
-//                 accumulator layout already is the B-operand layout once the 16
-//                 keys of a k-chunk are enumerated in accumulator order; V^T is
-//                 stored with the matching key permutation.
+//   O^T = V^T P^T A = V^T, read from the row-major V tile with the LDS transpose
+//                 read ds_read_b64_tr_b16 (a 16-lane group fetches 4 keys x 16 d and
+//                 lane i receives column i); B = P^T: the S^T accumulator layout
+//                 already is the B-operand layout once the 16 keys of a k-chunk are
+//                 enumerated in accumulator order (keys 16c + 8a + 4h + r for
+//                 k-slot 4a + r of lane half h), and the two transpose reads of an
+//                 operand fetch exactly those two groups of 4 consecutive keys.
 //
 // The block's own rows are read straight from k_new / v_new; every workgroup
 // copies a slice of them into the cache (the append) and adds that slice to the
 // running key sum the anchor is derived from.
+#include <type_traits>
+
 #include "kd_kernels.h"
 
 namespace kd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 constexpr float RESCALE_SLACK = 8.f;  // the running reference max may lag the true max by 2^8
+constexpr int STAGES = 4;             // LDS ring: one tile computed, STAGES - 1 in flight
 
-// Key permutation inside a 16-key chunk of V^T.  An S^T accumulator of lane
-// half h holds keys 8j + 4h + r (j = 0..3, r = 0..3) of its 32-key group; the
-// k-chunk c of the second MFMA takes j in {2c, 2c+1}, i.e. keys
-// 16c + 8a + 4h + r (a = 0,1).  Its 8 k-slots per half must be contiguous in
-// LDS: key (c, a, h, r) is stored at slot 16c + 8h + 4a + r.
+// Asynchronous 16-byte-per-lane copy global -> LDS.  `lds_base` is wave uniform; lane i writes
+// bytes [16 i, 16 i + 16) above it.  Issued through asm so that the compiler does not force
+// every outstanding copy to complete before the next LDS read; completion is awaited with
+// explicit s_waitcnt vmcnt(N) (copies complete in issue order).
+__device__ __forceinline__ void async_copy16(uint32_t lds_base, const void *gaddr)
+{
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(gaddr) : "memory");
+}
+__device__ __forceinline__ void async_copy16(uint32_t lds_base, const void *gbase, uint32_t byte_off)
+{
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+    const uint64_t g = (uint64_t)(uintptr_t)gbase;
+    // readfirstlane returns a signed int: widen through uint32_t, or a low word with bit 31 set
+    // would sign-extend into the high half of the address
+    const uint32_t g_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g);
+    const uint32_t g_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(g >> 32));
+    const uint64_t gu = ((uint64_t)g_hi << 32) | (uint64_t)g_lo;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(base), "v"(byte_off), "s"(gu) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_copies()  // at most N of this wave's copies still in flight
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 {
-    constexpr int NT = 64 * NW;  // threads; each wave owns 32 query rows
-    constexpr int UPR = D / 8;   // 16-byte units per K/V row
-    constexpr int NC = D / 16;   // k-chunks of the first MFMA
-    constexpr int NDB = D / 32;  // 32-wide d blocks of the output
-    constexpr int KLOADS = (TILE_KEYS * UPR) / NT;
-    constexpr int TILE_ELEMS = TILE_KEYS * D;
-    static_assert(KLOADS >= 1, "tile staging needs at least one K unit per thread");
+    constexpr int NT = 64 * NW;   // threads; each wave owns 32 query rows
+    constexpr int UPR = D / 8;    // 16-byte units per K/V row
+    constexpr int NC = D / 16;    // k-chunks of the first MFMA
+    constexpr int NDB = D / 32;   // 32-wide d blocks of the output
+    constexpr int ROWB = D * 2;   // bytes per row
+    constexpr int TILE_B = TILE_KEYS * ROWB;  // bytes of one K (or V) tile
+    constexpr int RPL = 64 / UPR;             // rows one wave-wide copy covers
+    constexpr int CPT = TILE_KEYS / RPL;      // wave-wide copies per K (or V) tile
+    constexpr int CPW = CPT / NW;             // ... per wave
+    static_assert(CPW >= 1 && CPW * NW == CPT, "tile copies must divide over the waves");
+    constexpr int LPW = 2 * CPW;              // copies per wave per tile (K and V)
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t *sK = smem;                    // [2][TILE_KEYS][D]   swizzled rows
-    uint16_t *sVT = smem + 2 * TILE_ELEMS;  // [2][D][TILE_KEYS]   transposed, permuted, swizzled
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [STAGES][K tile | V tile]
     __shared__ double red[NW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -75,6 +113,22 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const uint16_t *vcache = p.v + (size_t)bh * p.cap * D;
     const uint16_t *knew = p.k_new + (size_t)bh * p.Bt * D;
     const uint16_t *vnew = p.v_new + (size_t)bh * p.Bt * D;
+
+    // ---- query row of this lane: B operand of S^T = K Q^T, kept in registers
+    const int m = mt * (32 * NW) + wave * 32 + l32;
+    const bool valid = m < Mtot;
+    const int qg = valid ? m / p.Bt : 0, qj = valid ? m % p.Bt : 0;
+    const int vis = p.len + qj + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
+    bf16x8 qreg[NC];
+    {
+        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (valid) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
+            qreg[c] = as_bf16x8(z);
+        }
+    }
 
     // ---- append (Eq. 5): this workgroup's slice of the block's rows, and the key sum
     {
@@ -113,22 +167,6 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         if (tid < D && rows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
     }
 
-    // ---- query row of this lane: B operand of S^T = K Q^T, kept in registers
-    const int m = mt * (32 * NW) + wave * 32 + l32;
-    const bool valid = m < Mtot;
-    const int qg = valid ? m / p.Bt : 0, qj = valid ? m % p.Bt : 0;
-    const int vis = p.len + qj + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
-    bf16x8 qreg[NC];
-    {
-        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (valid) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
-            qreg[c] = as_bf16x8(z);
-        }
-    }
-
     f32x16 oacc[NDB];
     float mref = -INFINITY, lrun = 0.f;
 #pragma unroll
@@ -136,117 +174,96 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
 
-    // ---- tile staging: global -> registers (prefetch) -> LDS (double buffered)
-    u32x4 kpre[KLOADS], vpre[4];
-    const int v_db = tid % UPR, v_kq = tid / UPR;  // V item: 4 consecutive keys x one 16-byte unit
-    const bool v_active = tid < 16 * UPR;
-
-    auto row_ptr = [&](const uint16_t *cache, const uint16_t *fresh, int row) -> const uint16_t * {
-        return row < p.len ? cache + (size_t)row * D : fresh + (size_t)(row - p.len) * D;
-    };
-
-    auto prefetch = [&](int t) {
-        const int r0 = t * TILE_KEYS;
+    // ---- tile copies.  Wave w issues copies w, w + NW, ... of the K tile and of the V tile; copy s
+    // fills LDS bytes [1024 s, 1024 s + 1024) of the tile = rows RPL s .. RPL s + RPL - 1.  Lane i
+    // owns slot (row RPL s + i / UPR, unit i % UPR) and fetches the unit the swizzle puts there:
+    //   K: unit ^ (row & 7)            (ds_read_b128 of 8 consecutive rows hits 32 banks once)
+    //   V: unit ^ 2 (row & 3)          (the 4 rows x 32 bytes of a transpose read do the same)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    uint32_t koff[CPW], voff[CPW];  // byte offset of this lane's unit inside a whole tile in memory
+    int crow[CPW];                  // its row inside the tile
 #pragma unroll
-        for (int pp = 0; pp < KLOADS; ++pp) {
-            const int idx = tid + NT * pp;
-            const int row = r0 + idx / UPR, unit = idx % UPR;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (row < p.n) z = *reinterpret_cast<const u32x4 *>(row_ptr(kcache, knew, row) + unit * 8);
-            kpre[pp] = z;
-        }
-        if (v_active) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = r0 + 4 * v_kq + i;
-                u32x4 z = {0u, 0u, 0u, 0u};
-                if (row < p.n) z = *reinterpret_cast<const u32x4 *>(row_ptr(vcache, vnew, row) + v_db * 8);
-                vpre[i] = z;
-            }
-        }
-    };
-
-    auto stage = [&](int buf) {
-        uint16_t *dK = sK + buf * TILE_ELEMS, *dV = sVT + buf * TILE_ELEMS;
-#pragma unroll
-        for (int pp = 0; pp < KLOADS; ++pp) {
-            const int idx = tid + NT * pp;
-            const int row = idx / UPR, unit = idx % UPR;
-            const int su = unit ^ (row & 7);
-            *reinterpret_cast<u32x4 *>(dK + row * D + su * 8) = kpre[pp];
-        }
-        if (v_active) {
-            const int c = v_kq >> 2, q4 = v_kq & 3, a = q4 >> 1, hh = q4 & 1;
-            const int unit = 2 * c + hh;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-#pragma unroll
-                for (int bsel = 0; bsel < 2; ++bsel) {
-                    const int R = 8 * v_db + 2 * w + bsel;  // d index = row of V^T
-                    uint32_t lo, hi;
-                    if (bsel == 0) {
-                        lo = (vpre[0][w] & 0xFFFFu) | (vpre[1][w] << 16);
-                        hi = (vpre[2][w] & 0xFFFFu) | (vpre[3][w] << 16);
-                    } else {
-                        lo = (vpre[0][w] >> 16) | (vpre[1][w] & 0xFFFF0000u);
-                        hi = (vpre[2][w] >> 16) | (vpre[3][w] & 0xFFFF0000u);
-                    }
-                    const int su = unit ^ ((R ^ (R >> 3)) & 7);
-                    u32x2 val = {lo, hi};
-                    *reinterpret_cast<u32x2 *>(dV + R * TILE_KEYS + su * 8 + a * 4) = val;
-                }
-            }
-        }
-    };
-
-    if (t0 < t1) {
-        prefetch(t0);
-        stage(0);
-        if (t0 + 1 < t1) prefetch(t0 + 1);
+    for (int i = 0; i < CPW; ++i) {
+        const int s = wave + NW * i;
+        const int row = RPL * s + lane / UPR, su = lane % UPR;
+        crow[i] = row;
+        koff[i] = (uint32_t)(row * ROWB + ((su ^ (row & 7)) & (UPR - 1)) * 16);
+        voff[i] = (uint32_t)(row * ROWB + ((su ^ (2 * (row & 3))) & (UPR - 1)) * 16);
     }
-    int cur = 0;
-    for (int t = t0; t < t1; ++t) {
-        __syncthreads();  // tile t is staged; the other buffer is no longer read
-        if (t + 1 < t1) {
-            stage(cur ^ 1);
-            if (t + 2 < t1) prefetch(t + 2);  // in flight during this tile and the next staging
-        }
-        const uint16_t *tK = sK + cur * TILE_ELEMS, *tV = sVT + cur * TILE_ELEMS;
-        cur ^= 1;
-
+    // A tile is "whole" when its 64 rows are valid and come from one source (the cache, or the
+    // block's k_new / v_new): then only the base pointer differs.  A partial tile (it straddles len
+    // or n; at most two per step) takes per-row pointers; rows past n read row n - 1 -- finite
+    // data whose logits are masked, so it is never zeroed.
+    auto issue_tile = [&](int t) {
         const int r0 = t * TILE_KEYS;
-        const bool need_mask = r0 + TILE_KEYS > p.len;
+        const uint32_t kdst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B), vdst = kdst + TILE_B;
+        const bool whole = r0 + TILE_KEYS <= p.len || (r0 >= p.len && r0 + TILE_KEYS <= p.n);
+        if (whole) {
+            const bool cached = r0 < p.len;
+            const uint16_t *kt = cached ? kcache + (size_t)r0 * D : knew + (size_t)(r0 - p.len) * D;
+            const uint16_t *vt = cached ? vcache + (size_t)r0 * D : vnew + (size_t)(r0 - p.len) * D;
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) async_copy16(kdst + 1024u * (wave + NW * i), kt, koff[i]);
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) async_copy16(vdst + 1024u * (wave + NW * i), vt, voff[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int rc = min(r0 + crow[i], p.n - 1);
+                const uint16_t *src = rc < p.len ? kcache + (size_t)rc * D : knew + (size_t)(rc - p.len) * D;
+                async_copy16(kdst + 1024u * (wave + NW * i),
+                             reinterpret_cast<const char *>(src) + (koff[i] - crow[i] * ROWB));
+            }
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int rc = min(r0 + crow[i], p.n - 1);
+                const uint16_t *src = rc < p.len ? vcache + (size_t)rc * D : vnew + (size_t)(rc - p.len) * D;
+                async_copy16(vdst + 1024u * (wave + NW * i),
+                             reinterpret_cast<const char *>(src) + (voff[i] - crow[i] * ROWB));
+            }
+        }
+    };
 
-        // ---- per 32-key group: S^T = K Q^T, online softmax (per lane = per query column),
-        //      then O^T += V^T P^T
+    // ---- LDS byte offsets of this lane's MFMA A operands.
+    // K: row l32 of the key group, unit (2c + h) ^ (row & 7): the offset of k-chunk c is (offset of
+    // chunk 0) ^ 32 c for c < 4; the key group and c >> 2 add constants.
+    const int kof0 = l32 * ROWB + (h ^ (l32 & 7)) * 16;
+    // V (transpose read): the lane's 16-lane group fetches keys k0 .. k0 + 3 (k0 = 16 c + 4 h, + 8 for
+    // the second read) x columns d0 .. d0 + 15 (d0 = 32 db + 16 (group & 1)); this lane supplies row
+    // k0 + (lane % 16) / 4, columns d0 + 4 (lane % 4) .. + 3 and receives column d0 + lane % 16.
+    // The swizzled unit is (4 db + 2 (group & 1) + (lane % 4) / 2) ^ 2 (row & 3) = (per-lane part) ^ 4 db.
+    const int i16 = lane & 15, vrow = 4 * h + (i16 >> 2);
+    const int vof0 =
+        vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * (vrow & 3))) * 16) + (i16 & 1) * 8;
+
+    // one 64-key tile: per 32-key group S^T = K Q^T, online softmax (per lane = per query column),
+    // then O^T += V^T P^T
+    auto compute = [&](const unsigned char *tK, int r0, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const unsigned char *tV = tK + TILE_B;
 #pragma unroll
         for (int kg = 0; kg < 2; ++kg) {
             f32x16 sacc;
-            {
-                const int row = 32 * kg + l32;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    const int su = (2 * c + h) ^ (row & 7);
-                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(tK + row * D + su * 8));
-                    if (c == 0) {
-                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], zero, 0, 0, 0);
-                    } else {
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], sacc, 0, 0, 0);
-                    }
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                    tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+                if (c == 0) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], zero, 0, 0, 0);
+                } else {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], sacc, 0, 0, 0);
                 }
             }
-            float mloc = -INFINITY;
+            if (MASKED) {
+                // accumulator element e holds key r0 + 32 kg + 4 h + 8 (e / 4) + e % 4
+                const int lim = vis - r0 - 32 * kg - 4 * h;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float x = sacc[e];
-                if (need_mask) {
-                    const int key = r0 + 32 * kg + 8 * (e >> 2) + 4 * h + (e & 3);
-                    x = key < vis ? x : -INFINITY;
-                    sacc[e] = x;
-                }
-                mloc = fmaxf(mloc, x);
+                for (int e = 0; e < 16; ++e) sacc[e] = (8 * (e >> 2) + (e & 3)) < lim ? sacc[e] : -INFINITY;
             }
+            float mloc = sacc[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, sacc[e]);
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
             const float mtile = mloc * p.scale_log2e;
             // lazy rescale: the reference max only moves when the tile max exceeds it by 2^SLACK
@@ -261,32 +278,70 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
                     for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
             }
             const float nmuse = mref == -INFINITY ? 0.f : -mref;
-            float lsum = 0.f;
             bf16x8 pk[2];
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc) {
                 bf16x8 v;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
-                    lsum += pe;
-                    v[i] = (__bf16)pe;
-                }
+                for (int i = 0; i < 8; ++i)
+                    v[i] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
                 pk[cc] = v;
+                // the row sum adds the rounded weights the second MFMA multiplies with
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    bf16x2 pr = {v[2 * i], v[2 * i + 1]};
+                    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+                    lrun = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun, false);
+                }
             }
-            lrun += lsum;
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                const int R = 32 * db + l32;
 #pragma unroll
                 for (int cc = 0; cc < 2; ++cc) {
-                    const int su = (2 * (2 * kg + cc) + h) ^ ((R ^ (R >> 3)) & 7);
-                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(tV + R * TILE_KEYS + su * 8));
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pk[cc], oacc[db], 0, 0, 0);
+                    const unsigned char *va = tV + ((vof0 ^ (db * 64)) + (2 * kg + cc) * 16 * ROWB);
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3))) *)(va));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3))) *)(va + 8 * ROWB));
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pk[cc],
+                                                                       oacc[db], 0, 0, 0);
                 }
             }
         }
+    };
+
+    // Pin the query registers here: their global loads must not be pending when the tile loop
+    // starts (the explicit copy waits below count outstanding memory operations).
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        u32x4 qv = __builtin_bit_cast(u32x4, qreg[c]);
+        asm volatile("" : "+v"(qv));
+        qreg[c] = as_bf16x8(qv);
     }
+
+    // ---- the ring: STAGES - 1 tiles in flight while one is computed
+    const int ntl = t1 - t0;
+#pragma unroll
+    for (int i = 0; i < STAGES - 1; ++i)
+        if (i < ntl) issue_tile(t0 + i);
+    const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
+    auto step = [&](int t, auto masked_tag) {
+        // this wave's copies of tile t have landed when at most the copies of the later tiles in
+        // flight remain; the barrier then publishes every wave's part and retires tile t - 1
+        const int later = min(STAGES - 2, t1 - 1 - t);
+        if (later >= 2) wait_copies<2 * LPW>();
+        else if (later == 1) wait_copies<LPW>();
+        else wait_copies<0>();
+        __syncthreads();
+        if (t + STAGES - 1 < t1) issue_tile(t + STAGES - 1);  // into the buffer tile t - 1 just left
+        compute(smem + (size_t)(t % STAGES) * 2 * TILE_B, t * TILE_KEYS, masked_tag);
+    };
+    static_assert(STAGES == 4, "the wait ladder in step() assumes three tiles in flight");
+    // interior and edge tiles run in separate loops so that the rare masked path does not weigh on
+    // the register allocation of the hot one
+    for (int t = t0; t < tint; ++t) step(t, std::false_type{});
+    for (int t = tint; t < t1; ++t) step(t, std::true_type{});
 
     // ---- epilogue: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
     const float ltot = lrun + __shfl_xor(lrun, 32);
@@ -318,7 +373,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     }
 }
 
-static size_t main_lds_bytes(int D) { return (size_t)4 * TILE_KEYS * D * 2; }
+static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
 
 hipError_t configure_main_kernels()
 {

@@ -6,12 +6,11 @@
 // The pass is bandwidth bound, so the double FMAs are free; in exchange the
 // retained set does not depend on summation order beyond the last bit of a double.
 //
-// Selection.  Every score also lands in a 4096-bin histogram of its head (a
-// monotone map of the float).  In the next launch one workgroup per head scans the
-// histogram for the bin that holds the E-th largest score, evicts everything above
-// that bin and ranks the few rows inside it exactly by (score bits, position):
-// equal scores keep the lower position.  It then compacts the cache and takes the
-// evicted keys out of ksum.
+// Selection.  One workgroup per head loads the head's scores once, bins them into a
+// 4096-bin LDS histogram (a monotone map of the float), scans it for the bin that
+// holds the E-th largest score, evicts everything above that bin and ranks the few
+// rows inside it exactly by (score bits, position): equal scores keep the lower
+// position.  It then compacts the cache and takes the evicted keys out of ksum.
 #include "kd_kernels.h"
 
 namespace kd {
@@ -21,6 +20,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int NWAVES = POST_THREADS / 64;
+constexpr int SCORE_WAVES = SCORE_THREADS / 64;
 
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
@@ -71,26 +71,18 @@ __device__ __forceinline__ int score_bin(float s)
 }
 
 struct PostShared {
-    double mu[128];
-    double red[NWAVES];
+    uint32_t hist[HIST_BINS];  // score histogram of the head (a monotone map of the float)
     uint32_t wave_tot[NWAVES];
+    uint64_t wave_tot64[NWAVES];
     uint32_t radix_hist[256];
     uint32_t sel_bin, sel_rank, sel_cnt;
     int tb;           // threshold bin
     uint32_t need;    // rows to evict from the threshold bin
-    uint32_t ncand;
-    union {
-        struct {  // scoring: per-wave staging of (dot, |k|^2) so that sqrt and divide run on full waves
-            double dot[NWAVES][64];
-            double k2[NWAVES][64];
-        } fin;
-        struct {  // selection
-            uint32_t cand_slot[CAND_MAX];
-            uint32_t cand_key[CAND_MAX];
-            int32_t cand_pos[CAND_MAX];
-            double colsum[NWAVES][128];
-        } sel;
-    };
+    uint32_t ncand, nev;
+    uint32_t cand_slot[CAND_MAX];
+    uint32_t cand_key[CAND_MAX];
+    int32_t cand_pos[CAND_MAX];
+    double colsum[NWAVES][128];
 };
 
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
@@ -116,12 +108,43 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
     return base + inc - v;
 }
 
+// exclusive prefix sum of three packed 21-bit counters
+__device__ __forceinline__ uint64_t block_exclusive_scan64(uint64_t v, uint64_t *wave_tot, uint64_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t lo = __shfl_up((uint32_t)inc, off), hi = __shfl_up((uint32_t)(inc >> 32), off);
+        if (lane >= off) inc += ((uint64_t)hi << 32) | lo;
+    }
+    __syncthreads();  // wave_tot free for reuse
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint64_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
+        const uint64_t t = wave_tot[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
 // ------------------------------------------------------------------------ scores
-// Rows [row0, row1) of head bh.  D/8 lanes share a row (one 16-byte unit each); a
-// wave takes 64 consecutive rows per round, 64 / (D/8) ... rows per pass, stages
-// (mu.k, |k|^2) of each row in LDS and then lane i finishes row i of the round.
+struct ScoreShared {
+    double mu[128];
+    double red[SCORE_WAVES];
+    double dot[SCORE_WAVES][64];  // per-wave staging of (mu.k, |k|^2) so that sqrt and divide run on full waves
+    double k2[SCORE_WAVES][64];
+};
+
+// Rows [row0, row1) of head bh.  D/8 lanes share a row (one 16-byte unit each); a wave takes 64
+// consecutive rows per round, stages (mu.k, |k|^2) of each row in LDS and then lane i finishes
+// row i of the round.
 template <int D>
-__device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, int bh, int row0, int row1)
+__device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh, int bh, int row0, int row1)
 {
     constexpr int UPR = D / 8;
     constexpr int RPW = 64 / UPR;  // rows per wave per pass
@@ -139,7 +162,7 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
     __syncthreads();
     double mu2 = 0.0;
 #pragma unroll
-    for (int w = 0; w < NWAVES; ++w) mu2 += sh.red[w];
+    for (int w = 0; w < SCORE_WAVES; ++w) mu2 += sh.red[w];
     const double nmu = sqrt(mu2);
 
     const int u = lane % UPR, rl = lane / UPR;
@@ -148,7 +171,7 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
 #pragma unroll
     for (int i = 0; i < 8; ++i) mreg[i] = sh.mu[u * 8 + i];
     // a round = 64 rows per wave; rounds are spread over the waves
-    for (int base = row0 + wave * 64; base < row1; base += NWAVES * 64) {
+    for (int base = row0 + wave * 64; base < row1; base += SCORE_WAVES * 64) {
         u32x4 w[UPR];  // the round's loads are issued together
 #pragma unroll
         for (int ps = 0; ps < UPR; ++ps) {
@@ -171,8 +194,8 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
             dot = row_allreduce_f64<UPR>(dot);
             k2 = row_allreduce_f64<UPR>(k2);
             if (u == 0) {
-                sh.fin.dot[wave][ps * RPW + rl] = dot;
-                sh.fin.k2[wave][ps * RPW + rl] = k2;
+                sh.dot[wave][ps * RPW + rl] = dot;
+                sh.k2[wave][ps * RPW + rl] = k2;
             }
         }
         // same wave wrote and reads: the LDS accesses of one wave complete in order; the fence only
@@ -180,16 +203,12 @@ __device__ __forceinline__ void score_rows(const StepParams &p, PostShared &sh, 
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         const int row = base + lane;
         if (row < row1) {
-            const double dot = sh.fin.dot[wave][lane], k2 = sh.fin.k2[wave][lane];
+            const double dot = sh.dot[wave][lane], k2 = sh.k2[wave][lane];
             double den = nmu * sqrt(k2);
             if (den < p.eps) den = p.eps;
             const float s = (float)(dot / den) + 0.0f;  // +0 folds -0 into +0
             p.scores[(size_t)bh * p.cap + row] = s;
             if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = s;
-            if (p.do_evict) {
-                const bool exempt = p.window_W > 0 && p.pos[(size_t)bh * p.cap + row] >= p.window_pos_min;
-                if (!exempt) atomicAdd(p.hist + (size_t)bh * HIST_BINS + score_bin(s), 1u);
-            }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
@@ -287,24 +306,46 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     const int E = p.n - p.N;
     const float *sc = p.scores + (size_t)bh * p.cap;
     int32_t *pos = p.pos + (size_t)bh * p.cap;
-    uint32_t *hist = p.hist + (size_t)bh * HIST_BINS;
 
-    // ---- 1. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
+    // ---- 1. scores into registers (coalesced), histogram of the non-exempt ones in LDS
+    constexpr int SPT = MAX_CAP / POST_THREADS;  // scores per thread, at most
     const int nwords = (p.n + 31) / 32;
     for (int i = tid; i < nwords; i += POST_THREADS) evbits[i] = 0;
+    for (int i = tid; i < HIST_BINS; i += POST_THREADS) sh.hist[i] = 0;
     if (tid == 0) {
         sh.ncand = 0;
+        sh.nev = 0;
         sh.tb = 0;
         sh.need = 0;
     }
+    float sv[SPT];
+    int sbin[SPT];  // -1: not a candidate for eviction (exempt or past the end)
+#pragma unroll
+    for (int k = 0; k < SPT; ++k) {
+        const int i = k * POST_THREADS + tid;
+        sv[k] = 0.f;
+        sbin[k] = -1;
+        if (k * POST_THREADS < p.n && i < p.n) sv[k] = sc[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < SPT; ++k) {
+        const int i = k * POST_THREADS + tid;
+        if (k * POST_THREADS >= p.n) break;
+        if (i < p.n && !(p.window_W > 0 && pos[i] >= p.window_pos_min)) {
+            sbin[k] = score_bin(sv[k]);
+            atomicAdd(&sh.hist[sbin[k]], 1u);
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
     uint32_t cnt[HIST_BINS / POST_THREADS];
     uint32_t mine = 0;
     const int top = HIST_BINS - 1 - (HIST_BINS / POST_THREADS) * tid;
 #pragma unroll
-    for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) cnt[j] = hist[top - j];
-#pragma unroll
     for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
-        hist[top - j] = 0;  // left clean for the next step
+        cnt[j] = sh.hist[top - j];
         mine += cnt[j];
     }
     uint32_t total;
@@ -320,33 +361,23 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             above += cnt[j];
         }
     }
-    if (tid == 0 && total < (uint32_t)E) atomicOr(p.status, STATUS_SELECT_COUNT);  // corrupted histogram
+    if (tid == 0 && total < (uint32_t)E) atomicOr(p.status, STATUS_SELECT_COUNT);  // cannot happen: E <= candidates
     __syncthreads();
     const int tb = sh.tb;
     const uint32_t need = sh.need;
 
-    // ---- 2. one pass over the scores: above the bin -> evicted, inside it -> candidate
-    for (int i0 = 0; i0 < p.n; i0 += 4 * POST_THREADS) {
-        float sv[4];
+    // above the bin -> evicted, inside it -> candidate for the exact ranking
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int i = i0 + k * POST_THREADS + tid;
-            sv[k] = i < p.n ? sc[i] : 0.f;
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int i = i0 + k * POST_THREADS + tid;
-            if (i >= p.n) continue;
-            if (p.window_W > 0 && pos[i] >= p.window_pos_min) continue;  // exempt
-            const int bin = score_bin(sv[k]);
-            if (bin > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
-            else if (bin == tb) {
-                const uint32_t c = atomicAdd(&sh.ncand, 1u);
-                if (c < CAND_MAX) {
-                    sh.sel.cand_slot[c] = (uint32_t)i;
-                    sh.sel.cand_key[c] = orderable(sv[k]);
-                    sh.sel.cand_pos[c] = pos[i];
-                }
+    for (int k = 0; k < SPT; ++k) {
+        const int i = k * POST_THREADS + tid;
+        if (k * POST_THREADS >= p.n) break;
+        if (sbin[k] > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
+        else if (sbin[k] == tb) {
+            const uint32_t c = atomicAdd(&sh.ncand, 1u);
+            if (c < CAND_MAX) {
+                sh.cand_slot[c] = (uint32_t)i;
+                sh.cand_key[c] = orderable(sv[k]);
+                sh.cand_pos[c] = pos[i];
             }
         }
     }
@@ -356,15 +387,15 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     // ---- 3. exact ranking inside the bin by (score bits, position), largest first
     if (ncand <= CAND_MAX) {
         for (uint32_t c = tid; c < ncand; c += POST_THREADS) {
-            const uint32_t key = sh.sel.cand_key[c];
-            const int32_t ps = sh.sel.cand_pos[c];
+            const uint32_t key = sh.cand_key[c];
+            const int32_t ps = sh.cand_pos[c];
             uint32_t rank = 0;
             for (uint32_t o = 0; o < ncand; ++o) {
-                const uint32_t ok = sh.sel.cand_key[o];
-                rank += (ok > key) || (ok == key && sh.sel.cand_pos[o] > ps);
+                const uint32_t ok = sh.cand_key[o];
+                rank += (ok > key) || (ok == key && sh.cand_pos[o] > ps);
             }
             if (rank < need) {
-                const uint32_t i = sh.sel.cand_slot[c];
+                const uint32_t i = sh.cand_slot[c];
                 atomicOr(&evbits[i >> 5], 1u << (i & 31));
             }
         }
@@ -383,19 +414,23 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         nh += ev && i < p.N;
         nm += !ev && i >= p.N;
     }
-    uint32_t tot_ev, tot_hm;
-    uint32_t eb = block_exclusive_scan(nev, sh.wave_tot, &tot_ev);
-    const uint32_t hm = block_exclusive_scan(nh | (nm << 16), sh.wave_tot, &tot_hm);
-    const uint32_t nholes = tot_hm & 0xFFFFu, nmov = tot_hm >> 16;
+    uint64_t tot3;
+    const uint64_t ex3 = block_exclusive_scan64((uint64_t)nev | ((uint64_t)nh << 21) | ((uint64_t)nm << 42),
+                                                sh.wave_tot64, &tot3);
+    constexpr uint64_t M21 = (1ull << 21) - 1;
+    uint32_t eb = (uint32_t)(ex3 & M21);
+    const uint32_t hm_h = (uint32_t)((ex3 >> 21) & M21), hm_m = (uint32_t)((ex3 >> 42) & M21);
+    const uint32_t tot_ev = (uint32_t)(tot3 & M21), nholes = (uint32_t)((tot3 >> 21) & M21),
+                   nmov = (uint32_t)((tot3 >> 42) & M21);
     // an impossible count is reported and nothing is moved (keeps every index in range)
-    const bool sane = tot_ev == (uint32_t)E && nholes == nmov && (uint32_t)E <= 0xFFFFu;
+    const bool sane = tot_ev == (uint32_t)E && nholes == nmov;
     if (!sane) {
         if (tid == 0) atomicOr(p.status, STATUS_SELECT_COUNT);
         return;
     }
     int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E;
     {
-        uint32_t hb = hm & 0xFFFFu, mb = hm >> 16, e2 = eb;
+        uint32_t hb = hm_h, mb = hm_m, e2 = eb;
         for (int i = own0; i < own1; ++i) {
             const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
             if (ev) evlist[e2++] = i;
@@ -448,13 +483,13 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
         if (rl == 0) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) sh.sel.colsum[wave][u * 8 + i] = acc[i];
+            for (int i = 0; i < 8; ++i) sh.colsum[wave][u * 8 + i] = acc[i];
         }
         __syncthreads();
         if (tid < D) {
             double s = 0.0;
 #pragma unroll
-            for (int w = 0; w < NWAVES; ++w) s += sh.sel.colsum[w][tid];
+            for (int w = 0; w < NWAVES; ++w) s += sh.colsum[w][tid];
             p.ksum[(size_t)bh * D + tid] -= s;
         }
     }
@@ -501,19 +536,39 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     const int d4 = (int)(gid % (D / 4));
     const size_t row = gid / (D / 4);
     if (row >= rows) return;
+    // the loads of a batch of splits are issued together: a serial chain would cost a memory
+    // round trip per split
+    constexpr int MB = 8;
     float mx = -INFINITY;
-    for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, p.part_ml[(size_t)s * rows + row].x);
+    for (int s0 = 0; s0 < p.splits; s0 += MB) {
+        float2 ml[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            ml[i] = s0 + i < p.splits ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+        for (int i = 0; i < MB; ++i) mx = fmaxf(mx, ml[i].x);
+    }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float L = 0.f;
-    for (int s = 0; s < p.splits; ++s) {
-        const float2 ml = p.part_ml[(size_t)s * rows + row];
-        const float w = ml.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml.x - mx);
-        const float4 o = *reinterpret_cast<const float4 *>(p.part_o + ((size_t)s * rows + row) * D + 4 * d4);
-        acc.x += w * o.x;
-        acc.y += w * o.y;
-        acc.z += w * o.z;
-        acc.w += w * o.w;
-        L += w * ml.y;
+    for (int s0 = 0; s0 < p.splits; s0 += MB) {
+        float2 ml[MB];
+        float4 o[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const bool live = s0 + i < p.splits;
+            ml[i] = live ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
+            o[i] = live ? *reinterpret_cast<const float4 *>(p.part_o + ((size_t)(s0 + i) * rows + row) * D + 4 * d4)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const float w = ml[i].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[i].x - mx);
+            acc.x += w * o[i].x;
+            acc.y += w * o[i].y;
+            acc.z += w * o[i].z;
+            acc.w += w * o[i].w;
+            L += w * ml[i].y;
+        }
     }
     const float inv = 1.f / L;
     const int bh = (int)(row / Mtot), m = (int)(row % Mtot);
@@ -527,15 +582,15 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
 }
 
-// step_score: every workgroup scores score_rows rows of one head and adds them to the head's
-// histogram.  The launch boundary after it makes scores and histogram visible to step_post.
+// step_score: every workgroup scores SCORE_ROWS rows of one head.  The launch boundary after it
+// makes the scores visible to step_post.
 template <int D>
-__global__ __launch_bounds__(POST_THREADS) void step_score_kernel(StepParams p)
+__global__ __launch_bounds__(SCORE_THREADS) void step_score_kernel(StepParams p)
 {
-    __shared__ PostShared sh;
+    __shared__ ScoreShared sh;
     const int BH = p.batch * p.hkv;
     const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
-    const int row0 = chunk * p.score_rows, row1 = min(p.n, row0 + p.score_rows);
+    const int row0 = chunk * SCORE_ROWS, row1 = min(p.n, row0 + SCORE_ROWS);
     score_rows<D>(p, sh, bh, row0, row1);
 }
 
@@ -720,8 +775,8 @@ hipError_t configure_kernels()
 hipError_t launch_step_score(const StepParams &p, hipStream_t s)
 {
     const int grid = p.batch * p.hkv * p.score_chunks;
-    if (p.D == 128) hipLaunchKernelGGL((step_score_kernel<128>), dim3(grid), dim3(POST_THREADS), 0, s, p);
-    else if (p.D == 64) hipLaunchKernelGGL((step_score_kernel<64>), dim3(grid), dim3(POST_THREADS), 0, s, p);
+    if (p.D == 128) hipLaunchKernelGGL((step_score_kernel<128>), dim3(grid), dim3(SCORE_THREADS), 0, s, p);
+    else if (p.D == 64) hipLaunchKernelGGL((step_score_kernel<64>), dim3(grid), dim3(SCORE_THREADS), 0, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

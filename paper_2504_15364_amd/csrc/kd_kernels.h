@@ -15,7 +15,9 @@ namespace kd {
 
 constexpr int TILE_KEYS = 64;       // keys per attention K/V tile
 constexpr int POST_THREADS = 1024;  // workgroup size of step_post
-constexpr int HIST_BINS = 4096;     // score histogram resolution (bins over [-1, 1])
+constexpr int SCORE_THREADS = 256;  // workgroup size of step_score
+constexpr int SCORE_ROWS = 256;     // rows per step_score workgroup: 64 per wave
+constexpr int HIST_BINS = 4096;     // score histogram resolution in step_post (bins over [-1, 1])
 constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
 constexpr int MAX_CAP = 32768;      // budget_N + block_B limit (selection bitmaps, ownership)
 
@@ -37,13 +39,12 @@ struct StepParams {
     float *part_o;                   // [splits][BH * G * Bt][D] unnormalised partial outputs
     float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
-    uint32_t *hist;                  // [BH][HIST_BINS] zero between steps
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
     int32_t *lists;                  // [BH][3 * B] evicted rows | holes | movers of this step
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
-    int score_chunks, score_rows;    // score workgroups per head in step_post and rows each takes
+    int score_chunks;                // step_score workgroups per head
     int lists_in_lds;                // selection lists live in LDS (else in `lists`)
     int merge_wgs;                   // merge workgroups in step_post (0 when splits == 1)
     int do_score, do_evict;

@@ -28,7 +28,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
     size_t k_bytes, meta_bytes, scratch_bytes;
-    size_t off_pos, off_ksum, off_hist, off_status;                                   // in meta
+    size_t off_pos, off_ksum, off_status;                                             // in meta
     size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part;  // in scratch
     int cap, max_part_rows;
 };
@@ -65,7 +65,6 @@ Layout make_layout(const keydiff_config_t *c)
     size_t off = 0;
     L.off_pos = off;     off += align256(BH * L.cap * 4);
     L.off_ksum = off;    off += align256(BH * D * 8);
-    L.off_hist = off;    off += align256(BH * kd::HIST_BINS * 4);
     L.off_status = off;  off += 256;
     L.meta_bytes = off;
     // split-KV partial rows: splits * BH * G * Bt never exceeds this (see plan_attention)
@@ -157,7 +156,6 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.v = c->v;
     p.pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
     p.ksum = reinterpret_cast<double *>(c->meta + c->L.off_ksum);
-    p.hist = reinterpret_cast<uint32_t *>(c->meta + c->L.off_hist);
     p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
     p.part_o = reinterpret_cast<float *>(c->scratch + c->L.off_part_o);
     p.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
@@ -174,18 +172,8 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.B = cf.block_B;
     p.cap = c->L.cap;
     p.splits = 1;
-    {
-        // score workgroups: 512 rows each unless there are many heads, then fewer, larger chunks
-        const int BHs = cf.batch * cf.n_kv_heads;
-        int chunks = (n + 511) / 512;
-        const int cap_chunks = (384 + BHs - 1) / BHs;
-        if (chunks > cap_chunks) chunks = cap_chunks;
-        if (chunks < 1) chunks = 1;
-        p.score_rows = (((n + chunks - 1) / chunks) + 63) / 64 * 64;
-        if (p.score_rows < 64) p.score_rows = 64;
-        p.score_chunks = (n + p.score_rows - 1) / p.score_rows;
-        if (p.score_chunks < 1) p.score_chunks = 1;
-    }
+    p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
+    if (p.score_chunks < 1) p.score_chunks = 1;
     p.lists_in_lds = kd::lists_fit_lds(n, cf.budget_N) ? 1 : 0;
     p.anchor_mode = cf.anchor_mode;
     p.layout = cf.layout;
