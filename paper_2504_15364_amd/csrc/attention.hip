@@ -48,7 +48,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 constexpr float RESCALE_SLACK = 8.f;  // the running reference max may lag the true max by 2^8
-constexpr int STAGES = 4;             // LDS ring: one tile computed, STAGES - 1 in flight
+constexpr int STAGES = 4;             // LDS ring: tiles t - 1 and t in use, STAGES - 2 in flight
 
 // Asynchronous 16-byte-per-lane copy global -> LDS.  `lds_base` is wave uniform; lane i writes
 // bytes [16 i, 16 i + 16) above it.  Issued through asm so that the compiler does not force
@@ -236,79 +236,106 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const int vof0 =
         vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * (vrow & 3))) * 16) + (i16 & 1) * 8;
 
-    // one 64-key tile: per 32-key group S^T = K Q^T, online softmax (per lane = per query column),
-    // then O^T += V^T P^T
-    auto compute = [&](const unsigned char *tK, int r0, auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        const unsigned char *tV = tK + TILE_B;
+    // One 64-key tile.  Operand reads are issued a phase ahead of the MFMAs that consume them so
+    // that LDS latency hides behind matrix and vector work: K operands of both 32-key groups, then
+    // the V^T operands of group 0 while S is still in the matrix pipe; one reference-max decision
+    // per tile; then a straight-line block (softmax 0, PV 0, softmax 1, PV 1) in which the PV MFMAs
+    // of one group overlap the exponentials of the other.
+    auto read_k = [&](const unsigned char *tK, int kg, bf16x8 (&ka)[NC]) {
 #pragma unroll
-        for (int kg = 0; kg < 2; ++kg) {
-            f32x16 sacc;
+        for (int c = 0; c < NC; ++c)
+            ka[c] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+    };
+    auto read_v = [&](const unsigned char *tV, int kg, bf16x8 (&va)[NDB][2]) {
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                    tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
-                if (c == 0) {
-                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], zero, 0, 0, 0);
-                } else {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[c], sacc, 0, 0, 0);
-                }
-            }
-            if (MASKED) {
-                // accumulator element e holds key r0 + 32 kg + 4 h + 8 (e / 4) + e % 4
-                const int lim = vis - r0 - 32 * kg - 4 * h;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[e] = (8 * (e >> 2) + (e & 3)) < lim ? sacc[e] : -INFINITY;
-            }
-            float mloc = sacc[0];
-#pragma unroll
-            for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, sacc[e]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            const float mtile = mloc * p.scale_log2e;
-            // lazy rescale: the reference max only moves when the tile max exceeds it by 2^SLACK
-            const bool need = mtile > mref + RESCALE_SLACK;
-            if (__builtin_amdgcn_ballot_w64(need) != 0) {
-                const float alpha = need ? __builtin_amdgcn_exp2f(mref - mtile) : 1.f;
-                mref = need ? mtile : mref;
-                lrun *= alpha;
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-            }
-            const float nmuse = mref == -INFINITY ? 0.f : -mref;
-            bf16x8 pk[2];
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc) {
-                bf16x8 v;
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    v[i] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
-                pk[cc] = v;
-                // the row sum adds the rounded weights the second MFMA multiplies with
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    bf16x2 pr = {v[2 * i], v[2 * i + 1]};
-                    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-                    lrun = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun, false);
-                }
+                const unsigned char *a = tV + ((vof0 ^ (db * 64)) + (2 * kg + cc) * 16 * ROWB);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a));
+                const s16x4 hi =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a + 8 * ROWB));
+                va[db][cc] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
+    };
+    auto qk = [&](const bf16x8 (&ka)[NC]) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qreg[0], zero, 0, 0, 0);
 #pragma unroll
-            for (int db = 0; db < NDB; ++db) {
+        for (int c = 1; c < NC; ++c) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qreg[c], acc, 0, 0, 0);
+        return acc;
+    };
+    // exponentials of one group -> bf16 B operands; the row sum adds the rounded weights the
+    // second MFMA multiplies with
+    auto softmax = [&](const f32x16 &sacc, float nmuse, bf16x8 (&pk)[2]) {
 #pragma unroll
-                for (int cc = 0; cc < 2; ++cc) {
-                    const unsigned char *va = tV + ((vof0 ^ (db * 64)) + (2 * kg + cc) * 16 * ROWB);
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3))) *)(va));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3))) *)(va + 8 * ROWB));
-                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pk[cc],
-                                                                       oacc[db], 0, 0, 0);
-                }
+        for (int cc = 0; cc < 2; ++cc) {
+            bf16x8 v;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                v[i] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
+            pk[cc] = v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bf16x2 pr = {v[2 * i], v[2 * i + 1]};
+                const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+                lrun = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun, false);
             }
         }
+    };
+    auto pv = [&](const bf16x8 (&va)[NDB][2], const bf16x8 (&pk)[2]) {
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cc], pk[cc], oacc[db], 0, 0, 0);
+    };
+    // first half of a tile: S^T of both key groups (+ causal mask on edge tiles)
+    auto s_phase = [&](const unsigned char *tK, int r0, f32x16 &s0, f32x16 &s1, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        bf16x8 ka0[NC], ka1[NC];
+        read_k(tK, 0, ka0);
+        read_k(tK, 1, ka1);
+        s0 = qk(ka0);
+        s1 = qk(ka1);
+        if (MASKED) {
+            // accumulator element e of group kg holds key r0 + 32 kg + 4 h + 8 (e / 4) + e % 4
+            const int lim = vis - r0 - 4 * h;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                s0[e] = (8 * (e >> 2) + (e & 3)) < lim ? s0[e] : -INFINITY;
+                s1[e] = (32 + 8 * (e >> 2) + (e & 3)) < lim ? s1[e] : -INFINITY;
+            }
+        }
+    };
+    // second half: reference-max decision, exponentials, O^T += V^T P^T
+    auto pv_phase = [&](const unsigned char *tV, const f32x16 &s0, const f32x16 &s1) {
+        bf16x8 va0[NDB][2], va1[NDB][2];
+        read_v(tV, 0, va0);
+        float mloc = fmaxf(s0[0], s1[0]);
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, fmaxf(s0[e], s1[e]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float mtile = mloc * p.scale_log2e;
+        // lazy rescale: the reference max only moves when the tile max exceeds it by 2^SLACK
+        const bool need = mtile > mref + RESCALE_SLACK;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            const float alpha = need ? __builtin_amdgcn_exp2f(mref - mtile) : 1.f;
+            mref = need ? mtile : mref;
+            lrun *= alpha;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+        }
+        const float nmuse = mref == -INFINITY ? 0.f : -mref;
+        bf16x8 pk0[2], pk1[2];
+        softmax(s0, nmuse, pk0);
+        read_v(tV, 1, va1);
+        pv(va0, pk0);
+        softmax(s1, nmuse, pk1);
+        pv(va1, pk1);
     };
 
     // Pin the query registers here: their global loads must not be pending when the tile loop
@@ -320,28 +347,43 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         qreg[c] = as_bf16x8(qv);
     }
 
-    // ---- the ring: STAGES - 1 tiles in flight while one is computed
+    // ---- the ring.  Waves [0, NW/2) ("early") run both halves of tile t in iteration t; waves
+    // [NW/2, NW) ("late") -- the second wave on each SIMD -- run the second half one iteration
+    // behind: [second half of t - 1, first half of t].  The per-tile barrier would otherwise keep
+    // all waves in the same phase, and the two waves of a SIMD would queue for the same pipe
+    // (matrix, vector or LDS) instead of overlapping MFMAs with exponentials.  The V tile of
+    // t - 1 therefore stays live during iteration t: with STAGES buffers, STAGES - 2 tiles are
+    // in flight.
+    const bool late = wave >= NW / 2;
     const int ntl = t1 - t0;
 #pragma unroll
-    for (int i = 0; i < STAGES - 1; ++i)
+    for (int i = 0; i < STAGES - 2; ++i)
         if (i < ntl) issue_tile(t0 + i);
     const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
+    f32x16 sp0, sp1;  // S of the previous tile (late waves)
     auto step = [&](int t, auto masked_tag) {
-        // this wave's copies of tile t have landed when at most the copies of the later tiles in
-        // flight remain; the barrier then publishes every wave's part and retires tile t - 1
-        const int later = min(STAGES - 2, t1 - 1 - t);
-        if (later >= 2) wait_copies<2 * LPW>();
-        else if (later == 1) wait_copies<LPW>();
+        // this wave's copies of tile t have landed when at most the copies of the later tile in
+        // flight remain; the barrier then publishes every wave's part and retires tile t - 2
+        if (t + 1 < t1) wait_copies<LPW>();
         else wait_copies<0>();
         __syncthreads();
-        if (t + STAGES - 1 < t1) issue_tile(t + STAGES - 1);  // into the buffer tile t - 1 just left
-        compute(smem + (size_t)(t % STAGES) * 2 * TILE_B, t * TILE_KEYS, masked_tag);
+        if (t + STAGES - 2 < t1) issue_tile(t + STAGES - 2);  // into the buffer tile t - 2 left
+        const unsigned char *tK = smem + (size_t)(t % STAGES) * 2 * TILE_B;
+        if (!late) {
+            f32x16 s0, s1;
+            s_phase(tK, t * TILE_KEYS, s0, s1, masked_tag);
+            pv_phase(tK + TILE_B, s0, s1);
+        } else {
+            if (t > t0) pv_phase(smem + (size_t)((t - 1) % STAGES) * 2 * TILE_B + TILE_B, sp0, sp1);
+            s_phase(tK, t * TILE_KEYS, sp0, sp1, masked_tag);
+        }
     };
-    static_assert(STAGES == 4, "the wait ladder in step() assumes three tiles in flight");
+    static_assert(STAGES == 4, "the wait ladder in step() assumes two tiles in flight");
     // interior and edge tiles run in separate loops so that the rare masked path does not weigh on
     // the register allocation of the hot one
     for (int t = t0; t < tint; ++t) step(t, std::false_type{});
     for (int t = tint; t < t1; ++t) step(t, std::true_type{});
+    if (late && ntl > 0) pv_phase(smem + (size_t)((t1 - 1) % STAGES) * 2 * TILE_B + TILE_B, sp0, sp1);
 
     // ---- epilogue: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
     const float ltot = lrun + __shfl_xor(lrun, 32);
