@@ -27,6 +27,22 @@ from synth import get_config, make_layer  # noqa: E402
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # dense bf16, MI355X
 PEAK_HBM_GBPS = 8000.0
+CALIBRATION_COPY_BYTES = 256 << 20
+
+
+def measured_traffic(workload: str, layout: str):
+    """HBM bytes per step_main launch from the committed counter summary of this workload, or None.
+
+    The figure comes from two rocprofv3 --pmc runs of this script (FETCH_SIZE, WRITE_SIZE), each
+    scaled by the same counter's reading for the calibration copy; it cannot be measured from
+    inside the process."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"step_main_{workload}_{layout}_hbm_traffic.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def log(*a):
@@ -53,6 +69,9 @@ def main():
     ap.add_argument("--seed", type=int, default=20250415)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch plain device copies of a known size (untimed), so that a rocprofv3 "
+                         "--pmc run of this command holds the counter's reading for a known byte count")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -111,6 +130,12 @@ def main():
     for _ in range(args.warmup):
         run_block(i)
         i += 1
+    if args.pmc_calibration:
+        src = torch.empty(CALIBRATION_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads and writes CALIBRATION_COPY_BYTES each
+        del src, dst
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
@@ -138,7 +163,13 @@ def main():
                 a[0] += ms
                 a[1] += cnt
             c.profile_enable(False)
-        kernels = {k: {"avg_us": v[0] / v[1] * 1e3, "launches": v[1]} for k, v in tot.items() if v[1]}
+        # an event pair with nothing between it costs time by itself: the library records one such
+        # pair per profiled step, and its average is taken off every kernel's bracket
+        pair = tot.pop("event_pair", [0.0, 0])
+        pair_us = pair[0] / pair[1] * 1e3 if pair[1] else 0.0
+        kernels = {k: {"avg_us": v[0] / v[1] * 1e3 - pair_us, "launches": v[1],
+                       "event_bracket_us": v[0] / v[1] * 1e3, "empty_event_pair_us": pair_us}
+                   for k, v in tot.items() if v[1]}
     assert all(c.status() == 0 for c in caches)
 
     # algorithmic work of one steady-state block step of one layer
@@ -152,7 +183,7 @@ def main():
         achieved = flops_attn / t_attn / 1e12
         roofline = {"bound": "mfma", "kernel": "step_main_kernel", "achieved": achieved,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
-                    "traffic": None, "flops_per_launch": flops_attn,
+                    "traffic": measured_traffic(w.name, args.layout), "flops_per_launch": flops_attn,
                     "avg_launch_us": kernels["step_main"]["avg_us"]}
     t_min = max(flops_attn / (PEAK_BF16_MFMA_TFLOPS * 1e12), bytes_step / (PEAK_HBM_GBPS * 1e9))
     step_frac = t_min / (us_per_layer_step * 1e-6)

@@ -152,7 +152,10 @@ enum {
     KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction             */
     KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
     KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */
-    KEYDIFF_NKERNELS = 5
+    KEYDIFF_K_EVENT_PAIR = 5, /* no kernel: an empty event pair recorded once per profiled block
+                              step; its time is what the two records themselves add to every
+                              class above, to be subtracted by the reader                      */
+    KEYDIFF_NKERNELS = 6
 };
 KEYDIFF_API int keydiff_profile_enable(keydiff_cache_t *cache, int32_t enable);
 KEYDIFF_API int keydiff_profile_read(keydiff_cache_t *cache, float *ms_out, int32_t *launches_out);

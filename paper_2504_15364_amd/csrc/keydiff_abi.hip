@@ -327,6 +327,7 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
         ProfScope ps(c, KEYDIFF_K_COMPACT, s);
         KD_LAUNCH(kd::launch_compact_ordered(p, s), "ordered compaction kernel");
     }
+    if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
     c->len = evict ? N : n;
     c->contiguous = contiguous;
     c->next_pos = pos0 + Bt;
