@@ -44,10 +44,15 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-constexpr float RESCALE_SLACK = 8.f;  // the running reference max may lag the true max by 2^8
+// The running reference max may lag the true row max by 2^SLACK before the accumulators are
+// rescaled: weights then reach 2^64 and sums 2^64 * 32768 rows * |v|, far inside fp32 range, and
+// bf16 / fp32 keep their relative precision at any magnitude, so the slack costs no accuracy; it
+// makes the rescale (a pass over all accumulators) a once-per-row event instead of a per-tile one.
+constexpr float RESCALE_SLACK = 64.f;
 constexpr int STAGES = 4;             // LDS ring: tiles t - 1 and t in use, STAGES - 2 in flight
 
 // Asynchronous 16-byte-per-lane copy global -> LDS.  `lds_base` is wave uniform; lane i writes
@@ -71,6 +76,14 @@ __device__ __forceinline__ void async_copy16(uint32_t lds_base, const void *gbas
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(base), "v"(byte_off), "s"(gu) : "memory");
 }
 
+// max(a, b, c) without the NaN canonicalisation fmaxf carries (logits are finite or -inf)
+__device__ __forceinline__ float max3_raw(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_copies()  // at most N of this wave's copies still in flight
 {
@@ -78,10 +91,12 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int D, int NW>
+// NQ: 32-row query blocks per wave; every K / V fragment read from LDS feeds one MFMA per block
+template <int D, int NW, int NQ>
 __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 {
-    constexpr int NT = 64 * NW;   // threads; each wave owns 32 query rows
+    constexpr int NT = 64 * NW;   // threads
+    constexpr int TM = 32 * NQ * NW;          // query rows per workgroup
     constexpr int UPR = D / 8;    // 16-byte units per K/V row
     constexpr int NC = D / 16;    // k-chunks of the first MFMA
     constexpr int NDB = D / 32;   // 32-wide d blocks of the output
@@ -92,6 +107,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     constexpr int CPW = CPT / NW;             // ... per wave
     static_assert(CPW >= 1 && CPW * NW == CPT, "tile copies must divide over the waves");
     constexpr int LPW = 2 * CPW;              // copies per wave per tile (K and V)
+    static_assert(2 * LPW < 64, "two tiles of copies in flight must fit the 6-bit counter");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [STAGES][K tile | V tile]
     __shared__ double red[NW];
@@ -108,40 +124,425 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const int Mtot = p.G * p.Bt;
     const int t0 = (int)(((long)sp * p.ntiles) / p.splits);
     const int t1 = (int)(((long)(sp + 1) * p.ntiles) / p.splits);
+    const int ntl = t1 - t0;
 
     const uint16_t *kcache = p.k + (size_t)bh * p.cap * D;
     const uint16_t *vcache = p.v + (size_t)bh * p.cap * D;
     const uint16_t *knew = p.k_new + (size_t)bh * p.Bt * D;
     const uint16_t *vnew = p.v_new + (size_t)bh * p.Bt * D;
 
-    // ---- query row of this lane: B operand of S^T = K Q^T, kept in registers
-    const int m = mt * (32 * NW) + wave * 32 + l32;
-    const bool valid = m < Mtot;
-    const int qg = valid ? m / p.Bt : 0, qj = valid ? m % p.Bt : 0;
-    const int vis = p.len + qj + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
-    bf16x8 qreg[NC];
-    {
-        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
+    // ---- tile copies.  Wave w issues copies w, w + NW, ... of the K tile and of the V tile; copy s
+    // fills LDS bytes [1024 s, 1024 s + 1024) of the tile = rows RPL s .. RPL s + RPL - 1.  Lane i
+    // owns slot (row RPL s + i / UPR, unit i % UPR) and fetches the unit the swizzle puts there:
+    //   K: unit ^ (row & 7)            (ds_read_b128 of 8 consecutive rows hits 32 banks once)
+    //   V: unit ^ 2 (row & 3)          (the 4 rows x 32 bytes of a transpose read do the same)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    // Copy i of a wave covers rows RPL (wave + NW i) ..: NW RPL is a multiple of 8, so the swizzle
+    // terms (row & 7, row & 3) are those of copy 0 and copy i only adds i NW RPL rows.
+    static_assert((NW * RPL) % 8 == 0, "the swizzle of a lane must not depend on the copy index");
+    constexpr int CSTEP = NW * RPL;  // rows between consecutive copies of one wave
+    const int crow0 = RPL * wave + lane / UPR;   // row of copy 0 inside the tile
+    const uint32_t koff0 = (uint32_t)(crow0 * ROWB + (((lane % UPR) ^ (crow0 & 7)) & (UPR - 1)) * 16);
+    const uint32_t voff0 = (uint32_t)(crow0 * ROWB + (((lane % UPR) ^ (2 * (crow0 & 3))) & (UPR - 1)) * 16);
+    // A tile is "whole" when its 64 rows are valid and come from one source (the cache, or the
+    // block's k_new / v_new): then only the base pointer differs.  A partial tile (it straddles len
+    // or n; at most two per step) takes per-row pointers; rows past n read row n - 1 -- finite
+    // data whose logits are masked, so it is never zeroed.
+    auto issue_copy = [&](int t, int c) {   // copy c of tile t: c < CPW K tile, else V tile
+        const int r0 = t * TILE_KEYS;
+        const bool isv = c >= CPW;
+        const int i = isv ? c - CPW : c;
+        const uint32_t dst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B) + (isv ? TILE_B : 0) + 1024u * (wave + NW * i);
+        const uint32_t off0 = isv ? voff0 : koff0;
+        const bool whole = r0 + TILE_KEYS <= p.len || (r0 >= p.len && r0 + TILE_KEYS <= p.n);
+        if (whole) {
+            const bool cached = r0 < p.len;
+            const uint16_t *src = cached ? (isv ? vcache : kcache) + (size_t)r0 * D
+                                         : (isv ? vnew : knew) + (size_t)(r0 - p.len) * D;
+            async_copy16(dst, src + (size_t)i * CSTEP * D, off0);
+        } else {
+            const int rc = min(r0 + crow0 + i * CSTEP, p.n - 1);
+            const uint16_t *src = rc < p.len ? (isv ? vcache : kcache) + (size_t)rc * D
+                                             : (isv ? vnew : knew) + (size_t)(rc - p.len) * D;
+            async_copy16(dst, reinterpret_cast<const char *>(src) + (off0 - crow0 * ROWB));
+        }
+    };
+    auto issue_tile = [&](int t) {
+#pragma unroll
+        for (int c = 0; c < LPW; ++c) issue_copy(t, c);
+    };
+    // the same for a tile known to lie entirely in the cache: no decisions left, a handful of
+    // scalar instructions per copy
+    auto issue_copy_cached = [&](int t, int c) {
+        const bool isv = c >= CPW;
+        const int i = isv ? c - CPW : c;
+        const uint32_t dst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B) + (isv ? TILE_B : 0) + 1024u * (wave + NW * i);
+        const uint16_t *src = (isv ? vcache : kcache) + ((size_t)t * TILE_KEYS + (size_t)i * CSTEP) * D;
+        async_copy16(dst, src, isv ? voff0 : koff0);
+    };
+    // tile t0 first, then the queries: one memory round trip covers both
+    if (ntl > 0) issue_tile(t0);
+
+    // ---- query rows of this lane (one per block): B operands of S^T = K Q^T, kept in registers
+    int mrow[NQ], qg[NQ], qj[NQ], vis[NQ];
+    bool valid[NQ];
+    bf16x8 qreg[NQ][NC];
+#pragma unroll
+    for (int a = 0; a < NQ; ++a) {
+        mrow[a] = mt * TM + wave * (32 * NQ) + 32 * a + l32;
+        valid[a] = mrow[a] < Mtot;
+        qg[a] = valid[a] ? mrow[a] / p.Bt : 0;
+        qj[a] = valid[a] ? mrow[a] % p.Bt : 0;
+        vis[a] = p.len + qj[a] + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
+        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg[a]) * p.Bt + qj[a]) * D;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             u32x4 z = {0u, 0u, 0u, 0u};
-            if (valid) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
-            qreg[c] = as_bf16x8(z);
+            if (valid[a]) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
+            qreg[a][c] = as_bf16x8(z);
         }
     }
 
-    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and the key sum
+    // Pin the query registers: the compiler must see their global loads complete before the tile
+    // copies are issued, or it would wait for "all memory operations" at their first use in every
+    // iteration -- and thereby for tile copies in flight, which it does not know about.
+#pragma unroll
+    for (int a = 0; a < NQ; ++a)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            u32x4 qv = __builtin_bit_cast(u32x4, qreg[a][c]);
+            asm volatile("" : "+v"(qv));
+            qreg[a][c] = as_bf16x8(qv);
+        }
+
+    // the rest of the ring flies while the prologue computes on tile t0
+#pragma unroll
+    for (int i = 1; i < STAGES - 1; ++i)
+        if (i < ntl) issue_tile(t0 + i);
+
+    f32x16 oacc[NQ][NDB];
+    float mref[NQ], lrun[NQ][2];  // the row sum runs in two independent chains
+#pragma unroll
+    for (int a = 0; a < NQ; ++a) {
+        mref[a] = -INFINITY;
+        lrun[a][0] = lrun[a][1] = 0.f;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[a][db][e] = 0.f;
+    }
+
+    // ---- LDS byte offsets of this lane's MFMA A operands.
+    // K: row l32 of the key group, unit (2c + h) ^ (row & 7): the offset of k-chunk c is (offset of
+    // chunk 0) ^ 32 c for c < 4; the key group and c >> 2 add constants.
+    const int kof0 = l32 * ROWB + (h ^ (l32 & 7)) * 16;
+    // V (transpose read): the lane's 16-lane group fetches keys k0 .. k0 + 3 (k0 = 16 c + 4 h, + 8 for
+    // the second read) x columns d0 .. d0 + 15 (d0 = 32 db + 16 (group & 1)); this lane supplies row
+    // k0 + (lane % 16) / 4, columns d0 + 4 (lane % 4) .. + 3 and receives column d0 + lane % 16.
+    // The swizzled unit is (4 db + 2 (group & 1) + (lane % 4) / 2) ^ 2 (row & 3) = (per-lane part) ^ 4 db.
+    const int i16 = lane & 15, vrow = 4 * h + (i16 >> 2);
+    const int vof0 =
+        vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * (vrow & 3))) * 16) + (i16 & 1) * 8;
+
+    // S^T of one 64-key tile for both query blocks: s[a][kg], kg = 32-key group
+    auto qk_tile = [&](const unsigned char *tK, f32x16 (&s)[NQ][2]) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                    tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+#pragma unroll
+                for (int a = 0; a < NQ; ++a)
+                    s[a][kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[a][c], c == 0 ? zero : s[a][kg], 0, 0, 0);
+            }
+    };
+    // causal mask of an edge tile: accumulator element e of group kg holds key
+    // r0 + 32 kg + 4 h + 8 (e / 4) + e % 4
+    auto mask_tile = [&](f32x16 (&s)[NQ][2], int r0) {
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) {
+            const int lim = vis[a] - r0 - 4 * h;
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    s[a][kg][e] = (32 * kg + 8 * (e >> 2) + (e & 3)) < lim ? s[a][kg][e] : -INFINITY;
+        }
+    };
+    // reference-max decision for a tile whose per-lane logit maxima are mloc: the reference only
+    // moves when the tile max exceeds it by 2^SLACK (lazy rescale); then O and l are brought to
+    // the new reference
+    auto new_reference = [&](const float (&mloc)[NQ]) {
+        float mtile[NQ];
+        bool need[NQ];
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) {
+            mtile[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+            need[a] = mtile[a] > mref[a] + RESCALE_SLACK;
+        }
+        bool any = false;
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) any = any || need[a];
+        if (__builtin_amdgcn_ballot_w64(any) != 0) {
+#pragma unroll
+            for (int a = 0; a < NQ; ++a) {
+                const float alpha = need[a] ? __builtin_amdgcn_exp2f(mref[a] - mtile[a]) : 1.f;
+                mref[a] = need[a] ? mtile[a] : mref[a];
+                lrun[a][0] *= alpha;
+                lrun[a][1] *= alpha;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[a][db][e] *= alpha;
+            }
+        }
+    };
+    auto tile_max = [&](const f32x16 (&s)[NQ][2], float (&mloc)[NQ]) {
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) {
+            mloc[a] = max3_raw(s[a][0][0], s[a][1][0], s[a][0][0]);
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mloc[a] = max3_raw(mloc[a], s[a][0][e], s[a][1][e]);
+        }
+    };
+    // LDS fragment reads
+    auto read_k = [&](const unsigned char *tK, int i) {   // fragment i = (key group i / NC, k-chunk i % NC)
+        const int kg = i / NC, c = i % NC;
+        return as_bf16x8(*reinterpret_cast<const u32x4 *>(
+            tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+    };
+    auto read_v = [&](const unsigned char *tV, int j) {   // fragment j = (key chunk j / NDB, d block j % NDB)
+        const int kc = j / NDB, db = j % NDB;
+        const unsigned char *ap = tV + ((vof0 ^ (db * 64)) + kc * 16 * ROWB);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ap));
+        const s16x4 hi =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ap + 8 * ROWB));
+        return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // The 32 NQ exponentials a lane owes per tile are cut into 8 NQ slices of 4: slice i covers block
+    // (i / 2) % NQ, 16-key chunk i / (2 NQ), accumulator elements 8 (chunk % 2) + 4 (i % 2) .. + 3 of
+    // key group chunk / 2.  A slice goes through three steps one pipeline step apart, so that no
+    // instruction waits for the one before it: F scale and shift, E exponential, C round to bf16
+    // (the B operand of the second MFMA) and add the rounded weights to the row sum.
+    auto slice_F = [&](const f32x16 (&s)[NQ][2], int i, float (&arg)[4]) {
+        const int a = (i >> 1) % NQ, kc = i / (2 * NQ), kg = kc >> 1, cc = kc & 1, hf = i & 1;
+        const float nmuse = mref[a] == -INFINITY ? 0.f : -mref[a];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            arg[r] = __builtin_fmaf(s[a][kg][8 * cc + 4 * hf + r], p.scale_log2e, nmuse);
+            asm volatile("" : "+v"(arg[r]));   // computed here, not where the optimiser finds its use
+        }
+    };
+    auto slice_E = [&](const float (&arg)[4], float (&ex)[4]) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            ex[r] = __builtin_amdgcn_exp2f(arg[r]);
+            asm volatile("" : "+v"(ex[r]));
+        }
+    };
+    auto slice_C = [&](const float (&ex)[4], int i, bf16x8 (&pk)[NQ][4]) {
+        const int a = (i >> 1) % NQ, kc = i / (2 * NQ), hf = i & 1;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            bf16x2 pr;
+            pr[0] = (__bf16)ex[2 * r];
+            pr[1] = (__bf16)ex[2 * r + 1];
+            pk[a][kc][4 * hf + 2 * r] = pr[0];
+            pk[a][kc][4 * hf + 2 * r + 1] = pr[1];
+            const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+            lrun[a][r] = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun[a][r], false);
+            asm volatile("" : "+v"(lrun[a][r]));
+        }
+    };
+
+    const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
+    f32x16 s[NQ][2];
+    if (ntl > 0) {
+        // ---- prologue: this wave's copies of tile t0 landed before the queries did (the pin above)
+        __syncthreads();
+        qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
+        if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
+        float mloc[NQ];
+        tile_max(s, mloc);
+#pragma unroll
+        for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
+            mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+    }
+    // ---- the tile loop, software pipelined by hand (one wave per SIMD: nothing else hides a
+    // latency).  Iteration t:
+    //   stage A  the 2 NC MFMA pairs of S^T(t + 1), each issued with the K fragment read two
+    //            pairs ahead and one slice of the exponentials of tile t (vector pipe);
+    //   stage B  the 4 NDB MFMA pairs of O^T += V^T P^T(t), each with the V^T fragment read two
+    //            pairs ahead and one slice of the max scan of tile t + 1.
+    // The scheduling barriers pin that order.  Tiles t + 2 and t + 3 are in flight meanwhile.
+    // COPY: 0 no tile left to fetch, 1 the tile to fetch lies entirely in the cache, 2 decide per copy
+    auto step = [&](int t, auto next_tag, auto masked_tag, auto copy_tag) {
+        constexpr bool NEXT = decltype(next_tag)::value, MASKED = decltype(masked_tag)::value;
+        constexpr int COPY = decltype(copy_tag)::value;
+        constexpr int NA = 2 * NC, NB = 4 * NDB;
+        static_assert((NA == 16 && NB == 16) || (NA == 8 && NB == 8), "slice counts below assume D = 128 or 64");
+        constexpr int NS = 8 * NQ;                 // exponential slices per tile
+        constexpr int NG = NA < NS ? NA : NS;      // groups of slices, one group per STRIDE stage-A steps
+        constexpr int SPG = NS / NG, STRIDE = NA / NG;
+        constexpr int KAHEAD = 3, VAHEAD = 3;  // fragment reads run this many MFMA pairs ahead
+        const unsigned char *tV = smem + (size_t)(t % STAGES) * 2 * TILE_B + TILE_B;
+        const unsigned char *tK = smem + (size_t)((t + 1) % STAGES) * 2 * TILE_B;
+        f32x16 sn[NQ][2];
+        bf16x8 pk[NQ][4];
+        bf16x8 kf[KAHEAD + 1], vf[VAHEAD + 1];
+        float arg[2][SPG][4], ex[2][SPG][4];
+        if (NEXT) {
+            // tile t + 1 has landed when at most the copies of tile t + 2 remain; the barrier
+            // publishes every wave's part and retires the buffer tile t - 1 used
+            if (t + 2 < t1) wait_copies<LPW>();
+            else wait_copies<0>();
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < KAHEAD; ++i) kf[i] = read_k(tK, i);
+        }
+#pragma unroll
+        for (int e = 0; e < SPG; ++e) slice_F(s, e, arg[0][e]);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            if (NEXT) {
+                if (i + KAHEAD < NA) kf[(i + KAHEAD) % (KAHEAD + 1)] = read_k(tK, i + KAHEAD);
+                const int kg = i / NC, c = i % NC;
+#pragma unroll
+                for (int a = 0; a < NQ; ++a)
+                    sn[a][kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (KAHEAD + 1)], qreg[a][c],
+                                                                        c == 0 ? zero : sn[a][kg], 0, 0, 0);
+            }
+            if (i >= NA - VAHEAD) vf[i - (NA - VAHEAD)] = read_v(tV, i - (NA - VAHEAD));
+            if (NEXT) {
+                // the copies of tile t + 3 (into the buffer the barrier above retired), a few per
+                // step: issued in one burst they would fill the memory pipeline's queue and stall
+                // this wave -- the only one feeding this SIMD's matrix pipe
+#pragma unroll
+                for (int c = i * LPW / NA; c < (i + 1) * LPW / NA; ++c) {
+                    if (COPY == 1) issue_copy_cached(t + STAGES - 1, c);
+                    if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
+                }
+            }
+            if (i % STRIDE == 0) {
+                const int g = i / STRIDE;
+#pragma unroll
+                for (int e = 0; e < SPG; ++e) slice_E(arg[g & 1][e], ex[g & 1][e]);
+                if (g > 0) {
+#pragma unroll
+                    for (int e = 0; e < SPG; ++e) slice_C(ex[(g - 1) & 1][e], SPG * (g - 1) + e, pk);
+                }
+                if (g + 1 < NG) {
+#pragma unroll
+                    for (int e = 0; e < SPG; ++e) slice_F(s, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (NEXT && MASKED) mask_tile(sn, (t + 1) * TILE_KEYS);
+        float mch[NQ][2];  // max scan of tile t + 1 in two chains per block
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (j + VAHEAD < NB) vf[(j + VAHEAD) % (VAHEAD + 1)] = read_v(tV, j + VAHEAD);
+            if (j == 0) {
+                // the last slice's weights: first used by the last key chunk, a quarter stage away
+#pragma unroll
+                for (int e = 0; e < SPG; ++e) slice_C(ex[(NG - 1) & 1][e], SPG * (NG - 1) + e, pk);
+            }
+            const int kc = j / NDB, db = j % NDB;
+#pragma unroll
+            for (int a = 0; a < NQ; ++a)
+                oacc[a][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % (VAHEAD + 1)], pk[a][kc], oacc[a][db], 0, 0, 0);
+            if (NEXT) {
+                constexpr int PER = 16 / NB;  // accumulator elements per step (both key groups at once)
+#pragma unroll
+                for (int a = 0; a < NQ; ++a)
+#pragma unroll
+                    for (int r = 0; r < PER; ++r) {
+                        const int e = PER * j + r;
+                        s[a][0][e] = sn[a][0][e];   // tile t's logits are dead: all their slices ran in stage A
+                        s[a][1][e] = sn[a][1][e];
+                        mch[a][e & 1] = e < 2 ? max3_raw(s[a][0][e], s[a][1][e], s[a][0][e])
+                                              : max3_raw(mch[a][e & 1], s[a][0][e], s[a][1][e]);
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float mloc[NQ];
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) mloc[a] = NEXT ? max3_raw(mch[a][0], mch[a][1], mch[a][0]) : 0.f;
+        if (NEXT) {
+            new_reference(mloc);
+        }
+    };
+    // Four loops, so that the common iterations carry no decisions: (1) tile t + 1 unmasked and tile
+    // t + 3 entirely cached; (2) tile t + 1 unmasked, nothing left to fetch; (3) the general case
+    // (edge tiles: causal mask, rows from the block, partial tiles); then the last tile.
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int t = t0;
+    for (; t + STAGES - 1 < min(tint, t1); ++t) step(t, T_{}, F_{}, std::integral_constant<int, 1>{});
+    if (t + STAGES - 1 >= t1)
+        for (; t + 1 < tint; ++t) step(t, T_{}, F_{}, std::integral_constant<int, 0>{});
+    for (; t + 1 < t1; ++t) step(t, T_{}, T_{}, std::integral_constant<int, 2>{});
+    if (ntl > 0) step(t, F_{}, F_{}, std::integral_constant<int, 0>{});
+
+    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and the key sum.  Placed
+    // after the loop: the attention reads the block straight from k_new / v_new, so nothing waits
+    // for it, and its loads overlap the output stores below.
+    const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
+    const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
+    const int arows = j1 - j0;
     {
-        const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
-        const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
-        const int rows = j1 - j0;
-        for (int u = tid; u < rows * UPR * 2; u += NT) {
-            const int which = u / (rows * UPR), rem = u % (rows * UPR);
+        for (int u = tid; u < arows * UPR * 2; u += NT) {
+            const int which = u / (arows * UPR), rem = u % (arows * UPR);
             const int j = j0 + rem / UPR, unit = rem % UPR;
             const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
             *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
         }
         for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
+    }
+
+    // ---- output: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
+#pragma unroll
+    for (int a = 0; a < NQ; ++a) {
+        const float lsum = lrun[a][0] + lrun[a][1];
+        const float ltot = lsum + __shfl_xor(lsum, 32);
+        if (!valid[a]) continue;
+        const float inv = 1.f / ltot;   // every valid row of a split sees at least one key
+        if (p.splits == 1) {
+            uint16_t *op = p.out + ((size_t)(b * p.hq + kvh * p.G + qg[a]) * p.Bt + qj[a]) * D;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[a][db][4 * jj + r] * inv);
+                    *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * jj + 4 * h) = o;
+                }
+        } else {
+            // partial of this split: the normalised output in fp16 and (reference max, row sum)
+            const size_t row = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + mrow[a];
+            _Float16 *po = p.part_o + row * D;
+            const float invs = ltot > 0.f ? inv : 0.f;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    f16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * invs);
+                    *reinterpret_cast<f16x4 *>(po + 32 * db + 8 * jj + 4 * h) = o;
+                }
+            if (h == 0) p.part_ml[row] = make_float2(mref[a], ltot);
+        }
+    }
+
+    // ---- key sum of the appended slice
+    {
         double acc = 0.0;
         for (int j = j0; j < j1; ++j) {
             double x = 0.0;
@@ -164,254 +565,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             }
             acc += x;
         }
-        if (tid < D && rows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
-    }
-
-    f32x16 oacc[NDB];
-    float mref = -INFINITY, lrun = 0.f;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-
-    // ---- tile copies.  Wave w issues copies w, w + NW, ... of the K tile and of the V tile; copy s
-    // fills LDS bytes [1024 s, 1024 s + 1024) of the tile = rows RPL s .. RPL s + RPL - 1.  Lane i
-    // owns slot (row RPL s + i / UPR, unit i % UPR) and fetches the unit the swizzle puts there:
-    //   K: unit ^ (row & 7)            (ds_read_b128 of 8 consecutive rows hits 32 banks once)
-    //   V: unit ^ 2 (row & 3)          (the 4 rows x 32 bytes of a transpose read do the same)
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    uint32_t koff[CPW], voff[CPW];  // byte offset of this lane's unit inside a whole tile in memory
-    int crow[CPW];                  // its row inside the tile
-#pragma unroll
-    for (int i = 0; i < CPW; ++i) {
-        const int s = wave + NW * i;
-        const int row = RPL * s + lane / UPR, su = lane % UPR;
-        crow[i] = row;
-        koff[i] = (uint32_t)(row * ROWB + ((su ^ (row & 7)) & (UPR - 1)) * 16);
-        voff[i] = (uint32_t)(row * ROWB + ((su ^ (2 * (row & 3))) & (UPR - 1)) * 16);
-    }
-    // A tile is "whole" when its 64 rows are valid and come from one source (the cache, or the
-    // block's k_new / v_new): then only the base pointer differs.  A partial tile (it straddles len
-    // or n; at most two per step) takes per-row pointers; rows past n read row n - 1 -- finite
-    // data whose logits are masked, so it is never zeroed.
-    auto issue_tile = [&](int t) {
-        const int r0 = t * TILE_KEYS;
-        const uint32_t kdst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B), vdst = kdst + TILE_B;
-        const bool whole = r0 + TILE_KEYS <= p.len || (r0 >= p.len && r0 + TILE_KEYS <= p.n);
-        if (whole) {
-            const bool cached = r0 < p.len;
-            const uint16_t *kt = cached ? kcache + (size_t)r0 * D : knew + (size_t)(r0 - p.len) * D;
-            const uint16_t *vt = cached ? vcache + (size_t)r0 * D : vnew + (size_t)(r0 - p.len) * D;
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) async_copy16(kdst + 1024u * (wave + NW * i), kt, koff[i]);
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) async_copy16(vdst + 1024u * (wave + NW * i), vt, voff[i]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int rc = min(r0 + crow[i], p.n - 1);
-                const uint16_t *src = rc < p.len ? kcache + (size_t)rc * D : knew + (size_t)(rc - p.len) * D;
-                async_copy16(kdst + 1024u * (wave + NW * i),
-                             reinterpret_cast<const char *>(src) + (koff[i] - crow[i] * ROWB));
-            }
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int rc = min(r0 + crow[i], p.n - 1);
-                const uint16_t *src = rc < p.len ? vcache + (size_t)rc * D : vnew + (size_t)(rc - p.len) * D;
-                async_copy16(vdst + 1024u * (wave + NW * i),
-                             reinterpret_cast<const char *>(src) + (voff[i] - crow[i] * ROWB));
-            }
-        }
-    };
-
-    // ---- LDS byte offsets of this lane's MFMA A operands.
-    // K: row l32 of the key group, unit (2c + h) ^ (row & 7): the offset of k-chunk c is (offset of
-    // chunk 0) ^ 32 c for c < 4; the key group and c >> 2 add constants.
-    const int kof0 = l32 * ROWB + (h ^ (l32 & 7)) * 16;
-    // V (transpose read): the lane's 16-lane group fetches keys k0 .. k0 + 3 (k0 = 16 c + 4 h, + 8 for
-    // the second read) x columns d0 .. d0 + 15 (d0 = 32 db + 16 (group & 1)); this lane supplies row
-    // k0 + (lane % 16) / 4, columns d0 + 4 (lane % 4) .. + 3 and receives column d0 + lane % 16.
-    // The swizzled unit is (4 db + 2 (group & 1) + (lane % 4) / 2) ^ 2 (row & 3) = (per-lane part) ^ 4 db.
-    const int i16 = lane & 15, vrow = 4 * h + (i16 >> 2);
-    const int vof0 =
-        vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * (vrow & 3))) * 16) + (i16 & 1) * 8;
-
-    // One 64-key tile.  Operand reads are issued a phase ahead of the MFMAs that consume them so
-    // that LDS latency hides behind matrix and vector work: K operands of both 32-key groups, then
-    // the V^T operands of group 0 while S is still in the matrix pipe; one reference-max decision
-    // per tile; then a straight-line block (softmax 0, PV 0, softmax 1, PV 1) in which the PV MFMAs
-    // of one group overlap the exponentials of the other.
-    auto read_k = [&](const unsigned char *tK, int kg, bf16x8 (&ka)[NC]) {
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-            ka[c] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
-    };
-    auto read_v = [&](const unsigned char *tV, int kg, bf16x8 (&va)[NDB][2]) {
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int cc = 0; cc < 2; ++cc) {
-                const unsigned char *a = tV + ((vof0 ^ (db * 64)) + (2 * kg + cc) * 16 * ROWB);
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a));
-                const s16x4 hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a + 8 * ROWB));
-                va[db][cc] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-    };
-    auto qk = [&](const bf16x8 (&ka)[NC]) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qreg[0], zero, 0, 0, 0);
-#pragma unroll
-        for (int c = 1; c < NC; ++c) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qreg[c], acc, 0, 0, 0);
-        return acc;
-    };
-    // exponentials of one group -> bf16 B operands; the row sum adds the rounded weights the
-    // second MFMA multiplies with
-    auto softmax = [&](const f32x16 &sacc, float nmuse, bf16x8 (&pk)[2]) {
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-            bf16x8 v;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                v[i] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 * cc + i], p.scale_log2e, nmuse));
-            pk[cc] = v;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                bf16x2 pr = {v[2 * i], v[2 * i + 1]};
-                const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-                lrun = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun, false);
-            }
-        }
-    };
-    auto pv = [&](const bf16x8 (&va)[NDB][2], const bf16x8 (&pk)[2]) {
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cc], pk[cc], oacc[db], 0, 0, 0);
-    };
-    // first half of a tile: S^T of both key groups (+ causal mask on edge tiles)
-    auto s_phase = [&](const unsigned char *tK, int r0, f32x16 &s0, f32x16 &s1, auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        bf16x8 ka0[NC], ka1[NC];
-        read_k(tK, 0, ka0);
-        read_k(tK, 1, ka1);
-        s0 = qk(ka0);
-        s1 = qk(ka1);
-        if (MASKED) {
-            // accumulator element e of group kg holds key r0 + 32 kg + 4 h + 8 (e / 4) + e % 4
-            const int lim = vis - r0 - 4 * h;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s0[e] = (8 * (e >> 2) + (e & 3)) < lim ? s0[e] : -INFINITY;
-                s1[e] = (32 + 8 * (e >> 2) + (e & 3)) < lim ? s1[e] : -INFINITY;
-            }
-        }
-    };
-    // second half: reference-max decision, exponentials, O^T += V^T P^T
-    auto pv_phase = [&](const unsigned char *tV, const f32x16 &s0, const f32x16 &s1) {
-        bf16x8 va0[NDB][2], va1[NDB][2];
-        read_v(tV, 0, va0);
-        float mloc = fmaxf(s0[0], s1[0]);
-#pragma unroll
-        for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, fmaxf(s0[e], s1[e]));
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float mtile = mloc * p.scale_log2e;
-        // lazy rescale: the reference max only moves when the tile max exceeds it by 2^SLACK
-        const bool need = mtile > mref + RESCALE_SLACK;
-        if (__builtin_amdgcn_ballot_w64(need) != 0) {
-            const float alpha = need ? __builtin_amdgcn_exp2f(mref - mtile) : 1.f;
-            mref = need ? mtile : mref;
-            lrun *= alpha;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-        }
-        const float nmuse = mref == -INFINITY ? 0.f : -mref;
-        bf16x8 pk0[2], pk1[2];
-        softmax(s0, nmuse, pk0);
-        read_v(tV, 1, va1);
-        pv(va0, pk0);
-        softmax(s1, nmuse, pk1);
-        pv(va1, pk1);
-    };
-
-    // Pin the query registers here: their global loads must not be pending when the tile loop
-    // starts (the explicit copy waits below count outstanding memory operations).
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        u32x4 qv = __builtin_bit_cast(u32x4, qreg[c]);
-        asm volatile("" : "+v"(qv));
-        qreg[c] = as_bf16x8(qv);
-    }
-
-    // ---- the ring.  Waves [0, NW/2) ("early") run both halves of tile t in iteration t; waves
-    // [NW/2, NW) ("late") -- the second wave on each SIMD -- run the second half one iteration
-    // behind: [second half of t - 1, first half of t].  The per-tile barrier would otherwise keep
-    // all waves in the same phase, and the two waves of a SIMD would queue for the same pipe
-    // (matrix, vector or LDS) instead of overlapping MFMAs with exponentials.  The V tile of
-    // t - 1 therefore stays live during iteration t: with STAGES buffers, STAGES - 2 tiles are
-    // in flight.
-    const bool late = wave >= NW / 2;
-    const int ntl = t1 - t0;
-#pragma unroll
-    for (int i = 0; i < STAGES - 2; ++i)
-        if (i < ntl) issue_tile(t0 + i);
-    const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
-    f32x16 sp0, sp1;  // S of the previous tile (late waves)
-    auto step = [&](int t, auto masked_tag) {
-        // this wave's copies of tile t have landed when at most the copies of the later tile in
-        // flight remain; the barrier then publishes every wave's part and retires tile t - 2
-        if (t + 1 < t1) wait_copies<LPW>();
-        else wait_copies<0>();
-        __syncthreads();
-        if (t + STAGES - 2 < t1) issue_tile(t + STAGES - 2);  // into the buffer tile t - 2 left
-        const unsigned char *tK = smem + (size_t)(t % STAGES) * 2 * TILE_B;
-        if (!late) {
-            f32x16 s0, s1;
-            s_phase(tK, t * TILE_KEYS, s0, s1, masked_tag);
-            pv_phase(tK + TILE_B, s0, s1);
-        } else {
-            if (t > t0) pv_phase(smem + (size_t)((t - 1) % STAGES) * 2 * TILE_B + TILE_B, sp0, sp1);
-            s_phase(tK, t * TILE_KEYS, sp0, sp1, masked_tag);
-        }
-    };
-    static_assert(STAGES == 4, "the wait ladder in step() assumes two tiles in flight");
-    // interior and edge tiles run in separate loops so that the rare masked path does not weigh on
-    // the register allocation of the hot one
-    for (int t = t0; t < tint; ++t) step(t, std::false_type{});
-    for (int t = tint; t < t1; ++t) step(t, std::true_type{});
-    if (late && ntl > 0) pv_phase(smem + (size_t)((t1 - 1) % STAGES) * 2 * TILE_B + TILE_B, sp0, sp1);
-
-    // ---- epilogue: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
-    const float ltot = lrun + __shfl_xor(lrun, 32);
-    if (!valid) return;
-    if (p.splits == 1) {
-        uint16_t *op = p.out + ((size_t)(b * p.hq + kvh * p.G + qg) * p.Bt + qj) * D;
-        const float inv = 1.f / ltot;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                bf16x4 o;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[db][4 * jj + r] * inv);
-                *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * jj + 4 * h) = o;
-            }
-    } else {
-        const size_t row = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + m;
-        float *po = p.part_o + row * D;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                float4 o = make_float4(oacc[db][4 * jj], oacc[db][4 * jj + 1], oacc[db][4 * jj + 2],
-                                       oacc[db][4 * jj + 3]);
-                *reinterpret_cast<float4 *>(po + 32 * db + 8 * jj + 4 * h) = o;
-            }
-        if (h == 0) p.part_ml[row] = make_float2(mref, ltot);
+        if (tid < D && arows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
     }
 }
 
@@ -424,10 +578,10 @@ hipError_t configure_main_kernels()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             (int)main_lds_bytes(D));                                               \
     if (e != hipSuccess) return e;
-    KD_SET((step_main_kernel<128, 8>), 128)
-    KD_SET((step_main_kernel<128, 4>), 128)
-    KD_SET((step_main_kernel<64, 8>), 64)
-    KD_SET((step_main_kernel<64, 4>), 64)
+    KD_SET((step_main_kernel<128, 8, 1>), 128)
+    KD_SET((step_main_kernel<128, 4, 1>), 128)
+    KD_SET((step_main_kernel<64, 8, 1>), 64)
+    KD_SET((step_main_kernel<64, 4, 1>), 64)
 #undef KD_SET
     return hipSuccess;
 }
@@ -436,10 +590,10 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 {
     const int grid = p.batch * p.hkv * p.mtiles * p.splits;
     const size_t lds = main_lds_bytes(p.D);
-    if (p.D == 128 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<128, 8>), dim3(grid), dim3(512), lds, s, p);
-    else if (p.D == 128 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<128, 4>), dim3(grid), dim3(256), lds, s, p);
-    else if (p.D == 64 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<64, 8>), dim3(grid), dim3(512), lds, s, p);
-    else if (p.D == 64 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<64, 4>), dim3(grid), dim3(256), lds, s, p);
+    if (p.D == 128 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<128, 8, 1>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 128 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<128, 4, 1>), dim3(grid), dim3(256), lds, s, p);
+    else if (p.D == 64 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<64, 8, 1>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 64 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<64, 4, 1>), dim3(grid), dim3(256), lds, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

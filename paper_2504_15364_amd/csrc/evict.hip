@@ -17,6 +17,7 @@ namespace kd {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int NWAVES = POST_THREADS / 64;
@@ -552,22 +553,23 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     float L = 0.f;
     for (int s0 = 0; s0 < p.splits; s0 += MB) {
         float2 ml[MB];
-        float4 o[MB];
+        f16x4 o[MB];
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
             const bool live = s0 + i < p.splits;
+            const f16x4 zero = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
             ml[i] = live ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
-            o[i] = live ? *reinterpret_cast<const float4 *>(p.part_o + ((size_t)(s0 + i) * rows + row) * D + 4 * d4)
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
+            o[i] = live ? *reinterpret_cast<const f16x4 *>(p.part_o + ((size_t)(s0 + i) * rows + row) * D + 4 * d4) : zero;
         }
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-            const float w = ml[i].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[i].x - mx);
-            acc.x += w * o[i].x;
-            acc.y += w * o[i].y;
-            acc.z += w * o[i].z;
-            acc.w += w * o[i].w;
-            L += w * ml[i].y;
+            // a partial is its split's output normalised by its own row sum: weight it by that sum
+            const float w = ml[i].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[i].x - mx) * ml[i].y;
+            acc.x += w * (float)o[i][0];
+            acc.y += w * (float)o[i][1];
+            acc.z += w * (float)o[i][2];
+            acc.w += w * (float)o[i][3];
+            L += w;
         }
     }
     const float inv = 1.f / L;

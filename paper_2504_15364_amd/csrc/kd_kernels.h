@@ -36,7 +36,7 @@ struct StepParams {
     double *ksum;                    // [BH][D] running sum of the (raw or unit) keys in the cache
     int32_t *status;
     // scratch
-    float *part_o;                   // [splits][BH * G * Bt][D] unnormalised partial outputs
+    _Float16 *part_o;                // [splits][BH * G * Bt][D] partial outputs, each normalised by its row sum
     float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1

@@ -74,7 +74,7 @@ Layout make_layout(const keydiff_config_t *c)
     L.max_part_rows = (int)(by_tiles < by_rows ? by_tiles : by_rows);
     const size_t chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
     off = 0;
-    L.off_part_o = off;     off += align256((size_t)L.max_part_rows * D * 4);
+    L.off_part_o = off;     off += align256((size_t)L.max_part_rows * D * 2);
     L.off_part_ml = off;    off += align256((size_t)L.max_part_rows * 8);
     L.off_scores = off;     off += align256(BH * L.cap * 4);
     L.off_dstmap = off;     off += align256(BH * L.cap * 4);
@@ -157,7 +157,7 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
     p.ksum = reinterpret_cast<double *>(c->meta + c->L.off_ksum);
     p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
-    p.part_o = reinterpret_cast<float *>(c->scratch + c->L.off_part_o);
+    p.part_o = reinterpret_cast<_Float16 *>(c->scratch + c->L.off_part_o);
     p.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
     p.scores = reinterpret_cast<float *>(c->scratch + c->L.off_scores);
     p.dstmap = reinterpret_cast<int32_t *>(c->scratch + c->L.off_dstmap);
