@@ -134,16 +134,18 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     // ---- tile copies.  Wave w issues copies w, w + NW, ... of the K tile and of the V tile; copy s
     // fills LDS bytes [1024 s, 1024 s + 1024) of the tile = rows RPL s .. RPL s + RPL - 1.  Lane i
     // owns slot (row RPL s + i / UPR, unit i % UPR) and fetches the unit the swizzle puts there:
-    //   K: unit ^ (row & 7)            (ds_read_b128 of 8 consecutive rows hits 32 banks once)
+    //   K: unit ^ (row % UPR)          (LDS serves 256 bytes per clock to ds_read_b128: the 16 rows a
+    //                                   clock covers must spread over 16 distinct 16-byte units)
     //   V: unit ^ 2 (row & 3)          (the 4 rows x 32 bytes of a transpose read do the same)
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     // Copy i of a wave covers rows RPL (wave + NW i) ..: NW RPL is a multiple of 8, so the swizzle
-    // terms (row & 7, row & 3) are those of copy 0 and copy i only adds i NW RPL rows.
-    static_assert((NW * RPL) % 8 == 0, "the swizzle of a lane must not depend on the copy index");
+    // terms (row % UPR, row & 3) are those of copy 0 and copy i only adds i NW RPL rows.
+    static_assert((NW * RPL) % UPR == 0, "the swizzle of a lane must not depend on the copy index");
+    constexpr int VSW = UPR / 4;     // V swizzle stride: unit ^ VSW (row & 3)
     constexpr int CSTEP = NW * RPL;  // rows between consecutive copies of one wave
     const int crow0 = RPL * wave + lane / UPR;   // row of copy 0 inside the tile
-    const uint32_t koff0 = (uint32_t)(crow0 * ROWB + (((lane % UPR) ^ (crow0 & 7)) & (UPR - 1)) * 16);
-    const uint32_t voff0 = (uint32_t)(crow0 * ROWB + (((lane % UPR) ^ (2 * (crow0 & 3))) & (UPR - 1)) * 16);
+    const uint32_t koff0 = (uint32_t)(crow0 * ROWB + ((lane % UPR) ^ (crow0 & (UPR - 1))) * 16);
+    const uint32_t voff0 = (uint32_t)(crow0 * ROWB + ((lane % UPR) ^ (VSW * (crow0 & 3))) * 16);
     // A tile is "whole" when its 64 rows are valid and come from one source (the cache, or the
     // block's k_new / v_new): then only the base pointer differs.  A partial tile (it straddles len
     // or n; at most two per step) takes per-row pointers; rows past n read row n - 1 -- finite
@@ -235,14 +237,14 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     // ---- LDS byte offsets of this lane's MFMA A operands.
     // K: row l32 of the key group, unit (2c + h) ^ (row & 7): the offset of k-chunk c is (offset of
     // chunk 0) ^ 32 c for c < 4; the key group and c >> 2 add constants.
-    const int kof0 = l32 * ROWB + (h ^ (l32 & 7)) * 16;
+    const int kof0 = l32 * ROWB + (h ^ (l32 & (UPR - 1))) * 16;
     // V (transpose read): the lane's 16-lane group fetches keys k0 .. k0 + 3 (k0 = 16 c + 4 h, + 8 for
     // the second read) x columns d0 .. d0 + 15 (d0 = 32 db + 16 (group & 1)); this lane supplies row
     // k0 + (lane % 16) / 4, columns d0 + 4 (lane % 4) .. + 3 and receives column d0 + lane % 16.
     // The swizzled unit is (4 db + 2 (group & 1) + (lane % 4) / 2) ^ 2 (row & 3) = (per-lane part) ^ 4 db.
     const int i16 = lane & 15, vrow = 4 * h + (i16 >> 2);
     const int vof0 =
-        vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * (vrow & 3))) * 16) + (i16 & 1) * 8;
+        vrow * ROWB + (((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (VSW * (vrow & 3))) * 16) + (i16 & 1) * 8;
 
     // S^T of one 64-key tile for both query blocks: s[a][kg], kg = 32-key group
     auto qk_tile = [&](const unsigned char *tK, f32x16 (&s)[NQ][2]) {
@@ -252,7 +254,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                    tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+                    tK + ((kof0 ^ (c * 32)) + kg * 32 * ROWB)));
 #pragma unroll
                 for (int a = 0; a < NQ; ++a)
                     s[a][kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[a][c], c == 0 ? zero : s[a][kg], 0, 0, 0);
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     auto read_k = [&](const unsigned char *tK, int i) {   // fragment i = (key group i / NC, k-chunk i % NC)
         const int kg = i / NC, c = i % NC;
         return as_bf16x8(*reinterpret_cast<const u32x4 *>(
-            tK + ((kof0 ^ ((c & 3) * 32)) + kg * 32 * ROWB + (c >> 2) * 128)));
+            tK + ((kof0 ^ (c * 32)) + kg * 32 * ROWB)));
     };
     auto read_v = [&](const unsigned char *tV, int j) {   // fragment j = (key chunk j / NDB, d block j % NDB)
         const int kc = j / NDB, db = j % NDB;
@@ -487,62 +489,48 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     if (t + STAGES - 1 >= t1)
         for (; t + 1 < tint; ++t) step(t, T_{}, F_{}, std::integral_constant<int, 0>{});
     for (; t + 1 < t1; ++t) step(t, T_{}, T_{}, std::integral_constant<int, 2>{});
-    if (ntl > 0) step(t, F_{}, F_{}, std::integral_constant<int, 0>{});
 
-    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and the key sum.  Placed
-    // after the loop: the attention reads the block straight from k_new / v_new, so nothing waits
-    // for it, and its loads overlap the output stores below.
+    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and their sum for the anchor.
+    // The attention reads the block straight from k_new / v_new, so nothing waits for the append:
+    // its loads are issued here, fly during the last tile, and are stored after it.
     const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
     const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
     const int arows = j1 - j0;
-    {
+    constexpr int KPRE = 4;                                  // rows of the slice summed from registers
+    const bool small = arows * UPR * 2 <= NT && arows <= KPRE && p.anchor_mode == 0;
+    u32x4 aval = {0u, 0u, 0u, 0u};
+    uint32_t kx[KPRE] = {0u, 0u, 0u, 0u};
+    if (small) {
+        if (tid < arows * UPR * 2) {
+            const int which = tid / (arows * UPR), rem = tid % (arows * UPR);
+            aval = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)(j0 + rem / UPR) * D + (rem % UPR) * 8);
+        }
+        if (tid < D)
+#pragma unroll
+            for (int r = 0; r < KPRE; ++r)
+                if (r < arows) kx[r] = knew[(size_t)(j0 + r) * D + tid];
+    }
+
+    if (ntl > 0) step(t, F_{}, F_{}, std::integral_constant<int, 0>{});
+
+    if (small) {
+        if (tid < arows * UPR * 2) {
+            const int which = tid / (arows * UPR), rem = tid % (arows * UPR);
+            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j0 + rem / UPR) * D + (rem % UPR) * 8) = aval;
+        }
+        if (tid < D && arows > 0) {
+            double acc = 0.0;
+#pragma unroll
+            for (int r = 0; r < KPRE; ++r) acc += (double)__uint_as_float(kx[r] << 16);   // absent rows hold +0
+            unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
+        }
+    } else {
         for (int u = tid; u < arows * UPR * 2; u += NT) {
             const int which = u / (arows * UPR), rem = u % (arows * UPR);
             const int j = j0 + rem / UPR, unit = rem % UPR;
             const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
             *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
         }
-        for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
-    }
-
-    // ---- output: accumulator element e of d-block db is d = 32 db + 8 (e/4) + 4 h + e%4
-#pragma unroll
-    for (int a = 0; a < NQ; ++a) {
-        const float lsum = lrun[a][0] + lrun[a][1];
-        const float ltot = lsum + __shfl_xor(lsum, 32);
-        if (!valid[a]) continue;
-        const float inv = 1.f / ltot;   // every valid row of a split sees at least one key
-        if (p.splits == 1) {
-            uint16_t *op = p.out + ((size_t)(b * p.hq + kvh * p.G + qg[a]) * p.Bt + qj[a]) * D;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[a][db][4 * jj + r] * inv);
-                    *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * jj + 4 * h) = o;
-                }
-        } else {
-            // partial of this split: the normalised output in fp16 and (reference max, row sum)
-            const size_t row = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + mrow[a];
-            _Float16 *po = p.part_o + row * D;
-            const float invs = ltot > 0.f ? inv : 0.f;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    f16x4 o;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * invs);
-                    *reinterpret_cast<f16x4 *>(po + 32 * db + 8 * jj + 4 * h) = o;
-                }
-            if (h == 0) p.part_ml[row] = make_float2(mref[a], ltot);
-        }
-    }
-
-    // ---- key sum of the appended slice
-    {
         double acc = 0.0;
         for (int j = j0; j < j1; ++j) {
             double x = 0.0;
@@ -566,6 +554,69 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             acc += x;
         }
         if (tid < D && arows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
+    }
+    for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
+
+    // ---- output.  Accumulator element e of d-block db is d = 32 db + 8 (e / 4) + 4 h + e % 4 of
+    // query l32: 8-byte pieces of 32 different rows, which as direct stores would cost one memory
+    // transaction per piece.  Each wave transposes its 32 NQ rows through a private piece of LDS
+    // (the two ring buffers no tile occupies after the last barrier) and stores whole rows, 16
+    // bytes per lane; the rows of a wave are contiguous in memory in both output forms.
+    {
+        constexpr int WROWS = 32 * NQ, WBYTES = WROWS * ROWB;
+        static_assert(NW * WBYTES <= 2 * 2 * TILE_B, "the transposition uses two ring buffers");
+        // stages (t1 + 1) % STAGES and t1 % STAGES: tiles t1 - 3 and t1 - 4 (or never filled)
+        const int region = wave * WBYTES;
+        auto stage_ptr = [&](int off) {   // byte `off` of the 2-buffer scratch area
+            const int half = off / (2 * TILE_B);
+            return smem + (size_t)((t1 + 1 - half + STAGES) % STAGES) * 2 * TILE_B + (off - half * 2 * TILE_B);
+        };
+        const bool direct = p.splits == 1;
+        float ltot[NQ];
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) {
+            const float lsum = lrun[a][0] + lrun[a][1];
+            ltot[a] = lsum + __shfl_xor(lsum, 32);
+            const float inv = ltot[a] > 0.f ? 1.f / ltot[a] : 0.f;   // a row of a split may see no key at all
+            const int row = 32 * a + l32;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    // 16-byte unit 4 db + jj of the row, swizzled by the row; lane half h takes 8 bytes
+                    unsigned char *dst = stage_ptr(region + row * ROWB + (((4 * db + jj) ^ (row & (UPR - 1))) * 16) + 8 * h);
+                    if (direct) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[a][db][4 * jj + r] * inv);
+                        *reinterpret_cast<bf16x4 *>(dst) = o;
+                    } else {
+                        f16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * inv);
+                        *reinterpret_cast<f16x4 *>(dst) = o;
+                    }
+                }
+        }
+        // rows of this wave: m = mbase .. mbase + WROWS - 1
+        const int mbase = mt * TM + wave * WROWS;
+        unsigned char *gbase;
+        if (direct) {
+            gbase = reinterpret_cast<unsigned char *>(p.out + ((size_t)(b * p.hq + kvh * p.G) * p.Bt + mbase) * D);
+        } else {
+            const size_t prow = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + mbase;
+            gbase = reinterpret_cast<unsigned char *>(p.part_o + prow * D);
+#pragma unroll
+            for (int a = 0; a < NQ; ++a)
+                if (h == 0 && valid[a]) p.part_ml[prow + 32 * a + l32] = make_float2(mref[a], ltot[a]);
+        }
+        constexpr int RPI = 1024 / ROWB;   // rows one wave-wide 16-byte-per-lane store covers
+#pragma unroll
+        for (int i = 0; i < WBYTES / 1024; ++i) {
+            const int row = RPI * i + lane / UPR, unit = lane % UPR;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(stage_ptr(region + row * ROWB + ((unit ^ (row & (UPR - 1))) * 16)));
+            if (mbase + row < Mtot) *reinterpret_cast<u32x4 *>(gbase + (size_t)row * ROWB + unit * 16) = val;
+        }
     }
 }
 
