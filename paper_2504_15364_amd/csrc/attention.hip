@@ -310,8 +310,10 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         }
     };
     // LDS fragment reads
-    auto read_k = [&](const unsigned char *tK, int i) {   // fragment i = (key group i / NC, k-chunk i % NC)
-        const int kg = i / NC, c = i % NC;
+    // fragment i = (key group i % 2, k-chunk i / 2): consecutive MFMAs alternate between the two
+    // accumulators, so none waits for the result of the one before it
+    auto read_k = [&](const unsigned char *tK, int i) {
+        const int kg = i % 2, c = i / 2;
         return as_bf16x8(*reinterpret_cast<const u32x4 *>(
             tK + ((kof0 ^ (c * 32)) + kg * 32 * ROWB)));
     };
@@ -385,9 +387,39 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         constexpr int COPY = decltype(copy_tag)::value;
         constexpr int NA = 2 * NC, NB = 4 * NDB;
         static_assert((NA == 16 && NB == 16) || (NA == 8 && NB == 8), "slice counts below assume D = 128 or 64");
+        // The exponential slices are spread evenly over stage A and the first half of stage B (whose
+        // second half multiplies with the weights computed last): group g runs in slot g SLOTS / NG,
+        // slots [0, NA) being the steps of stage A and [NA, SLOTS) steps of stage B.
         constexpr int NS = 8 * NQ;                 // exponential slices per tile
-        constexpr int NG = NA < NS ? NA : NS;      // groups of slices, one group per STRIDE stage-A steps
-        constexpr int SPG = NS / NG, STRIDE = NA / NG;
+        constexpr int SLOTS = NA + NB / 2;
+        constexpr int SPG = NS > SLOTS ? 2 : 1;    // slices per group
+        constexpr int NG = NS / SPG;
+        auto slot_of = [](int g) { return g * SLOTS / NG; };
+        // the max scan of stage B (16 / NB accumulator elements per step) overwrites tile t's logits:
+        // every group must have read its logits (F, one beat before its own) by then
+        constexpr bool order_ok = [] {
+            for (int g = 1; g < NG; ++g) {
+                const int sl = SPG * g, kc = sl / (2 * NQ), e0 = 8 * (kc & 1) + 4 * (sl & 1);
+                if ((g - 1) * SLOTS / NG > NA + e0 / (16 / NB)) return false;
+            }
+            return true;
+        }();
+        static_assert(order_ok, "an exponential group would read logits the max scan already replaced");
+        // one pipeline beat: E of group g, C of group g - 1, F of group g + 1
+        auto beat = [&](int g, float (&arg)[2][SPG][4], float (&ex)[2][SPG][4], bf16x8 (&pk)[NQ][4]) {
+            if (g < NG) {
+#pragma unroll
+                for (int e = 0; e < SPG; ++e) slice_E(arg[g & 1][e], ex[g & 1][e]);
+            }
+            if (g > 0) {
+#pragma unroll
+                for (int e = 0; e < SPG; ++e) slice_C(ex[(g - 1) & 1][e], SPG * (g - 1) + e, pk);
+            }
+            if (g + 1 < NG) {
+#pragma unroll
+                for (int e = 0; e < SPG; ++e) slice_F(s, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
+            }
+        };
         constexpr int KAHEAD = 3, VAHEAD = 3;  // fragment reads run this many MFMA pairs ahead
         const unsigned char *tV = smem + (size_t)(t % STAGES) * 2 * TILE_B + TILE_B;
         const unsigned char *tK = smem + (size_t)((t + 1) % STAGES) * 2 * TILE_B;
@@ -411,7 +443,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         for (int i = 0; i < NA; ++i) {
             if (NEXT) {
                 if (i + KAHEAD < NA) kf[(i + KAHEAD) % (KAHEAD + 1)] = read_k(tK, i + KAHEAD);
-                const int kg = i / NC, c = i % NC;
+                const int kg = i % 2, c = i / 2;
 #pragma unroll
                 for (int a = 0; a < NQ; ++a)
                     sn[a][kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (KAHEAD + 1)], qreg[a][c],
@@ -428,19 +460,9 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
                     if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
                 }
             }
-            if (i % STRIDE == 0) {
-                const int g = i / STRIDE;
 #pragma unroll
-                for (int e = 0; e < SPG; ++e) slice_E(arg[g & 1][e], ex[g & 1][e]);
-                if (g > 0) {
-#pragma unroll
-                    for (int e = 0; e < SPG; ++e) slice_C(ex[(g - 1) & 1][e], SPG * (g - 1) + e, pk);
-                }
-                if (g + 1 < NG) {
-#pragma unroll
-                    for (int e = 0; e < SPG; ++e) slice_F(s, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
-                }
-            }
+            for (int g = 0; g < NG; ++g)
+                if (slot_of(g) == i) beat(g, arg, ex, pk);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (NEXT && MASKED) mask_tile(sn, (t + 1) * TILE_KEYS);
@@ -448,11 +470,12 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             if (j + VAHEAD < NB) vf[(j + VAHEAD) % (VAHEAD + 1)] = read_v(tV, j + VAHEAD);
-            if (j == 0) {
-                // the last slice's weights: first used by the last key chunk, a quarter stage away
+            // remaining exponential groups; the last beat only rounds the last group's weights.  A
+            // group's logits are read (F) before the max scan below overwrites them: its first
+            // element 8 cc + 4 hf is overwritten in step (8 cc + 4 hf) / PER, F runs a beat earlier.
 #pragma unroll
-                for (int e = 0; e < SPG; ++e) slice_C(ex[(NG - 1) & 1][e], SPG * (NG - 1) + e, pk);
-            }
+            for (int g = 0; g <= NG; ++g)
+                if ((g < NG ? slot_of(g) : slot_of(NG - 1) + 1) == NA + j) beat(g, arg, ex, pk);
             const int kc = j / NDB, db = j % NDB;
 #pragma unroll
             for (int a = 0; a < NQ; ++a)

@@ -21,6 +21,8 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int NWAVES = POST_THREADS / 64;
+constexpr int SPT_SMALL = 12;                       // scores per thread: caches of up to 12288 rows
+constexpr int SPT_LARGE = MAX_CAP / POST_THREADS;   // ... and up to the limit
 constexpr int SCORE_WAVES = SCORE_THREADS / 64;
 
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
@@ -299,17 +301,52 @@ __device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const f
 // ------------------------------------------------------------- select + compaction
 // `lists` holds three arrays of E row indices (evicted | holes | movers): in LDS when
 // they fit, else in the scratch buffer.
-template <int D>
+// SPT: scores per thread the instantiation can hold (n <= SPT * POST_THREADS)
+template <int D, int SPT>
 __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int32_t *lists, int bh)
 {
     constexpr int UPR = D / 8;
+    // 16-byte units of the tail rows a thread keeps in registers (the large instantiation has none to spare)
+    constexpr int TAILU = SPT * POST_THREADS < MAX_CAP ? 8 : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = p.n - p.N;
     const float *sc = p.scores + (size_t)bh * p.cap;
     int32_t *pos = p.pos + (size_t)bh * p.cap;
+    uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    uint16_t *vb = p.v + (size_t)bh * p.cap * D;
 
-    // ---- 1. scores into registers (coalesced), histogram of the non-exempt ones in LDS
-    constexpr int SPT = MAX_CAP / POST_THREADS;  // scores per thread, at most
+    // ---- 0. every load that does not depend on the selection is issued here, so that the chain
+    // below costs one memory round trip now and one for the evicted rows later: the scores and
+    // positions of all rows, the running key sum, and (FILL layout) the K/V rows [N, n), the only
+    // ones that can move.
+    float sv[SPT];
+    int32_t sp[SPT];
+#pragma unroll
+    for (int k = 0; k < SPT; ++k) {
+        const int i = k * POST_THREADS + tid;
+        sv[k] = 0.f;
+        sp[k] = 0;
+        if (k * POST_THREADS < p.n && i < p.n) {
+            sv[k] = sc[i];
+            sp[k] = pos[i];
+        }
+    }
+    const double ksum_old = tid < D ? p.ksum[(size_t)bh * D + tid] : 0.0;
+    const bool tail_regs = TAILU > 0 && p.layout == 1 && 2 * E * UPR <= TAILU * POST_THREADS;
+    u32x4 tailv[TAILU > 0 ? TAILU : 1];
+    if (tail_regs) {
+#pragma unroll
+        for (int q = 0; q < TAILU; ++q) {
+            const int w = q * POST_THREADS + tid;
+            tailv[q] = u32x4{0u, 0u, 0u, 0u};
+            if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
+                const int which = w / (E * UPR), rem = w % (E * UPR);
+                tailv[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)(p.N + rem / UPR) * D + (rem % UPR) * 8);
+            }
+        }
+    }
+
+    // ---- 1. histogram of the non-exempt scores in LDS
     const int nwords = (p.n + 31) / 32;
     for (int i = tid; i < nwords; i += POST_THREADS) evbits[i] = 0;
     for (int i = tid; i < HIST_BINS; i += POST_THREADS) sh.hist[i] = 0;
@@ -319,24 +356,12 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         sh.tb = 0;
         sh.need = 0;
     }
-    float sv[SPT];
-    int sbin[SPT];  // -1: not a candidate for eviction (exempt or past the end)
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = k * POST_THREADS + tid;
-        sv[k] = 0.f;
-        sbin[k] = -1;
-        if (k * POST_THREADS < p.n && i < p.n) sv[k] = sc[i];
-    }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < SPT; ++k) {
         const int i = k * POST_THREADS + tid;
         if (k * POST_THREADS >= p.n) break;
-        if (i < p.n && !(p.window_W > 0 && pos[i] >= p.window_pos_min)) {
-            sbin[k] = score_bin(sv[k]);
-            atomicAdd(&sh.hist[sbin[k]], 1u);
-        }
+        if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) atomicAdd(&sh.hist[score_bin(sv[k])], 1u);
     }
     __syncthreads();
 
@@ -372,30 +397,38 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     for (int k = 0; k < SPT; ++k) {
         const int i = k * POST_THREADS + tid;
         if (k * POST_THREADS >= p.n) break;
-        if (sbin[k] > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
-        else if (sbin[k] == tb) {
+        // bin of the row, -1 if it cannot be evicted (exempt or past the end)
+        const int sb = (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) ? score_bin(sv[k]) : -1;
+        if (sb > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
+        else if (sb == tb) {
             const uint32_t c = atomicAdd(&sh.ncand, 1u);
             if (c < CAND_MAX) {
                 sh.cand_slot[c] = (uint32_t)i;
                 sh.cand_key[c] = orderable(sv[k]);
-                sh.cand_pos[c] = pos[i];
+                sh.cand_pos[c] = sp[k];
             }
         }
     }
     __syncthreads();
     const uint32_t ncand = sh.ncand;
 
-    // ---- 3. exact ranking inside the bin by (score bits, position), largest first
+    // ---- 3. exact ranking inside the bin by (score bits, position), largest first: a wave takes a
+    // candidate, its lanes compare it with 64 others at a time and count by ballot
     if (ncand <= CAND_MAX) {
-        for (uint32_t c = tid; c < ncand; c += POST_THREADS) {
+        for (uint32_t c = wave; c < ncand; c += NWAVES) {   // uniform per wave
             const uint32_t key = sh.cand_key[c];
             const int32_t ps = sh.cand_pos[c];
             uint32_t rank = 0;
-            for (uint32_t o = 0; o < ncand; ++o) {
-                const uint32_t ok = sh.cand_key[o];
-                rank += (ok > key) || (ok == key && sh.cand_pos[o] > ps);
+            for (uint32_t o0 = 0; o0 < ncand; o0 += 64) {
+                const uint32_t o = o0 + lane;
+                bool gt = false;
+                if (o < ncand) {
+                    const uint32_t ok = sh.cand_key[o];
+                    gt = (ok > key) || (ok == key && sh.cand_pos[o] > ps);
+                }
+                rank += (uint32_t)__popcll(__ballot(gt));
             }
-            if (rank < need) {
+            if (lane == 0 && rank < need) {
                 const uint32_t i = sh.cand_slot[c];
                 atomicOr(&evbits[i >> 5], 1u << (i & 31));
             }
@@ -405,18 +438,16 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         radix_select_in_bin(p, sh, sc, pos, evbits, tb, need);
     }
 
-    // ---- 4. ordered lists by contiguous ownership: thread t owns rows [t*S, t*S + S)
-    const int S = (p.n + POST_THREADS - 1) / POST_THREADS;
-    const int own0 = min(p.n, tid * S), own1 = min(p.n, own0 + S);
-    uint32_t nev = 0, nh = 0, nm = 0;
-    for (int i = own0; i < own1; ++i) {
-        const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
-        nev += ev;
-        nh += ev && i < p.N;
-        nm += !ev && i >= p.N;
-    }
+    // ---- 4. ordered lists: thread t owns bitmap word t = rows [32 t, 32 t + 32)
+    static_assert(MAX_CAP / 32 <= POST_THREADS, "one bitmap word per thread");
+    const int own0 = min(p.n, 32 * tid), own1 = min(p.n, own0 + 32);
+    const uint32_t valid = own1 - own0 == 32 ? 0xFFFFFFFFu : ((1u << (own1 - own0)) - 1u);
+    const uint32_t low = own0 + 32 <= p.N ? 0xFFFFFFFFu : (own0 >= p.N ? 0u : ((1u << (p.N - own0)) - 1u));  // rows < N
+    const uint32_t evw = tid < nwords ? (evbits[tid] & valid) : 0u;
+    const uint32_t holew = evw & low, movew = ~evw & ~low & valid;
     uint64_t tot3;
-    const uint64_t ex3 = block_exclusive_scan64((uint64_t)nev | ((uint64_t)nh << 21) | ((uint64_t)nm << 42),
+    const uint64_t ex3 = block_exclusive_scan64((uint64_t)__popc(evw) | ((uint64_t)__popc(holew) << 21) |
+                                                    ((uint64_t)__popc(movew) << 42),
                                                 sh.wave_tot64, &tot3);
     constexpr uint64_t M21 = (1ull << 21) - 1;
     uint32_t eb = (uint32_t)(ex3 & M21);
@@ -429,22 +460,27 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         if (tid == 0) atomicOr(p.status, STATUS_SELECT_COUNT);
         return;
     }
-    int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E;
+    // evicted rows | holes (evicted rows below N) | movers (kept rows from N on) | rank of tail row N + r
+    // among the movers (-1: evicted)
+    int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E, *mrank = lists + 3 * E;
     {
         uint32_t hb = hm_h, mb = hm_m, e2 = eb;
-        for (int i = own0; i < own1; ++i) {
-            const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
-            if (ev) evlist[e2++] = i;
-            if (ev && i < p.N) holes[hb++] = i;
-            if (!ev && i >= p.N) movers[mb++] = i;
+        for (uint32_t w = evw; w; w &= w - 1) {
+            const int i = own0 + __ffs(w) - 1;
+            evlist[e2++] = i;
+            if (i < p.N) holes[hb++] = i;
+            else mrank[i - p.N] = -1;
+        }
+        for (uint32_t w = movew; w; w &= w - 1) {
+            const int i = own0 + __ffs(w) - 1;
+            mrank[i - p.N] = (int32_t)mb;
+            movers[mb++] = i;
         }
     }
     __syncthreads();
 
     // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
     // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
-    uint16_t *kb = p.k + (size_t)bh * p.cap * D;
-    uint16_t *vb = p.v + (size_t)bh * p.cap * D;
     {
         constexpr int RPW = 64 / UPR;
         const int u = lane % UPR, rl = lane / UPR;
@@ -486,36 +522,50 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
 #pragma unroll
             for (int i = 0; i < 8; ++i) sh.colsum[wave][u * 8 + i] = acc[i];
         }
-        __syncthreads();
+        __syncthreads();   // also: every evicted row has been read before the compaction overwrites it
         if (tid < D) {
             double s = 0.0;
 #pragma unroll
             for (int w = 0; w < NWAVES; ++w) s += sh.colsum[w][tid];
-            p.ksum[(size_t)bh * D + tid] -= s;
+            p.ksum[(size_t)bh * D + tid] = ksum_old - s;
         }
     }
 
     // ---- 6. compaction
     if (p.layout == 1) {
-        // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N)
-        const int nmove = (int)nholes;
-        for (int w = tid; w < nmove * UPR * 2; w += POST_THREADS) {
-            const int r = w / (UPR * 2), rem = w % (UPR * 2);
-            const int u = rem % UPR;
-            uint16_t *base_ptr = rem < UPR ? kb : vb;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(base_ptr + (size_t)movers[r] * D + u * 8);
-            *reinterpret_cast<u32x4 *>(base_ptr + (size_t)holes[r] * D + u * 8) = val;
+        // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N).  Rows from N
+        // on belong to this step's block: row i holds token pos0 + (i - len).
+        if (tail_regs) {
+#pragma unroll
+            for (int q = 0; q < TAILU; ++q) {
+                const int w = q * POST_THREADS + tid;
+                if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
+                    const int which = w / (E * UPR), rem = w % (E * UPR);
+                    const int mr = mrank[rem / UPR];
+                    if (mr >= 0)
+                        *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)holes[mr] * D + (rem % UPR) * 8) = tailv[q];
+                }
+            }
+        } else {
+            const int nmove = (int)nholes;
+            for (int w = tid; w < nmove * UPR * 2; w += POST_THREADS) {
+                const int r = w / (UPR * 2), rem = w % (UPR * 2);
+                const int u = rem % UPR;
+                uint16_t *base_ptr = rem < UPR ? kb : vb;
+                const u32x4 val = *reinterpret_cast<const u32x4 *>(base_ptr + (size_t)movers[r] * D + u * 8);
+                *reinterpret_cast<u32x4 *>(base_ptr + (size_t)holes[r] * D + u * 8) = val;
+            }
         }
-        for (int r = tid; r < nmove; r += POST_THREADS) pos[holes[r]] = pos[movers[r]];
+        for (int r = tid; r < (int)nholes; r += POST_THREADS) pos[holes[r]] = p.pos0 + (movers[r] - p.len);
     } else {
         // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here
         // (all reads precede all writes), the K/V rows by compact_ordered_kernel.
-        int32_t mypos[(MAX_CAP + POST_THREADS - 1) / POST_THREADS];
+        int32_t mypos[32];
         int32_t *dst = p.dstmap + (size_t)bh * p.cap;
         for (int i = own0, j = 0; i < own1; ++i, ++j) mypos[j] = pos[i];
         __syncthreads();
         for (int i = own0, j = 0; i < own1; ++i, ++j) {
-            const bool ev = (evbits[i >> 5] >> (i & 31)) & 1u;
+            const bool ev = (evw >> j) & 1u;
             if (ev) {
                 dst[i] = -1;
                 ++eb;
@@ -598,7 +648,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void step_score_kernel(StepParams p)
 
 // step_post: workgroups [0, BH) select and compact one head each (when this step evicts); the
 // rest merge the attention partials.
-template <int D>
+template <int D, int SPT>
 __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -611,8 +661,8 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
     const int bh = blockIdx.x;
     uint32_t *evbits = reinterpret_cast<uint32_t *>(smem_raw);
     int32_t *lists = p.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (p.n + 31) / 32)
-                                    : p.lists + (size_t)bh * 3 * p.B;
-    select_and_compact<D>(p, sh, evbits, lists, bh);
+                                    : p.lists + (size_t)bh * 4 * p.B;
+    select_and_compact<D, SPT>(p, sh, evbits, lists, bh);
 }
 
 // ------------------------------------------------------------- ordered compaction
@@ -745,12 +795,12 @@ __global__ void load_pos_kernel(const int32_t *src, int32_t *dst, int cap, int l
 // ---------------------------------------------------------------------- launchers
 constexpr size_t LISTS_LDS_MAX = 48 * 1024;
 
-bool lists_fit_lds(int n, int N) { return n > N && (size_t)(n - N) * 12 <= LISTS_LDS_MAX; }
+bool lists_fit_lds(int n, int N) { return n > N && (size_t)(n - N) * 16 <= LISTS_LDS_MAX; }
 
 size_t post_lds_bytes(int n, int N)
 {
     size_t b = (size_t)((n + 31) / 32) * 4;
-    if (lists_fit_lds(n, N)) b += (size_t)(n - N) * 12;
+    if (lists_fit_lds(n, N)) b += (size_t)(n - N) * 16;
     return b + 16;
 }
 
@@ -766,11 +816,14 @@ hipError_t configure_kernels()
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)compact_lds_bytes(128));
     if (e != hipSuccess) return e;
     const int post_max = (int)(MAX_CAP / 8 + LISTS_LDS_MAX + 16);
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_post_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(step_post_kernel<64>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
+    const void *post_fns[] = {reinterpret_cast<const void *>(step_post_kernel<128, SPT_SMALL>),
+                              reinterpret_cast<const void *>(step_post_kernel<128, SPT_LARGE>),
+                              reinterpret_cast<const void *>(step_post_kernel<64, SPT_SMALL>),
+                              reinterpret_cast<const void *>(step_post_kernel<64, SPT_LARGE>)};
+    for (const void *fn : post_fns) {
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
+        if (e != hipSuccess) return e;
+    }
     return e;
 }
 
@@ -788,8 +841,11 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
     const int grid = (p.do_evict ? p.batch * p.hkv : 0) + p.merge_wgs;
     if (grid == 0) return hipSuccess;
     const size_t lds = post_lds_bytes(p.n, p.N);
-    if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128>), dim3(grid), dim3(POST_THREADS), lds, s, p);
-    else if (p.D == 64) hipLaunchKernelGGL((step_post_kernel<64>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    const bool small = p.n <= SPT_SMALL * POST_THREADS;
+    if (p.D == 128 && small) hipLaunchKernelGGL((step_post_kernel<128, SPT_SMALL>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128, SPT_LARGE>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 64 && small) hipLaunchKernelGGL((step_post_kernel<64, SPT_SMALL>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 64) hipLaunchKernelGGL((step_post_kernel<64, SPT_LARGE>), dim3(grid), dim3(POST_THREADS), lds, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -40,7 +40,7 @@ struct StepParams {
     float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
-    int32_t *lists;                  // [BH][3 * B] evicted rows | holes | movers of this step
+    int32_t *lists;                  // [BH][4 * B] evicted rows | holes | movers | mover rank of each tail row
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup

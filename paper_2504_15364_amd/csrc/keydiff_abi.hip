@@ -78,7 +78,7 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_part_ml = off;    off += align256((size_t)L.max_part_rows * 8);
     L.off_scores = off;     off += align256(BH * L.cap * 4);
     L.off_dstmap = off;     off += align256(BH * L.cap * 4);
-    L.off_lists = off;      off += align256(BH * 3 * (size_t)c->block_B * 4);
+    L.off_lists = off;      off += align256(BH * 4 * (size_t)c->block_B * 4);
     L.off_ksum_part = off;  off += align256(BH * chunks * D * 8);
     L.scratch_bytes = off;
     return L;
