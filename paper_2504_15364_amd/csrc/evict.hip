@@ -21,6 +21,7 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int NWAVES = POST_THREADS / 64;
+constexpr int TAIL_WORDS = 72;                      // bitmap words the tail rows [N, n) may span on the fast path
 constexpr int SPT_SMALL = 12;                       // scores per thread: caches of up to 12288 rows
 constexpr int SPT_LARGE = MAX_CAP / POST_THREADS;   // ... and up to the limit
 constexpr int SCORE_WAVES = SCORE_THREADS / 64;
@@ -86,53 +87,69 @@ struct PostShared {
     uint32_t cand_key[CAND_MAX];
     int32_t cand_pos[CAND_MAX];
     double colsum[NWAVES][128];
+    uint32_t tail_word[TAIL_WORDS], tail_base[TAIL_WORDS];  // mover bitmap words of rows >= N and movers before each
 };
 
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
+// value of the lane `ctrl` names (DPP), 0 where that lane lies outside the row or the row is masked out
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_fetch(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, true);
+}
+
+// inclusive prefix sum over the 64 lanes of a wave, on the vector ALU alone: Hillis-Steele inside
+// each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and 2 into rows 1 and 3
+// (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31)
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
+{
+    x += dpp_fetch<0x111, 0xF>(x);
+    x += dpp_fetch<0x112, 0xF>(x);
+    x += dpp_fetch<0x114, 0xF>(x);
+    x += dpp_fetch<0x118, 0xF>(x);
+    x += dpp_fetch<0x142, 0xA>(x);
+    x += dpp_fetch<0x143, 0xC>(x);
+    return x;
+}
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t x)
+{
+#define KD_STEP64(CTRL, MASK)                                                                   \
+    x += ((uint64_t)dpp_fetch<CTRL, MASK>((uint32_t)(x >> 32)) << 32) | dpp_fetch<CTRL, MASK>((uint32_t)x);
+    KD_STEP64(0x111, 0xF)
+    KD_STEP64(0x112, 0xF)
+    KD_STEP64(0x114, 0xF)
+    KD_STEP64(0x118, 0xF)
+    KD_STEP64(0x142, 0xA)
+    KD_STEP64(0x143, 0xC)
+#undef KD_STEP64
+    return x;
+}
+
+// exclusive prefix sum over the workgroup (32-bit, or three packed 21-bit counters in 64 bits)
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan_t(T v, T *wave_tot, T *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t t = __shfl_up(inc, off);
-        if (lane >= off) inc += t;
-    }
+    const T inc = wave_inclusive_scan(v);
     __syncthreads();  // wave_tot free for reuse
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
-    uint32_t base = 0, tot = 0;
+    T base = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < NWAVES; ++w) {
-        const uint32_t t = wave_tot[w];
+        const T t = wave_tot[w];
         if (w < wave) base += t;
         tot += t;
     }
     *total = tot;
     return base + inc - v;
 }
-
-// exclusive prefix sum of three packed 21-bit counters
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
+{
+    return block_exclusive_scan_t<uint32_t>(v, wave_tot, total);
+}
 __device__ __forceinline__ uint64_t block_exclusive_scan64(uint64_t v, uint64_t *wave_tot, uint64_t *total)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint64_t inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t lo = __shfl_up((uint32_t)inc, off), hi = __shfl_up((uint32_t)(inc >> 32), off);
-        if (lane >= off) inc += ((uint64_t)hi << 32) | lo;
-    }
-    __syncthreads();  // wave_tot free for reuse
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    uint64_t base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < NWAVES; ++w) {
-        const uint64_t t = wave_tot[w];
-        if (w < wave) base += t;
-        tot += t;
-    }
-    *total = tot;
-    return base + inc - v;
+    return block_exclusive_scan_t<uint64_t>(v, wave_tot, total);
 }
 
 // ------------------------------------------------------------------------ scores
@@ -152,6 +169,22 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
     constexpr int UPR = D / 8;
     constexpr int RPW = 64 / UPR;  // rows per wave per pass
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = lane % UPR, rl = lane / UPR;
+    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    // the rows of the first round are requested before the anchor is formed: the two memory
+    // round trips (key sum, rows) then overlap
+    auto load_round = [&](int base, u32x4 (&w)[UPR]) {
+#pragma unroll
+        for (int ps = 0; ps < UPR; ++ps) {
+            const int row = base + ps * RPW + rl;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (row < row1) z = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+            w[ps] = z;
+        }
+    };
+    const int base0 = row0 + wave * 64;
+    u32x4 w[UPR];
+    load_round(base0, w);
     // anchor = ksum / n (Method, "Efficient Variant"); |mu| by a fixed-shape reduction
     double m = 0.0;
     if (tid < D) {
@@ -168,21 +201,12 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
     for (int w = 0; w < SCORE_WAVES; ++w) mu2 += sh.red[w];
     const double nmu = sqrt(mu2);
 
-    const int u = lane % UPR, rl = lane / UPR;
-    const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     double mreg[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) mreg[i] = sh.mu[u * 8 + i];
     // a round = 64 rows per wave; rounds are spread over the waves
-    for (int base = row0 + wave * 64; base < row1; base += SCORE_WAVES * 64) {
-        u32x4 w[UPR];  // the round's loads are issued together
-#pragma unroll
-        for (int ps = 0; ps < UPR; ++ps) {
-            const int row = base + ps * RPW + rl;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (row < row1) z = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
-            w[ps] = z;
-        }
+    for (int base = base0; base < row1; base += SCORE_WAVES * 64) {
+        if (base != base0) load_round(base, w);  // the round's loads are issued together
 #pragma unroll
         for (int ps = 0; ps < UPR; ++ps) {
             double dot = 0.0, k2 = 0.0;
@@ -340,7 +364,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             const int w = q * POST_THREADS + tid;
             tailv[q] = u32x4{0u, 0u, 0u, 0u};
             if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
-                const int which = w / (E * UPR), rem = w % (E * UPR);
+                const int which = w >= E * UPR, rem = w - which * E * UPR;
                 tailv[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)(p.N + rem / UPR) * D + (rem % UPR) * 8);
             }
         }
@@ -463,6 +487,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     // evicted rows | holes (evicted rows below N) | movers (kept rows from N on) | rank of tail row N + r
     // among the movers (-1: evicted)
     int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E, *mrank = lists + 3 * E;
+    const bool tail_par = E <= POST_THREADS && (nwords - (p.N >> 5)) <= TAIL_WORDS;
     {
         uint32_t hb = hm_h, mb = hm_m, e2 = eb;
         for (uint32_t w = evw; w; w &= w - 1) {
@@ -471,13 +496,33 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             if (i < p.N) holes[hb++] = i;
             else mrank[i - p.N] = -1;
         }
-        for (uint32_t w = movew; w; w &= w - 1) {
-            const int i = own0 + __ffs(w) - 1;
-            mrank[i - p.N] = (int32_t)mb;
-            movers[mb++] = i;
+        // The tail rows [N, n) sit in a few words that are mostly movers: those words and their
+        // mover counts before them go to LDS, and one thread per tail row finishes below.
+        const int tw = tid - (p.N >> 5);
+        if (tail_par) {
+            if (tw >= 0 && tid < nwords) {
+                sh.tail_word[tw] = movew;
+                sh.tail_base[tw] = mb;
+            }
+        } else {
+            for (uint32_t w = movew; w; w &= w - 1) {
+                const int i = own0 + __ffs(w) - 1;
+                mrank[i - p.N] = (int32_t)mb;
+                movers[mb++] = i;
+            }
         }
     }
     __syncthreads();
+    if (tail_par && tid < E) {
+        const int row = p.N + tid, tw = (row >> 5) - (p.N >> 5), bit = row & 31;
+        const uint32_t mw = sh.tail_word[tw];
+        if ((mw >> bit) & 1u) {
+            const uint32_t r = sh.tail_base[tw] + (uint32_t)__popc(mw & ((1u << bit) - 1u));
+            mrank[tid] = (int32_t)r;
+            movers[r] = row;
+        }   // an evicted tail row got its -1 above
+    }
+    // (the ranks are first read after the barrier inside step 5)
 
     // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
     // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
@@ -540,7 +585,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             for (int q = 0; q < TAILU; ++q) {
                 const int w = q * POST_THREADS + tid;
                 if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
-                    const int which = w / (E * UPR), rem = w % (E * UPR);
+                    const int which = w >= E * UPR, rem = w - which * E * UPR;
                     const int mr = mrank[rem / UPR];
                     if (mr >= 0)
                         *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)holes[mr] * D + (rem % UPR) * 8) = tailv[q];
