@@ -85,6 +85,49 @@ def test_two_query_sets_per_wave_and_split_merge():
     run_prompt(w, data, 768, 128, layout=kd.LAYOUT_FILL)
 
 
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+@pytest.mark.parametrize("shape", ["toy", "ragged"])
+def test_unit_key_anchor(layout, shape):
+    # Eq. 7 literally: the anchor is the mean of the unit keys (anchor_mode = 1); the running sum of
+    # unit keys goes through the same append / evict updates as the raw-key sum
+    if shape == "toy":
+        w = get_config("toy")
+        N, B = w.budget_N, w.block_B
+    else:
+        w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=500)
+        N, B = 200, 48
+    data = make_layer(w, seed=31)
+    run_prompt(w, data, N, B, layout=layout, anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY)
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+@pytest.mark.parametrize("frac", [0.1, 0.2])
+def test_sliding_window_is_exempt_from_eviction(layout, frac):
+    # Method, "KeyDiff with Sliding Window": the W most recent tokens always stay, KeyDiff picks
+    # the rest of the budget (the paper uses 10 % and 20 % of the budget)
+    w = get_config("toy")
+    N, B = w.budget_N, w.block_B
+    W = int(frac * N)
+    data = make_layer(w, seed=32)
+    cache, oc = make_pair(w, N, B, layout=layout, window_W=W)
+    for t, Bt, q, k, v in blocks(data, B):
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.prefill_block(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
+        check_state(cache, oc, f"window {W}, block at token {t}")
+        if ev > 0:
+            kept = np.sort(cache.positions().cpu().numpy(), axis=-1)
+            assert np.all(kept[..., -W:] == np.arange(t + Bt - W, t + Bt)), "a window token was evicted"
+    assert cache.status() == 0
+    cache.close()
+
+
+def test_window_with_unit_key_anchor_large_group():
+    w = get_config("llama32_3b").small(n_q_heads=14, n_kv_heads=2, head_dim=128, prompt_T=448)
+    data = make_layer(w, seed=33)
+    run_prompt(w, data, 320, 64, layout=kd.LAYOUT_FILL, anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY, window_W=64)
+
+
 def test_budget_not_reached_only_appends():
     w = get_config("toy").small(prompt_T=96)
     data = make_layer(w, seed=2)
