@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "kd_kernels.h"
+#include "kd_device.h"
 
 namespace kd {
 
@@ -111,6 +112,12 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [STAGES][K tile | V tile]
     __shared__ double red[NW];
+    __shared__ double bs_part[NW][D];   // per-wave column sums of the block's keys
+    __shared__ double mu_s[D];          // the anchor: (key sum incl. this block) / n
+    // (mu.k, |k|^2, row) of scored rows, staged per wave until 64 are there: the square root and the
+    // division that finish a score are long instruction sequences, run once per 64 rows this way
+    __shared__ double st_dot[NW][64], st_k2[NW][64];
+    __shared__ int st_row[NW][64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -205,6 +212,51 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         }
     }
 
+    // ---- anchor (Method, "Efficient Variant"): key sum after this step = key sum before it + the
+    // block's keys.  Every workgroup that scores forms it by itself (the block is 32 KB in L2); one
+    // workgroup per head also stores it for step_post and the next step.  The loads go out with
+    // the queries and are consumed before any further tile copy is issued: the compiler counts
+    // only its own loads when it waits for them.
+    const bool writer = sp == 0 && mt == 0;
+    const bool need_sum = p.do_score != 0 || writer;
+    constexpr int BROWS = NT / UPR;    // block rows per pass: UPR consecutive lanes share a row
+    constexpr int BPASS = 4;           // passes loaded together
+    const int bu = tid % UPR, brl = tid / UPR;
+    double bacc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bacc[i] = 0.0;
+    const double ksum_before = (need_sum && tid < D) ? p.ksum[(size_t)bh * D + tid] : 0.0;
+    auto block_rows = [&](int j0) {   // rows j0 + pass * BROWS + brl of the block, BPASS passes
+        u32x4 kw[BPASS];
+#pragma unroll
+        for (int ps = 0; ps < BPASS; ++ps) {
+            const int j = j0 + ps * BROWS + brl;
+            kw[ps] = u32x4{0u, 0u, 0u, 0u};
+            if (j < p.Bt) kw[ps] = *reinterpret_cast<const u32x4 *>(knew + (size_t)j * D + bu * 8);
+        }
+#pragma unroll
+        for (int ps = 0; ps < BPASS; ++ps) {
+            double x[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = bf16_lo(kw[ps][i]);
+                x[2 * i + 1] = bf16_hi(kw[ps][i]);
+            }
+            double inv = 1.0;
+            if (p.anchor_mode == 1) {  // unit keys (Eq. 7): x / |k_j|, a zero key adds nothing
+                double k2 = 0.0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
+                k2 = row_allreduce_f64<UPR>(k2);
+                const double nk = sqrt(k2);
+                inv = nk > 0.0 ? 1.0 / nk : 0.0;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bacc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
+        }
+    };
+    if (need_sum) block_rows(0);   // the first BPASS * BROWS rows: their loads fly with the queries
+
     // Pin the query registers: the compiler must see their global loads complete before the tile
     // copies are issued, or it would wait for "all memory operations" at their first use in every
     // iteration -- and thereby for tile copies in flight, which it does not know about.
@@ -216,6 +268,37 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             asm volatile("" : "+v"(qv));
             qreg[a][c] = as_bf16x8(qv);
         }
+
+    double ksum_after = 0.0;   // element tid of the new key sum (tid < D), stored at the end by the writer
+    if (need_sum) {
+        for (int j0 = BPASS * BROWS; j0 < p.Bt; j0 += BPASS * BROWS) block_rows(j0);   // uniform
+        // fold the lanes that hold the same unit (bu), then the waves
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+#pragma unroll
+            for (int off = UPR; off < 64; off <<= 1) bacc[i] += shfl_xor_f64(bacc[i], off);
+        }
+        if (lane < UPR) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bs_part[wave][bu * 8 + i] = bacc[i];
+        }
+        __syncthreads();
+        double sq = 0.0;
+        if (tid < D) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tot += bs_part[w][tid];
+            ksum_after = ksum_before + tot;
+            const double m = ksum_after / (double)p.n;
+            mu_s[tid] = m;
+            sq = m * m;
+        }
+        // |mu|^2: waves 0 .. D/64 - 1 hold the terms
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) sq += shfl_xor_f64(sq, off);
+        if (lane == 0) red[wave] = sq;
+        // (published by the barrier of the prologue below)
+    }
 
     // the rest of the ring flies while the prologue computes on tile t0
 #pragma unroll
@@ -361,6 +444,87 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         }
     };
 
+    // ---- cosine score of the rows of one K tile (appendix "FLOP count of KeyDiff"), read from LDS
+    // while the tile is there for the attention: s_i = mu.k_i / max(|mu| |k_i|, eps) in double on
+    // the bf16 values, rounded once to float.  The query-row tiles of a head share the K tiles, so
+    // tile t is scored by the workgroup with mt == t % mtiles.  UPR lanes share a row.
+    int staged = 0;   // rows this wave has staged (wave uniform)
+    auto flush_scores = [&]() {
+        // same wave wrote and reads: the LDS accesses of one wave complete in order; the fences only
+        // keep the compiler from moving the reads above the writes, and later writes above the reads
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane < staged) {
+            const int row = st_row[wave][lane];
+            if (row < p.n) {
+                double nmu2 = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) nmu2 += red[w];
+                const float sc = finish_score(st_dot[wave][lane], st_k2[wave][lane], sqrt(nmu2), p.eps);
+                p.scores[(size_t)bh * p.cap + row] = sc;
+                if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = sc;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        staged = 0;
+    };
+    auto score_tile = [&](int t) {
+        constexpr int RPP = 64 / UPR;            // rows per pass
+        constexpr int PASSES = TILE_KEYS / NW / RPP;
+        static_assert(PASSES >= 1, "a wave scores at least one pass of rows per tile");
+        const unsigned char *tK = smem + (size_t)(t % STAGES) * 2 * TILE_B;
+        const int u = lane % UPR, rl = lane / UPR;
+        double mu8[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mu8[i] = mu_s[u * 8 + i];
+        double dotp[PASSES], k2p[PASSES];
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = wave * (TILE_KEYS / NW) + ps * RPP + rl;   // row inside the tile
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(tK + r * ROWB + ((u ^ (r & (UPR - 1))) * 16));
+            // products of two bf16 values are exact in double, so fma(a, a, .) is the plain sum of
+            // squares; mu.k takes one rounding per term either way
+            double dot = 0.0, k2 = 0.0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const double a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+                dot = __builtin_fma(mu8[2 * i], a, dot);
+                k2 = __builtin_fma(a, a, k2);
+                dot = __builtin_fma(mu8[2 * i + 1], b, dot);
+                k2 = __builtin_fma(b, b, k2);
+            }
+            dotp[ps] = dot;
+            k2p[ps] = k2;
+        }
+        if constexpr (UPR == 16 && PASSES == 2) {
+            // lanes 0-3 of a row end with mu.k of pass 0, 4-7 with |k|^2 of pass 0, 8-11 and 12-15
+            // with those of pass 1
+            const double v = row_reduce_scatter4_f64(dotp[0], k2p[0], dotp[1], k2p[1], u);
+            if ((u & 3) == 0) {
+                const int ps = u >> 3;
+                const int slot = staged + ps * RPP + rl;
+                if (u & 4) st_k2[wave][slot] = v;
+                else {
+                    st_dot[wave][slot] = v;
+                    st_row[wave][slot] = t * TILE_KEYS + wave * (TILE_KEYS / NW) + ps * RPP + rl;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const double dot = row_allreduce_f64<UPR>(dotp[ps]), k2 = row_allreduce_f64<UPR>(k2p[ps]);
+                if (u == 0) {
+                    const int slot = staged + ps * RPP + rl;
+                    st_dot[wave][slot] = dot;
+                    st_k2[wave][slot] = k2;
+                    st_row[wave][slot] = t * TILE_KEYS + wave * (TILE_KEYS / NW) + ps * RPP + rl;
+                }
+            }
+        }
+        staged += PASSES * RPP;
+        if (staged + PASSES * RPP > 64) flush_scores();
+    };
+    const bool scoring = p.do_score != 0;
+
     const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
     f32x16 s[NQ][2];
     if (ntl > 0) {
@@ -495,6 +659,8 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        // tile t is still in its buffer (recycled in the next iteration): score its rows
+        if (scoring && t % p.mtiles == mt) score_tile(t);
         float mloc[NQ];
 #pragma unroll
         for (int a = 0; a < NQ; ++a) mloc[a] = NEXT ? max3_raw(mch[a][0], mch[a][1], mch[a][0]) : 0.f;
@@ -513,72 +679,38 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         for (; t + 1 < tint; ++t) step(t, T_{}, F_{}, std::integral_constant<int, 0>{});
     for (; t + 1 < t1; ++t) step(t, T_{}, T_{}, std::integral_constant<int, 2>{});
 
-    // ---- append (Eq. 5): this workgroup's slice of the block's rows, and their sum for the anchor.
-    // The attention reads the block straight from k_new / v_new, so nothing waits for the append:
+    // ---- append (Eq. 5): this workgroup's slice of the block's rows.  The attention reads the
+    // block straight from k_new / v_new, so nothing waits for the append: when the slice is small
     // its loads are issued here, fly during the last tile, and are stored after it.
     const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
     const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
     const int arows = j1 - j0;
-    constexpr int KPRE = 4;                                  // rows of the slice summed from registers
-    const bool small = arows * UPR * 2 <= NT && arows <= KPRE && p.anchor_mode == 0;
+    const bool small = arows * UPR * 2 <= NT;
     u32x4 aval = {0u, 0u, 0u, 0u};
-    uint32_t kx[KPRE] = {0u, 0u, 0u, 0u};
-    if (small) {
-        if (tid < arows * UPR * 2) {
-            const int which = tid / (arows * UPR), rem = tid % (arows * UPR);
-            aval = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)(j0 + rem / UPR) * D + (rem % UPR) * 8);
-        }
-        if (tid < D)
-#pragma unroll
-            for (int r = 0; r < KPRE; ++r)
-                if (r < arows) kx[r] = knew[(size_t)(j0 + r) * D + tid];
+    if (small && tid < arows * UPR * 2) {
+        const int which = tid >= arows * UPR, rem = tid - which * arows * UPR;
+        aval = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)(j0 + rem / UPR) * D + (rem % UPR) * 8);
     }
 
     if (ntl > 0) step(t, F_{}, F_{}, std::integral_constant<int, 0>{});
+    if (scoring) flush_scores();
 
     if (small) {
         if (tid < arows * UPR * 2) {
-            const int which = tid / (arows * UPR), rem = tid % (arows * UPR);
+            const int which = tid >= arows * UPR, rem = tid - which * arows * UPR;
             *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j0 + rem / UPR) * D + (rem % UPR) * 8) = aval;
-        }
-        if (tid < D && arows > 0) {
-            double acc = 0.0;
-#pragma unroll
-            for (int r = 0; r < KPRE; ++r) acc += (double)__uint_as_float(kx[r] << 16);   // absent rows hold +0
-            unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
         }
     } else {
         for (int u = tid; u < arows * UPR * 2; u += NT) {
-            const int which = u / (arows * UPR), rem = u % (arows * UPR);
+            const int which = u >= arows * UPR, rem = u - which * arows * UPR;
             const int j = j0 + rem / UPR, unit = rem % UPR;
             const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
             *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
         }
-        double acc = 0.0;
-        for (int j = j0; j < j1; ++j) {
-            double x = 0.0;
-            if (tid < D) x = (double)__uint_as_float((uint32_t)knew[(size_t)j * D + tid] << 16);
-            if (p.anchor_mode == 1) {  // unit keys (Eq. 7): x / |k_j|, a zero key adds nothing
-                double k2 = x * x;
-#pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    int lo = __shfl_xor(__double2loint(k2), off), hi = __shfl_xor(__double2hiint(k2), off);
-                    k2 += __hiloint2double(hi, lo);
-                }
-                __syncthreads();
-                if (lane == 0) red[wave] = k2;
-                __syncthreads();
-                double tot = 0.0;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) tot += red[w];
-                const double nk = sqrt(tot);
-                x = nk > 0.0 ? x * (1.0 / nk) : 0.0;
-            }
-            acc += x;
-        }
-        if (tid < D && arows > 0) unsafeAtomicAdd(p.ksum + (size_t)bh * D + tid, acc);
     }
     for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
+    // the key sum after this step, for step_post and for the next step
+    if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
 
     // ---- output.  Accumulator element e of d-block db is d = 32 db + 8 (e / 4) + 4 h + e % 4 of
     // query l32: 8-byte pieces of 32 different rows, which as direct stores would cost one memory

@@ -12,6 +12,7 @@
 // rows inside it exactly by (score bits, position): equal scores keep the lower
 // position.  It then compacts the cache and takes the evicted keys out of ksum.
 #include "kd_kernels.h"
+#include "kd_device.h"
 
 namespace kd {
 
@@ -25,40 +26,6 @@ constexpr int TAIL_WORDS = 72;                      // bitmap words the tail row
 constexpr int SPT_SMALL = 12;                       // scores per thread: caches of up to 12288 rows
 constexpr int SPT_LARGE = MAX_CAP / POST_THREADS;   // ... and up to the limit
 constexpr int SCORE_WAVES = SCORE_THREADS / 64;
-
-__device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
-__device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
-
-__device__ __forceinline__ double shfl_xor_f64(double x, int m)
-{
-    int lo = __double2loint(x), hi = __double2hiint(x);
-    lo = __shfl_xor(lo, m);
-    hi = __shfl_xor(hi, m);
-    return __hiloint2double(hi, lo);
-}
-
-// x + (x of another lane of the same 16-lane row), by a DPP control word
-template <int CTRL>
-__device__ __forceinline__ double dpp_add_f64(double x)
-{
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
-    return x + __hiloint2double(hi, lo);
-}
-
-// sum over the LANES (8 or 16) consecutive lanes that share one key row; every lane gets the
-// total.  Quad exchanges, then mirrors inside the half row and the row: each step pairs a lane
-// with one that holds the sum of a different, equally sized group.
-template <int LANES>
-__device__ __forceinline__ double row_allreduce_f64(double x)
-{
-    static_assert(LANES == 8 || LANES == 16, "a key row spans 8 or 16 lanes");
-    x = dpp_add_f64<0xB1>(x);                    // quad_perm [1,0,3,2]
-    x = dpp_add_f64<0x4E>(x);                    // quad_perm [2,3,0,1]
-    x = dpp_add_f64<0x141>(x);                   // row_half_mirror: lane i <-> 7 - i
-    if (LANES == 16) x = dpp_add_f64<0x140>(x);  // row_mirror: lane i <-> 15 - i
-    return x;
-}
 
 // float -> unsigned key with the same order
 __device__ __forceinline__ uint32_t orderable(float s)
@@ -231,9 +198,7 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
         const int row = base + lane;
         if (row < row1) {
             const double dot = sh.dot[wave][lane], k2 = sh.k2[wave][lane];
-            double den = nmu * sqrt(k2);
-            if (den < p.eps) den = p.eps;
-            const float s = (float)(dot / den) + 0.0f;  // +0 folds -0 into +0
+            const float s = finish_score(dot, k2, nmu, p.eps);
             p.scores[(size_t)bh * p.cap + row] = s;
             if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = s;
         }
@@ -355,7 +320,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             sp[k] = pos[i];
         }
     }
-    const double ksum_old = tid < D ? p.ksum[(size_t)bh * D + tid] : 0.0;
+    const double ksum_old = tid < D ? p.ksum_next[(size_t)bh * D + tid] : 0.0;  // the sum step_main just wrote
     const bool tail_regs = TAILU > 0 && p.layout == 1 && 2 * E * UPR <= TAILU * POST_THREADS;
     u32x4 tailv[TAILU > 0 ? TAILU : 1];
     if (tail_regs) {
@@ -572,7 +537,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             double s = 0.0;
 #pragma unroll
             for (int w = 0; w < NWAVES; ++w) s += sh.colsum[w][tid];
-            p.ksum[(size_t)bh * D + tid] = ksum_old - s;
+            p.ksum_next[(size_t)bh * D + tid] = ksum_old - s;
         }
     }
 
@@ -904,7 +869,7 @@ hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s)
 hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s)
 {
     const int BH = p.batch * p.hkv;
-    if (p.n == 0) return launch_zero_words(reinterpret_cast<int32_t *>(p.ksum), (size_t)BH * p.D * 2, s);
+    if (p.n == 0) return launch_zero_words(reinterpret_cast<int32_t *>(const_cast<double *>(p.ksum)), (size_t)BH * p.D * 2, s);
     const int nchunks = (p.n + CHUNK_ROWS - 1) / CHUNK_ROWS;
     dim3 grid(nchunks, BH);
     if (p.D == 128) hipLaunchKernelGGL((ksum_partial_kernel<128>), grid, dim3(256), 0, s, p, partials, nchunks);
@@ -912,7 +877,7 @@ hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_
     else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ksum_final_kernel, dim3(BH), dim3(128), 0, s, partials, p.ksum, nchunks, p.D);
+    hipLaunchKernelGGL(ksum_final_kernel, dim3(BH), dim3(128), 0, s, partials, const_cast<double *>(p.ksum), nchunks, p.D);
     return hipGetLastError();
 }
 

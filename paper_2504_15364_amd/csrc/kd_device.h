@@ -1,0 +1,81 @@
+// Device helpers shared by the kernels: bf16 -> double, and double-precision lane exchanges.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kd {
+
+__device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
+__device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ double shfl_xor_f64(double x, int m)
+{
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __shfl_xor(lo, m);
+    hi = __shfl_xor(hi, m);
+    return __hiloint2double(hi, lo);
+}
+
+// x + (x of another lane of the same 16-lane row), by a DPP control word
+template <int CTRL>
+__device__ __forceinline__ double dpp_add_f64(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+    return x + __hiloint2double(hi, lo);
+}
+
+// sum over the LANES (8 or 16) consecutive lanes that share one key row; every lane gets the
+// total.  Quad exchanges, then mirrors inside the half row and the row: each step pairs a lane
+// with one that holds the sum of a different, equally sized group.
+template <int LANES>
+__device__ __forceinline__ double row_allreduce_f64(double x)
+{
+    static_assert(LANES == 8 || LANES == 16, "a key row spans 8 or 16 lanes");
+    x = dpp_add_f64<0xB1>(x);                    // quad_perm [1,0,3,2]
+    x = dpp_add_f64<0x4E>(x);                    // quad_perm [2,3,0,1]
+    x = dpp_add_f64<0x141>(x);                   // row_half_mirror: lane i <-> 7 - i
+    if (LANES == 16) x = dpp_add_f64<0x140>(x);  // row_mirror: lane i <-> 15 - i
+    return x;
+}
+
+
+// the double another lane holds, fetched by a DPP control word (rows of 16 lanes)
+template <int CTRL>
+__device__ __forceinline__ double dpp_fetch_f64(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Four quantities, each spread over the 16 lanes of a row, summed with 5 additions per lane instead
+// of 16: the lanes first split the quantities between them (lane bit 3, then bit 2, decides which
+// a lane keeps; it hands the others to a partner on the other side of that bit and adds what the
+// partner hands over), then the four lanes left with the same quantity finish among themselves.
+// On return lanes 4k .. 4k + 3 of every row hold the full sum of quantity k.
+__device__ __forceinline__ double row_reduce_scatter4_f64(double q0, double q1, double q2, double q3, int u)
+{
+    const bool b3 = (u & 8) != 0, b2 = (u & 4) != 0;
+    double k0 = b3 ? q2 : q0, k1 = b3 ? q3 : q1;          // kept
+    const double s0 = b3 ? q0 : q2, s1 = b3 ? q1 : q3;    // handed to lane u ^ 8
+    k0 += dpp_fetch_f64<0x128>(s0);                       // row_ror:8
+    k1 += dpp_fetch_f64<0x128>(s1);
+    double k = b2 ? k1 : k0;
+    const double s = b2 ? k0 : k1;                        // handed to lane 7 - u of the half row
+    k += dpp_fetch_f64<0x141>(s);                         // row_half_mirror
+    k += dpp_fetch_f64<0xB1>(k);                          // quad_perm [1,0,3,2]
+    k += dpp_fetch_f64<0x4E>(k);                          // quad_perm [2,3,0,1]
+    return k;
+}
+
+// The canonical score of one key (appendix "FLOP count of KeyDiff"): mu.k / max(|mu| |k|, eps) in
+// IEEE double, rounded once to float; + 0 folds -0 into +0.  Every kernel that scores calls this.
+__device__ __forceinline__ float finish_score(double dot, double k2, double nmu, double eps)
+{
+    double den = nmu * sqrt(k2);
+    if (den < eps) den = eps;
+    return (float)(dot / den) + 0.0f;
+}
+
+}  // namespace kd

@@ -2,11 +2,12 @@
 //
 // One block step is three launches:
 //   step_main  append (Eq. 5) + split-KV flash attention partials (Eq. 1-2)
-//              + running key sum S += sum of the block's keys (the anchor is S / n)
-//   step_score cosine score of every row + per-head score histogram
+//              + running key sum S' = S + sum of the block's keys (the anchor is S' / n)
+//              + cosine score of every row, taken from the K tiles while they sit in LDS
 //   step_post  merge of the attention partials  ||  selection of the rows to evict
 //              and compaction, one workgroup per head (Eq. 6-7)
 // plus, for the ORDERED layout only, one more launch that shifts rows in place.
+// step_score scores a cache outside a block step (keydiff_scores).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -33,7 +34,9 @@ struct StepParams {
     // caller-owned state
     uint16_t *k, *v;                 // caches [BH][cap][D]
     int32_t *pos;                    // [BH][cap] token position of every row
-    double *ksum;                    // [BH][D] running sum of the (raw or unit) keys in the cache
+    const double *ksum;              // [BH][D] running sum of the (raw or unit) keys in the cache before this step
+    double *ksum_next;               // [BH][D] ... after it (the other half of a double buffer): written by
+                                     // step_main (+ the block's keys), then by step_post (- the evicted keys)
     int32_t *status;
     // scratch
     _Float16 *part_o;                // [splits][BH * G * Bt][D] partial outputs, each normalised by its row sum

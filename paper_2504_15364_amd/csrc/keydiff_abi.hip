@@ -64,7 +64,7 @@ Layout make_layout(const keydiff_config_t *c)
     L.k_bytes = align256(BH * L.cap * D * 2);
     size_t off = 0;
     L.off_pos = off;     off += align256(BH * L.cap * 4);
-    L.off_ksum = off;    off += align256(BH * D * 8);
+    L.off_ksum = off;    off += align256(2 * BH * D * 8);  // double buffer: see StepParams::ksum_next
     L.off_status = off;  off += 256;
     L.meta_bytes = off;
     // split-KV partial rows: splits * BH * G * Bt never exceeds this (see plan_attention)
@@ -101,6 +101,7 @@ struct keydiff_cache {
     float scale_log2e;
     bool contiguous;      // every block so far started where the previous one ended
     int64_t next_pos;
+    int kpar;             // which half of the key-sum double buffer holds the current sum
     bool profiling;
     std::vector<ProfEvent> events;
     std::vector<hipEvent_t> pool;
@@ -155,7 +156,12 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.k = c->k;
     p.v = c->v;
     p.pos = reinterpret_cast<int32_t *>(c->meta + c->L.off_pos);
-    p.ksum = reinterpret_cast<double *>(c->meta + c->L.off_ksum);
+    {
+        double *both = reinterpret_cast<double *>(c->meta + c->L.off_ksum);
+        const size_t half = (size_t)cf.batch * cf.n_kv_heads * cf.head_dim;
+        p.ksum = both + (size_t)c->kpar * half;
+        p.ksum_next = both + (size_t)(c->kpar ^ 1) * half;
+    }
     p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
     p.part_o = reinterpret_cast<_Float16 *>(c->scratch + c->L.off_part_o);
     p.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
@@ -248,6 +254,7 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->contiguous = true;
     c->next_pos = -1;
     c->profiling = false;
+    c->kpar = 0;
     static hipError_t configured = kd::configure_kernels();  // once per process
     hipError_t e = configured;
     if (e == hipSuccess)
@@ -315,10 +322,6 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
         ProfScope ps(c, KEYDIFF_K_MAIN, s);
         KD_LAUNCH(kd::launch_step_main(p, s), "step_main kernel");
     }
-    if (p.do_score) {
-        ProfScope ps(c, KEYDIFF_K_SCORE, s);
-        KD_LAUNCH(kd::launch_step_score(p, s), "step_score kernel");
-    }
     if (evict || p.merge_wgs > 0) {
         ProfScope ps(c, KEYDIFF_K_POST, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
@@ -328,6 +331,7 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
         KD_LAUNCH(kd::launch_compact_ordered(p, s), "ordered compaction kernel");
     }
     if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
+    c->kpar ^= 1;   // step_main wrote the new key sum into the other half
     c->len = evict ? N : n;
     c->contiguous = contiguous;
     c->next_pos = pos0 + Bt;
