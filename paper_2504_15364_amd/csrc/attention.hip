@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     static_assert(2 * LPW < 64, "two tiles of copies in flight must fit the 6-bit counter");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [STAGES][K tile | V tile]
-    __shared__ double red[NW];
+    __shared__ double red[NW][4];       // |mu|^2 in pieces: one per 16-lane row of every wave
     __shared__ double bs_part[NW][D];   // per-wave column sums of the block's keys
     __shared__ double mu_s[D];          // the anchor: (key sum incl. this block) / n
     // (mu.k, |k|^2, row) of scored rows, staged per wave until 64 are there: the square root and the
@@ -189,10 +189,15 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         const uint16_t *src = (isv ? vcache : kcache) + ((size_t)t * TILE_KEYS + (size_t)i * CSTEP) * D;
         async_copy16(dst, src, isv ? voff0 : koff0);
     };
-    // tile t0 first, then the queries: one memory round trip covers both
+    // tile t0 first, then the queries, then tile t0 + 1: one memory round trip covers all three
     if (ntl > 0) issue_tile(t0);
 
-    // ---- query rows of this lane (one per block): B operands of S^T = K Q^T, kept in registers
+    // ---- query rows of this lane (one per block): B operands of S^T = K Q^T, kept in registers.
+    // Row m of a head is query (m / Bt, m % Bt) and the rows are contiguous in memory, so a wave's
+    // 32 NQ rows are one block of memory: it is copied asynchronously, whole rows at a time, into
+    // the wave's piece of the two ring buffers that tiles t0 + 2 and t0 + 3 will use later (with
+    // the K swizzle), and read from there into registers.  Loading the B-operand layout directly
+    // would touch 32 rows per instruction.
     int mrow[NQ], qg[NQ], qj[NQ], vis[NQ];
     bool valid[NQ];
     bf16x8 qreg[NQ][NC];
@@ -203,14 +208,22 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         qg[a] = valid[a] ? mrow[a] / p.Bt : 0;
         qj[a] = valid[a] ? mrow[a] % p.Bt : 0;
         vis[a] = p.len + qj[a] + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
-        const uint16_t *qp = p.q + ((size_t)(b * p.hq + kvh * p.G + qg[a]) * p.Bt + qj[a]) * D;
+    }
+    constexpr int QROWS = 32 * NQ, QBYTES = QROWS * ROWB;
+    static_assert(NW * QBYTES <= 2 * 2 * TILE_B && (2 * TILE_B) % QBYTES == 0, "query staging uses two ring buffers");
+    const int qoff = wave * QBYTES, qhalf = qoff / (2 * TILE_B);
+    unsigned char *qwave = smem + (size_t)((t0 + 2 + qhalf) % STAGES) * 2 * TILE_B + (qoff - qhalf * 2 * TILE_B);
+    {
+        const char *qhead = reinterpret_cast<const char *>(p.q + (size_t)(b * p.hq + kvh * p.G) * p.Bt * D);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (valid[a]) z = *reinterpret_cast<const u32x4 *>(qp + 16 * c + 8 * h);
-            qreg[a][c] = as_bf16x8(z);
+        for (int i = 0; i < QBYTES / 1024; ++i) {
+            const int r = RPL * i + lane / UPR;                       // row inside the wave's block
+            const int m = min(mt * TM + wave * QROWS + r, Mtot - 1);  // rows past the end repeat the last one
+            async_copy16((uint32_t)(uintptr_t)qwave + 1024u * i,
+                         qhead + (size_t)m * ROWB + (((lane % UPR) ^ (r & (UPR - 1))) * 16));
         }
     }
+    if (ntl > 1) issue_tile(t0 + 1);
 
     // ---- anchor (Method, "Efficient Variant"): key sum after this step = key sum before it + the
     // block's keys.  Every workgroup that scores forms it by itself (the block is 32 KB in L2); one
@@ -257,17 +270,15 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     };
     if (need_sum) block_rows(0);   // the first BPASS * BROWS rows: their loads fly with the queries
 
-    // Pin the query registers: the compiler must see their global loads complete before the tile
-    // copies are issued, or it would wait for "all memory operations" at their first use in every
-    // iteration -- and thereby for tile copies in flight, which it does not know about.
+    // everything issued so far has landed: the queries go from LDS to registers (a wave reads only
+    // what its own copies wrote)
+    wait_copies<0>();
 #pragma unroll
     for (int a = 0; a < NQ; ++a)
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            u32x4 qv = __builtin_bit_cast(u32x4, qreg[a][c]);
-            asm volatile("" : "+v"(qv));
-            qreg[a][c] = as_bf16x8(qv);
-        }
+        for (int c = 0; c < NC; ++c)
+            qreg[a][c] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                qwave + (32 * a + l32) * ROWB + (((2 * c + h) ^ (l32 & (UPR - 1))) * 16)));
 
     double ksum_after = 0.0;   // element tid of the new key sum (tid < D), stored at the end by the writer
     if (need_sum) {
@@ -282,28 +293,8 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 #pragma unroll
             for (int i = 0; i < 8; ++i) bs_part[wave][bu * 8 + i] = bacc[i];
         }
-        __syncthreads();
-        double sq = 0.0;
-        if (tid < D) {
-            double tot = 0.0;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) tot += bs_part[w][tid];
-            ksum_after = ksum_before + tot;
-            const double m = ksum_after / (double)p.n;
-            mu_s[tid] = m;
-            sq = m * m;
-        }
-        // |mu|^2: waves 0 .. D/64 - 1 hold the terms
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) sq += shfl_xor_f64(sq, off);
-        if (lane == 0) red[wave] = sq;
-        // (published by the barrier of the prologue below)
+        // (the per-wave sums are published by the barrier of the prologue below and added up after it)
     }
-
-    // the rest of the ring flies while the prologue computes on tile t0
-#pragma unroll
-    for (int i = 1; i < STAGES - 1; ++i)
-        if (i < ntl) issue_tile(t0 + i);
 
     f32x16 oacc[NQ][NDB];
     float mref[NQ], lrun[NQ][2];  // the row sum runs in two independent chains
@@ -458,7 +449,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             if (row < p.n) {
                 double nmu2 = 0.0;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) nmu2 += red[w];
+                for (int w = 0; w < NW; ++w) nmu2 += (red[w][0] + red[w][1]) + (red[w][2] + red[w][3]);
                 const float sc = finish_score(st_dot[wave][lane], st_k2[wave][lane], sqrt(nmu2), p.eps);
                 p.scores[(size_t)bh * p.cap + row] = sc;
                 if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = sc;
@@ -528,8 +519,26 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
     f32x16 s[NQ][2];
     if (ntl > 0) {
-        // ---- prologue: this wave's copies of tile t0 landed before the queries did (the pin above)
+        // ---- prologue: every wave has its queries in registers and its part of tiles t0, t0 + 1 in
+        // LDS; the staging buffers are free for tile t0 + 2, which flies while S^T of tile t0 is formed
         __syncthreads();
+        static_assert(STAGES == 4, "the prologue fills three of the four ring buffers");
+        if (ntl > 2) issue_tile(t0 + 2);
+        if (need_sum) {
+            // the anchor: waves 0 .. D/64 - 1 form it while the others already work on tile t0
+            double sq = 0.0;
+            if (tid < D) {
+                double tot = 0.0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tot += bs_part[w][tid];
+                ksum_after = ksum_before + tot;
+                const double m = ksum_after / (double)p.n;
+                mu_s[tid] = m;
+                sq = m * m;
+            }
+            sq = row_allreduce_f64<16>(sq);
+            if ((lane & 15) == 0) red[wave][lane >> 4] = sq;
+        }
         qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
         if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
         float mloc[NQ];
@@ -537,6 +546,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 #pragma unroll
         for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
             mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+        if (need_sum) __syncthreads();   // the anchor is complete before any row is scored
     }
     // ---- the tile loop, software pipelined by hand (one wave per SIMD: nothing else hides a
     // latency).  Iteration t:
