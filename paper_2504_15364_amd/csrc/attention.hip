@@ -147,12 +147,15 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     // Copy i of a wave covers rows RPL (wave + NW i) ..: NW RPL is a multiple of 8, so the swizzle
     // terms (row % UPR, row & 3) are those of copy 0 and copy i only adds i NW RPL rows.
-    static_assert((NW * RPL) % UPR == 0, "the swizzle of a lane must not depend on the copy index");
+    // ... or by half a period, which flips the top bit of the K swizzle: (row + UPR / 2) % UPR == (row % UPR) ^ (UPR / 2)
+    static_assert((NW * RPL) % UPR == 0 || (NW * RPL) % UPR == UPR / 2, "the K swizzle of copy i must follow from that of copy 0");
+    static_assert((NW * RPL) % 4 == 0, "the V swizzle of a lane must not depend on the copy index");
     constexpr int VSW = UPR / 4;     // V swizzle stride: unit ^ VSW (row & 3)
     constexpr int CSTEP = NW * RPL;  // rows between consecutive copies of one wave
     const int crow0 = RPL * wave + lane / UPR;   // row of copy 0 inside the tile
     const uint32_t koff0 = (uint32_t)(crow0 * ROWB + ((lane % UPR) ^ (crow0 & (UPR - 1))) * 16);
     const uint32_t voff0 = (uint32_t)(crow0 * ROWB + ((lane % UPR) ^ (VSW * (crow0 & 3))) * 16);
+    auto koff_of = [&](int i) { return koff0 ^ (uint32_t)((((i * CSTEP) & (UPR - 1))) * 16); };  // copy i of the K tile
     // A tile is "whole" when its 64 rows are valid and come from one source (the cache, or the
     // block's k_new / v_new): then only the base pointer differs.  A partial tile (it straddles len
     // or n; at most two per step) takes per-row pointers; rows past n read row n - 1 -- finite
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         const bool isv = c >= CPW;
         const int i = isv ? c - CPW : c;
         const uint32_t dst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B) + (isv ? TILE_B : 0) + 1024u * (wave + NW * i);
-        const uint32_t off0 = isv ? voff0 : koff0;
+        const uint32_t off0 = isv ? voff0 : koff_of(i);
         const bool whole = r0 + TILE_KEYS <= p.len || (r0 >= p.len && r0 + TILE_KEYS <= p.n);
         if (whole) {
             const bool cached = r0 < p.len;
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         const int i = isv ? c - CPW : c;
         const uint32_t dst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B) + (isv ? TILE_B : 0) + 1024u * (wave + NW * i);
         const uint16_t *src = (isv ? vcache : kcache) + ((size_t)t * TILE_KEYS + (size_t)i * CSTEP) * D;
-        async_copy16(dst, src, isv ? voff0 : koff0);
+        async_copy16(dst, src, isv ? voff0 : koff_of(i));
     };
     // tile t0 first, then the queries, then tile t0 + 1: one memory round trip covers all three
     if (ntl > 0) issue_tile(t0);

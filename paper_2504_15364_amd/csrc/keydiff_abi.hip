@@ -194,7 +194,7 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p)
 {
     const int BH = p.batch * p.hkv;
     const int Mtot = p.G * p.Bt;
-    p.NW = (Mtot % 256 == 0 || Mtot > 512) ? 8 : 4;
+    p.NW = (Mtot % 256 == 0 || Mtot > 512) ? 8 : 4;   // waves of 32 query rows per workgroup
     const int TM = 32 * p.NW;
     p.mtiles = (Mtot + TM - 1) / TM;
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
