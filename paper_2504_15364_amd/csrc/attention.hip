@@ -1,11 +1,12 @@
-// step_main: append + block attention over cache || block (Eq. 5, Eq. 1-2) for gfx950.
+// step_main: append (Eq. 5) + block attention over cache || block (Eq. 1-2) + anchor and cosine
+// score of every key (Method, "Efficient Variant"; appendix "FLOP count of KeyDiff") for gfx950.
 //
 // Flash-style: the attention matrix is never materialised (Method, "Efficient
 // Variant": KeyDiff needs no attention weights).  bf16 MFMA 32x32x16 for both
 // contractions, fp32 online softmax.
 //
 // Work decomposition.  All G * Bt query rows that share one KV head form the M
-// dimension (GQA packing): a workgroup of NW waves owns 32 * NW of them and a
+// dimension (GQA packing): a workgroup of NW waves owns 32 * NQ * NW of them and a
 // contiguous range of 64-key tiles (split-KV); the splits are merged by
 // log-sum-exp in step_post.  Workgroup ids map KV heads round-robin so that the
 // workgroups of one head share an XCD and its L2.
@@ -15,6 +16,7 @@
 // through a ring of STAGES buffers, so several tiles are in flight per CU while
 // one is computed.  Both tiles are stored row-major with a 16-byte-unit XOR swizzle
 // applied on the global side (a lane fetches the unit that belongs in its LDS slot).
+// The queries take the same road once, at the start.
 //
 // Both contractions are computed transposed so that softmax statistics are
 // per-lane scalars and P never leaves registers:
@@ -29,8 +31,10 @@
 //                 operand fetch exactly those two groups of 4 consecutive keys.
 //
 // The block's own rows are read straight from k_new / v_new; every workgroup
-// copies a slice of them into the cache (the append) and adds that slice to the
-// running key sum the anchor is derived from.
+// copies a slice of them into the cache (the append).  Every workgroup also sums
+// the block's keys in double (32 KB from L2) to form the key sum after this step
+// and from it the anchor, and scores the rows of its K tiles while they sit in LDS,
+// so the keys cross HBM once per step.
 #include <type_traits>
 
 #include "kd_kernels.h"
@@ -551,12 +555,13 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
         if (need_sum) __syncthreads();   // the anchor is complete before any row is scored
     }
-    // ---- the tile loop, software pipelined by hand (one wave per SIMD: nothing else hides a
-    // latency).  Iteration t:
-    //   stage A  the 2 NC MFMA pairs of S^T(t + 1), each issued with the K fragment read two
-    //            pairs ahead and one slice of the exponentials of tile t (vector pipe);
-    //   stage B  the 4 NDB MFMA pairs of O^T += V^T P^T(t), each with the V^T fragment read two
-    //            pairs ahead and one slice of the max scan of tile t + 1.
+    // ---- the tile loop, software pipelined by hand (at most two waves share a SIMD: little else
+    // hides a latency).  Iteration t:
+    //   stage A  the 2 NC MFMA groups of S^T(t + 1), each issued with the K fragment read a few
+    //            groups ahead, a share of the copies of tile t + 3 and of the exponentials of tile t;
+    //   stage B  the 4 NDB MFMA groups of O^T += V^T P^T(t), each with the V^T fragment read a few
+    //            groups ahead, the rest of the exponentials and one slice of the max scan of tile t + 1;
+    //   then the cosine score of tile t's rows if this workgroup owns them.
     // The scheduling barriers pin that order.  Tiles t + 2 and t + 3 are in flight meanwhile.
     // COPY: 0 no tile left to fetch, 1 the tile to fetch lies entirely in the cache, 2 decide per copy
     auto step = [&](int t, auto next_tag, auto masked_tag, auto copy_tag) {

@@ -1,10 +1,10 @@
-// step_score and step_post: cosine score (appendix "FLOP count of KeyDiff"), then selection
-// and compaction (Eq. 6-7) running next to the log-sum-exp merge of the attention partials.
+// step_post: selection and compaction (Eq. 6-7) running next to the log-sum-exp merge of the
+// attention partials; step_score: the cosine score (appendix "FLOP count of KeyDiff") of a cache
+// outside a block step (inside one, step_main scores the keys while it holds them in LDS).
 //
 // The score that decides an eviction is IEEE double arithmetic on the bf16 data,
-// rounded once to float: s_i = mu.k_i / max(|mu||k_i|, eps) with mu = ksum / n.
-// The pass is bandwidth bound, so the double FMAs are free; in exchange the
-// retained set does not depend on summation order beyond the last bit of a double.
+// rounded once to float: s_i = mu.k_i / max(|mu||k_i|, eps) with mu = ksum / n, so
+// the retained set does not depend on summation order beyond the last bit of a double.
 //
 // Selection.  One workgroup per head loads the head's scores once, bins them into a
 // 4096-bin LDS histogram (a monotone map of the float), scans it for the bin that
