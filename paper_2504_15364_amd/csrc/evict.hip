@@ -676,40 +676,63 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 }
 
 // ------------------------------------------------------------- ordered compaction
-// Stable in-place shift.  One workgroup per (sequence, KV head) walks the rows in
-// ascending chunks: a chunk's surviving rows are read into LDS, then written to
-// their destinations, which lie at or before their sources, so nothing unread is
-// overwritten.
-__global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p)
+// Stable in-place shift: kept row i moves to dst[i] = i - (evicted rows before i), so a row moves
+// down by at most E = n - N rows.  One workgroup per ORD_ROWS rows reads its moving rows into
+// registers, announces that (flag = epoch of this launch), waits until the workgroups whose rows
+// it may overwrite -- the ceil(E / ORD_ROWS) chunks before it -- have announced the same, and
+// stores.  Workgroups are numbered chunk-major, so a workgroup only ever waits for lower-numbered
+// ones; the wait is bounded and reports a timeout in the status word instead of hanging.
+template <int D>
+__global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p, int32_t *flags, int nchunks, int32_t epoch)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    const int bh = blockIdx.x, tid = threadIdx.x;
-    const int UPR = p.D / 8;
-    u32x4 *stage = reinterpret_cast<u32x4 *>(smem_raw);  // [2][CHUNK_ROWS][UPR]
-    uint16_t *kb = p.k + (size_t)bh * p.cap * p.D;
-    uint16_t *vb = p.v + (size_t)bh * p.cap * p.D;
+    constexpr int UPR = D / 8;
+    constexpr int UPT = ORD_ROWS * UPR * 2 / 1024;   // 16-byte units (K and V) per thread
+    static_assert(UPT * 1024 == ORD_ROWS * UPR * 2, "the chunk must divide over the threads");
+    const int BH = p.batch * p.hkv;
+    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH, tid = threadIdx.x;
+    uint16_t *kb = p.k + (size_t)bh * p.cap * D;
+    uint16_t *vb = p.v + (size_t)bh * p.cap * D;
     const int32_t *dst = p.dstmap + (size_t)bh * p.cap;
-    const int per_chunk = CHUNK_ROWS * UPR * 2;
-    for (int r0 = 0; r0 < p.n; r0 += CHUNK_ROWS) {
-        for (int w = tid; w < per_chunk; w += 1024) {
-            const int which = w / (CHUNK_ROWS * UPR), rem = w % (CHUNK_ROWS * UPR);
-            const int r = rem / UPR, u = rem % UPR;
-            const int row = r0 + r;
-            if (row < p.n && dst[row] >= 0 && dst[row] != row)
-                stage[w] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)row * p.D + u * 8);
-        }
-        __syncthreads();
-        for (int w = tid; w < per_chunk; w += 1024) {
-            const int which = w / (CHUNK_ROWS * UPR), rem = w % (CHUNK_ROWS * UPR);
-            const int r = rem / UPR, u = rem % UPR;
-            const int row = r0 + r;
-            if (row < p.n) {
-                const int d = dst[row];
-                if (d >= 0 && d != row)
-                    *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)d * p.D + u * 8) = stage[w];
+    const int r0 = chunk * ORD_ROWS;
+    u32x4 val[UPT];
+    int drow[UPT];
+#pragma unroll
+    for (int q = 0; q < UPT; ++q) {
+        const int w = q * 1024 + tid;
+        const int which = w >= ORD_ROWS * UPR, rem = w - which * ORD_ROWS * UPR;
+        const int row = r0 + rem / UPR, u = rem % UPR;
+        drow[q] = -1;
+        val[q] = u32x4{0u, 0u, 0u, 0u};
+        if (row < p.n) {
+            const int d = dst[row];
+            if (d >= 0 && d != row) {
+                drow[q] = d;
+                val[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)row * D + u * 8);
             }
         }
-        __syncthreads();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // every row of this chunk is in registers
+    __syncthreads();
+    int32_t *myflags = flags + (size_t)bh * nchunks;
+    if (tid == 0) __hip_atomic_store(&myflags[chunk], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int reach = (p.n - p.N + ORD_ROWS - 1) / ORD_ROWS;   // chunks below this one its rows can land in
+    if (tid < reach && chunk - 1 - tid >= 0) {
+        int spins = 0;
+        while (__hip_atomic_load(&myflags[chunk - 1 - tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+            if (++spins > ORD_SPIN_LIMIT) {
+                atomicOr(p.status, STATUS_ORDER_TIMEOUT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < UPT; ++q) {
+        const int w = q * 1024 + tid;
+        const int which = w >= ORD_ROWS * UPR, rem = w - which * ORD_ROWS * UPR;
+        if (drow[q] >= 0)
+            *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)drow[q] * D + (rem % UPR) * 8) = val[q];
     }
 }
 
@@ -814,16 +837,12 @@ size_t post_lds_bytes(int n, int N)
     return b + 16;
 }
 
-static size_t compact_lds_bytes(int D) { return (size_t)2 * CHUNK_ROWS * (D / 8) * 16; }
 
 hipError_t configure_main_kernels();
 
 hipError_t configure_kernels()
 {
     hipError_t e = configure_main_kernels();
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(compact_ordered_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)compact_lds_bytes(128));
     if (e != hipSuccess) return e;
     const int post_max = (int)(MAX_CAP / 8 + LISTS_LDS_MAX + 16);
     const void *post_fns[] = {reinterpret_cast<const void *>(step_post_kernel<128, SPT_SMALL>),
@@ -860,9 +879,14 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s)
+hipError_t launch_compact_ordered(const StepParams &p, int32_t *flags, int32_t epoch, hipStream_t s)
 {
-    hipLaunchKernelGGL(compact_ordered_kernel, dim3(p.batch * p.hkv), dim3(1024), compact_lds_bytes(p.D), s, p);
+    const int nchunks = (p.n + ORD_ROWS - 1) / ORD_ROWS;
+    const int grid = p.batch * p.hkv * nchunks;
+    if (p.n - p.N > 1024 * ORD_ROWS) return hipErrorInvalidValue;   // one waiting thread per chunk in reach
+    if (p.D == 128) hipLaunchKernelGGL((compact_ordered_kernel<128>), dim3(grid), dim3(1024), 0, s, p, flags, nchunks, epoch);
+    else if (p.D == 64) hipLaunchKernelGGL((compact_ordered_kernel<64>), dim3(grid), dim3(1024), 0, s, p, flags, nchunks, epoch);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

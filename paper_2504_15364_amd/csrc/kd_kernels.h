@@ -20,10 +20,13 @@ constexpr int SCORE_THREADS = 256;  // workgroup size of step_score
 constexpr int SCORE_ROWS = 256;     // rows per step_score workgroup: 64 per wave
 constexpr int HIST_BINS = 4096;     // score histogram resolution in step_post (bins over [-1, 1])
 constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
+constexpr int ORD_ROWS = 128;       // rows per workgroup of the ordered compaction
+constexpr int ORD_SPIN_LIMIT = 1 << 20;  // polls of a predecessor's flag before giving up
 constexpr int MAX_CAP = 32768;      // budget_N + block_B limit (selection bitmaps, ownership)
 
 // status bits kernels may raise (device word in the metadata buffer)
 constexpr int STATUS_SELECT_COUNT = 1;  // selection evicted a number of rows other than n - N
+constexpr int STATUS_ORDER_TIMEOUT = 2; // ordered compaction: a workgroup gave up waiting for its predecessors
 
 struct StepParams {
     // tensors of the call
@@ -61,7 +64,8 @@ hipError_t configure_kernels();      // one-time function attributes (dynamic LD
 hipError_t launch_step_main(const StepParams &p, hipStream_t s);
 hipError_t launch_step_score(const StepParams &p, hipStream_t s);
 hipError_t launch_step_post(const StepParams &p, hipStream_t s);
-hipError_t launch_compact_ordered(const StepParams &p, hipStream_t s);
+// flags: [BH][ceil(cap / ORD_ROWS)] int32 in zero-initialised device memory; epoch: a value no earlier launch used
+hipError_t launch_compact_ordered(const StepParams &p, int32_t *flags, int32_t epoch, hipStream_t s);
 hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s);
 hipError_t launch_zero_words(int32_t *p, size_t nwords, hipStream_t s);
 hipError_t launch_load_rows(const uint16_t *src, uint16_t *dst, int BH, int cap, int D, int len,

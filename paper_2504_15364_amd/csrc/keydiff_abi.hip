@@ -28,7 +28,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
     size_t k_bytes, meta_bytes, scratch_bytes;
-    size_t off_pos, off_ksum, off_status;                                             // in meta
+    size_t off_pos, off_ksum, off_status, off_oflags;                                 // in meta
     size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part;  // in scratch
     int cap, max_part_rows;
 };
@@ -66,6 +66,7 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_pos = off;     off += align256(BH * L.cap * 4);
     L.off_ksum = off;    off += align256(2 * BH * D * 8);  // double buffer: see StepParams::ksum_next
     L.off_status = off;  off += 256;
+    L.off_oflags = off;  off += align256(BH * ((L.cap + kd::ORD_ROWS - 1) / kd::ORD_ROWS) * 4);  // ordered compaction
     L.meta_bytes = off;
     // split-KV partial rows: splits * BH * G * Bt never exceeds this (see plan_attention)
     const int max_mtiles = (G * c->block_B + 127) / 128;
@@ -101,6 +102,7 @@ struct keydiff_cache {
     float scale_log2e;
     bool contiguous;      // every block so far started where the previous one ended
     int64_t next_pos;
+    int32_t epoch;        // launches of the ordered compaction so far (its flags compare against it)
     int kpar;             // which half of the key-sum double buffer holds the current sum
     bool profiling;
     std::vector<ProfEvent> events;
@@ -255,6 +257,7 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->next_pos = -1;
     c->profiling = false;
     c->kpar = 0;
+    c->epoch = 0;
     static hipError_t configured = kd::configure_kernels();  // once per process
     hipError_t e = configured;
     if (e == hipSuccess)
@@ -328,7 +331,9 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
     }
     if (evict && cf.layout == KEYDIFF_LAYOUT_ORDERED) {
         ProfScope ps(c, KEYDIFF_K_COMPACT, s);
-        KD_LAUNCH(kd::launch_compact_ordered(p, s), "ordered compaction kernel");
+        c->epoch = c->epoch == 0x7fffffff ? 1 : c->epoch + 1;
+        KD_LAUNCH(kd::launch_compact_ordered(p, reinterpret_cast<int32_t *>(c->meta + c->L.off_oflags), c->epoch, s),
+                  "ordered compaction kernel");
     }
     if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
     c->kpar ^= 1;   // step_main wrote the new key sum into the other half
