@@ -175,6 +175,65 @@ def test_ties_keep_the_lower_position(layout):
     assert np.array_equal(np.sort(cache.positions().cpu().numpy())[0, 0], np.arange(N))
 
 
+def test_thousands_of_identical_keys_take_the_radix_path():
+    # every score equal: the threshold bin holds all rows (more than the LDS ranking takes), so the
+    # selection falls back to the radix select on (score bits, position); the survivors must be the
+    # N lowest positions
+    hq, hkv, d, N, B = 2, 1, 64, 2560, 512
+    T = N + 2 * B
+    w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
+    data = make_layer(w, seed=13)
+    same = f32_to_bf16_bits(np.tile(np.linspace(0.5, 1.5, d, dtype=np.float32), (T, hkv, 1)))
+    data = dict(data, k=same)
+    cache, oc = make_pair(w, N, B, layout=kd.LAYOUT_FILL)
+    for t, Bt, q, k, v in blocks(data, B):
+        cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        oc.prefill_block(None, k, v, t)
+    check_state(cache, oc, "identical keys")
+    assert np.array_equal(np.sort(cache.positions().cpu().numpy())[0, 0], np.arange(N))
+    assert cache.status() == 0
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+def test_block_larger_than_the_budget(layout):
+    # the very first block overflows the budget: rows are evicted before any was ever kept
+    w = get_config("toy").small(n_q_heads=4, n_kv_heads=2, head_dim=64, prompt_T=192)
+    data = make_layer(w, seed=14)
+    run_prompt(w, data, 16, 64, layout=layout)
+
+
+def test_single_tokens_from_an_empty_cache():
+    # B = 1 from the first token on: one-key attention, then one eviction per step once full
+    w = get_config("toy").small(n_q_heads=4, n_kv_heads=2, head_dim=128, prompt_T=40)
+    data = make_layer(w, seed=15)
+    run_prompt(w, data, 24, 1, layout=kd.LAYOUT_FILL)
+
+
+def test_largest_capacity():
+    # budget_N + block_B at the limit of the library (32768 rows): the large selection instantiation,
+    # lists in device memory, 512 key tiles.  One head pair keeps the oracle fast; the cache is brought
+    # to the budget by a load, then two block steps run, the first with attention checked.
+    hq, hkv, d, B = 2, 1, 128, 256
+    N = 32768 - B
+    w = get_config("llama31_8b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=N + 2 * B)
+    data = make_layer(w, seed=16)
+    cache, oc = make_pair(w, N, B, layout=kd.LAYOUT_FILL)
+    K0 = data["k"][:N].transpose(1, 0, 2)[None].copy()
+    V0 = data["v"][:N].transpose(1, 0, 2)[None].copy()
+    P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (1, hkv, N)).copy()
+    cache.load(to_dev(K0), to_dev(V0), torch.from_numpy(P0).cuda())
+    oc.load(K0, V0, P0)
+    for i, (t, Bt, q, k, v) in enumerate(b for b in blocks(data, B) if b[0] >= N):
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.prefill_block(q if i == 0 else None, k, v, t)
+        assert ev == B
+        if i == 0:
+            assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
+        check_state(cache, oc, f"largest capacity, token {t}")
+    assert cache.status() == 0
+    cache.close()
+
+
 def test_zero_key_and_tiny_keys_hit_the_eps_clamp():
     hq, hkv, d, N, B = 2, 1, 64, 40, 16
     w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=64)
