@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--seed", type=int, default=20250415)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--no-whole-prompt", dest="whole_prompt", action="store_false",
+                    help="skip the whole-prompt run of one layer (fill steps + evicting steps)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain device copies of a known size (untimed), so that a rocprofv3 "
                          "--pmc run of this command holds the counter's reading for a known byte count")
@@ -188,6 +190,31 @@ def main():
     t_min = max(flops_attn / (PEAK_BF16_MFMA_TFLOPS * 1e12), bytes_step / (PEAK_HBM_GBPS * 1e9))
     step_frac = t_min / (us_per_layer_step * 1e-6)
 
+    # ---- whole prompt of one layer: the N / B fill steps (fewer keys, nothing evicted) and every
+    # evicting step, back to back from an empty cache
+    whole = None
+    if args.whole_prompt:
+        wl = make_layer(w, seed=args.seed + 100 * 3, layer=0, t1=w.prompt_T)
+        wq, wk, wv = (to_blocks(wl[x], B) for x in ("q", "k", "v"))
+        wc = kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=layout))
+        wout = torch.empty_like(wq[0])
+        nb = w.prompt_T // B
+        empty_kv = torch.empty((w.batch, Hkv, 0, D), dtype=torch.bfloat16, device="cuda")
+        empty_pos = torch.empty((w.batch, Hkv, 0), dtype=torch.int32, device="cuda")
+        for rep in range(2):                       # first pass warms up, second is timed
+            wc.load(empty_kv, empty_kv, empty_pos)  # back to the empty cache
+            torch.cuda.synchronize()
+            t_w = time.perf_counter()
+            for b_ in range(nb):
+                wc.prefill_block(wq[b_], wk[b_], wv[b_], b_ * B, out=wout)
+            torch.cuda.synchronize()
+            t_w = time.perf_counter() - t_w
+        whole = {"prompt_tokens": w.prompt_T, "steps": nb, "fill_steps": fill_blocks, "ms_per_layer": t_w * 1e3,
+                 "tokens_per_s_per_layer": w.prompt_T / t_w,
+                 "tokens_per_s_all_layers_extrapolated": w.prompt_T / (t_w * L), "layers_extrapolated": L}
+        assert wc.status() == 0
+        wc.close()
+
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -229,7 +256,7 @@ def main():
         "us_per_layer_step": us_per_layer_step,
         "step_roofline": {"binding": "mfma" if flops_attn / 2.5e15 > bytes_step / 8e12 else "hbm",
                           "t_min_us": t_min * 1e6, "frac": step_frac, "flops": flops_attn, "bytes": bytes_step},
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "whole_prompt": whole, "cpu_baseline": cpu,
     }))
 
 
