@@ -602,7 +602,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
                 for (int e = 0; e < SPG; ++e) slice_F(s, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
             }
         };
-        constexpr int KAHEAD = 3, VAHEAD = 3;  // fragment reads run this many MFMA pairs ahead
+        constexpr int KAHEAD = 2, VAHEAD = 2;  // fragment reads run this many MFMA groups ahead (deeper spills)
         const unsigned char *tV = smem + (size_t)(t % STAGES) * 2 * TILE_B + TILE_B;
         const unsigned char *tK = smem + (size_t)((t + 1) % STAGES) * 2 * TILE_B;
         f32x16 sn[NQ][2];
