@@ -69,8 +69,9 @@ def main():
     ap.add_argument("--seed", type=int, default=20250415)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
-    ap.add_argument("--no-whole-prompt", dest="whole_prompt", action="store_false",
-                    help="skip the whole-prompt run of one layer (fill steps + evicting steps)")
+    ap.add_argument("--whole-prompt", action="store_true",
+                    help="also time the whole prompt of one layer from an empty cache (fill steps + evicting "
+                         "steps); off by default so that every launch of the default run is a steady-state one")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain device copies of a known size (untimed), so that a rocprofv3 "
                          "--pmc run of this command holds the counter's reading for a known byte count")
