@@ -96,8 +96,10 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// NQ: 32-row query blocks per wave; every K / V fragment read from LDS feeds one MFMA per block
-template <int D, int NW, int NQ>
+// NQ: 32-row query blocks per wave; every K / V fragment read from LDS feeds one MFMA per block.
+// HELP: some waves of a workgroup may have no query row at all (few query rows: decode); such a
+// wave takes no part in the attention, it copies its share of every tile and scores rows.
+template <int D, int NW, int NQ, bool HELP>
 __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 {
     constexpr int NT = 64 * NW;   // threads
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         qj[a] = valid[a] ? mrow[a] % p.Bt : 0;
         vis[a] = p.len + qj[a] + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
     }
+    const bool active = !HELP || mt * TM + wave * (32 * NQ) < Mtot;   // wave uniform
     constexpr int QROWS = 32 * NQ, QBYTES = QROWS * ROWB;
     static_assert(NW * QBYTES <= 2 * 2 * TILE_B && (2 * TILE_B) % QBYTES == 0, "query staging uses two ring buffers");
     const int qoff = wave * QBYTES, qhalf = qoff / (2 * TILE_B);
@@ -465,7 +468,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         staged = 0;
     };
-    auto score_tile = [&](int t) {
+    auto score_tile_fixed = [&](int t) {
         constexpr int RPP = 64 / UPR;            // rows per pass
         constexpr int PASSES = TILE_KEYS / NW / RPP;
         static_assert(PASSES >= 1, "a wave scores at least one pass of rows per tile");
@@ -521,6 +524,75 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
         staged += PASSES * RPP;
         if (staged + PASSES * RPP > 64) flush_scores();
     };
+    // Which waves score when some have no query rows: only those, so that the waves carrying the
+    // attention do not also carry the score.  A scoring wave takes the passes (RPP consecutive rows
+    // each) sidx, sidx + nscore, ... of every tile its workgroup owns.
+    const int nactive = HELP ? min(NW, (Mtot - mt * TM + 32 * NQ - 1) / (32 * NQ)) : NW;
+    const int nscore = nactive < NW ? NW - nactive : NW;
+    const int sidx = nactive < NW ? wave - nactive : wave;   // negative: this wave does not score
+    auto score_tile_shared = [&](int t) {
+        constexpr int RPP = 64 / UPR;              // rows per pass
+        constexpr int TPASS = TILE_KEYS / RPP;     // passes per tile
+        if (sidx < 0) return;
+        const unsigned char *tK = smem + (size_t)(t % STAGES) * 2 * TILE_B;
+        const int u = lane % UPR, rl = lane / UPR;
+        double mu8[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mu8[i] = mu_s[u * 8 + i];
+        auto partial = [&](int ps, double &dot, double &k2) {
+            const int r = ps * RPP + rl;
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(tK + r * ROWB + ((u ^ (r & (UPR - 1))) * 16));
+            dot = 0.0;
+            k2 = 0.0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const double a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+                dot = __builtin_fma(mu8[2 * i], a, dot);
+                k2 = __builtin_fma(a, a, k2);
+                dot = __builtin_fma(mu8[2 * i + 1], b, dot);
+                k2 = __builtin_fma(b, b, k2);
+            }
+        };
+        int ps = sidx;   // wave uniform
+        if constexpr (UPR == 16) {
+            // two passes at a time, see score_tile
+            for (; ps + nscore < TPASS; ps += 2 * nscore) {
+                double d0, q0, d1, q1;
+                partial(ps, d0, q0);
+                partial(ps + nscore, d1, q1);
+                const double v = row_reduce_scatter4_f64(d0, q0, d1, q1, u);
+                if ((u & 3) == 0) {
+                    const int second = u >> 3;
+                    const int slot = staged + second * RPP + rl;
+                    if (u & 4) st_k2[wave][slot] = v;
+                    else {
+                        st_dot[wave][slot] = v;
+                        st_row[wave][slot] = t * TILE_KEYS + (ps + second * nscore) * RPP + rl;
+                    }
+                }
+                staged += 2 * RPP;
+            }
+        }
+        for (; ps < TPASS; ps += nscore) {
+            double dot, k2;
+            partial(ps, dot, k2);
+            dot = row_allreduce_f64<UPR>(dot);
+            k2 = row_allreduce_f64<UPR>(k2);
+            if (u == 0) {
+                const int slot = staged + rl;
+                st_dot[wave][slot] = dot;
+                st_k2[wave][slot] = k2;
+                st_row[wave][slot] = t * TILE_KEYS + ps * RPP + rl;
+            }
+            staged += RPP;
+        }
+        // room for the next tile's rows of this wave?
+        if (staged + ((TPASS + nscore - 1) / nscore) * RPP > 64) flush_scores();
+    };
+    auto score_tile = [&](int t) {
+        if constexpr (HELP) score_tile_shared(t);
+        else score_tile_fixed(t);
+    };
     const bool scoring = p.do_score != 0;
 
     const int tint = min(t1, max(t0, p.len / TILE_KEYS));  // tiles before it: every key cached, no mask
@@ -546,13 +618,15 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             sq = row_allreduce_f64<16>(sq);
             if ((lane & 15) == 0) red[wave][lane >> 4] = sq;
         }
-        qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
-        if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
-        float mloc[NQ];
-        tile_max(s, mloc);
+        if (active) {
+            qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
+            if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
+            float mloc[NQ];
+            tile_max(s, mloc);
 #pragma unroll
-        for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
-            mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+            for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
+                mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+        }
         if (need_sum) __syncthreads();   // the anchor is complete before any row is scored
     }
     // ---- the tile loop, software pipelined by hand (at most two waves share a SIMD: little else
@@ -615,6 +689,19 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
             if (t + 2 < t1) wait_copies<LPW>();
             else wait_copies<0>();
             __syncthreads();
+        }
+        if (HELP && !active) {
+            if (NEXT) {
+#pragma unroll
+                for (int c = 0; c < LPW; ++c) {
+                    if (COPY == 1) issue_copy_cached(t + STAGES - 1, c);
+                    if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
+                }
+            }
+            if (scoring && t % p.mtiles == mt) score_tile(t);
+            return;
+        }
+        if (NEXT) {
 #pragma unroll
             for (int i = 0; i < KAHEAD; ++i) kf[i] = read_k(tK, i);
         }
@@ -735,7 +822,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     // transaction per piece.  Each wave transposes its 32 NQ rows through a private piece of LDS
     // (the two ring buffers no tile occupies after the last barrier) and stores whole rows, 16
     // bytes per lane; the rows of a wave are contiguous in memory in both output forms.
-    {
+    if (active) {
         constexpr int WROWS = 32 * NQ, WBYTES = WROWS * ROWB;
         static_assert(NW * WBYTES <= 2 * 2 * TILE_B, "the transposition uses two ring buffers");
         // stages (t1 + 1) % STAGES and t1 % STAGES: tiles t1 - 3 and t1 - 4 (or never filled)
@@ -802,10 +889,14 @@ hipError_t configure_main_kernels()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             (int)main_lds_bytes(D));                                               \
     if (e != hipSuccess) return e;
-    KD_SET((step_main_kernel<128, 8, 1>), 128)
-    KD_SET((step_main_kernel<128, 4, 1>), 128)
-    KD_SET((step_main_kernel<64, 8, 1>), 64)
-    KD_SET((step_main_kernel<64, 4, 1>), 64)
+    KD_SET((step_main_kernel<128, 8, 1, false>), 128)
+    KD_SET((step_main_kernel<128, 8, 1, true>), 128)
+    KD_SET((step_main_kernel<128, 4, 1, false>), 128)
+    KD_SET((step_main_kernel<128, 4, 1, true>), 128)
+    KD_SET((step_main_kernel<64, 8, 1, false>), 64)
+    KD_SET((step_main_kernel<64, 8, 1, true>), 64)
+    KD_SET((step_main_kernel<64, 4, 1, false>), 64)
+    KD_SET((step_main_kernel<64, 4, 1, true>), 64)
 #undef KD_SET
     return hipSuccess;
 }
@@ -814,10 +905,17 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 {
     const int grid = p.batch * p.hkv * p.mtiles * p.splits;
     const size_t lds = main_lds_bytes(p.D);
-    if (p.D == 128 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<128, 8, 1>), dim3(grid), dim3(512), lds, s, p);
-    else if (p.D == 128 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<128, 4, 1>), dim3(grid), dim3(256), lds, s, p);
-    else if (p.D == 64 && p.NW == 8) hipLaunchKernelGGL((step_main_kernel<64, 8, 1>), dim3(grid), dim3(512), lds, s, p);
-    else if (p.D == 64 && p.NW == 4) hipLaunchKernelGGL((step_main_kernel<64, 4, 1>), dim3(grid), dim3(256), lds, s, p);
+    // workgroups whose last waves have no query row at all run the variant in which those waves help
+    const int TM = 32 * p.NW;
+    const bool help = p.mtiles * TM - p.G * p.Bt >= 32;
+#define KD_GO(DD, WW)                                                                                          \
+    if (help) hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, true>), dim3(grid), dim3(64 * WW), lds, s, p);  \
+    else hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, false>), dim3(grid), dim3(64 * WW), lds, s, p);
+    if (p.D == 128 && p.NW == 8) { KD_GO(128, 8) }
+    else if (p.D == 128 && p.NW == 4) { KD_GO(128, 4) }
+    else if (p.D == 64 && p.NW == 8) { KD_GO(64, 8) }
+    else if (p.D == 64 && p.NW == 4) { KD_GO(64, 4) }
+#undef KD_GO
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
