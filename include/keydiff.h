@@ -147,8 +147,8 @@ KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *stat
  * keydiff_profile_read synchronises, writes the summed milliseconds and launch
  * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
 enum {
-    KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key-sum update          */
-    KEYDIFF_K_SCORE = 1,   /* step_score: cosine score of every row                            */
+    KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key sum + cosine scores */
+    KEYDIFF_K_SCORE = 1,   /* step_score: cosine scores outside a block step (keydiff_scores)  */
     KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction             */
     KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
     KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */
