@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--layers", type=int, default=0, help="0 = the workload's layer count")
     ap.add_argument("--layout", choices=["fill", "ordered"], default="fill")
+    ap.add_argument("--eviction", choices=["deferred", "immediate"], default="deferred",
+                    help="deferred: the selection and compaction of layer l runs inside the attention launch "
+                         "of layer l + 1 (keydiff_prefill_block_deferred); immediate: inside layer l's own step")
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps timed per kernel with HIP events")
     ap.add_argument("--seed", type=int, default=20250415)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -110,9 +113,18 @@ def main():
         dv.append(to_blocks(layers[l]["v"], B))
         outs.append(torch.empty_like(dq[l][0]))
 
+    deferred = args.eviction == "deferred" and args.layout == "fill" and L > 1
+
     def run_block(i):
         for l in range(L):
-            caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
+            if deferred:   # layer l takes along the eviction layer l - 1 left pending (layer 0: the last layer's)
+                caches[l].prefill_block_deferred(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l], carry=caches[l - 1])
+            else:
+                caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
+
+    def finish_all():   # the one eviction still pending belongs to the timed work
+        if deferred:
+            caches[L - 1].finish()
 
     def load_first_N(cache, l):
         # while n <= N nothing is evicted, so after the first N tokens the cache IS those tokens in
@@ -133,6 +145,7 @@ def main():
     for _ in range(args.warmup):
         run_block(i)
         i += 1
+    finish_all()
     if args.pmc_calibration:
         src = torch.empty(CALIBRATION_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(3)
         dst = torch.empty_like(src)
@@ -144,6 +157,7 @@ def main():
     for _ in range(args.steps):
         run_block(i)
         i += 1
+    finish_all()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed / args.steps * 1e3
@@ -158,6 +172,7 @@ def main():
         for _ in range(args.profile_steps):
             run_block(i)
             i += 1
+        finish_all()
         torch.cuda.synchronize()
         tot = {}
         for c in caches:
@@ -252,7 +267,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "budget_N": N,
-                   "block_B": B, "layers": L, "layout": args.layout, "tokens_per_step": B,
+                   "block_B": B, "layers": L, "layout": args.layout,
+                   "eviction": "deferred" if deferred else "immediate", "tokens_per_step": B,
                    "step": "one steady-state block step through every layer"},
         "us_per_layer_step": us_per_layer_step,
         "step_roofline": {"binding": "mfma" if flops_attn / 2.5e15 > bytes_step / 8e12 else "hbm",

@@ -114,12 +114,37 @@ KEYDIFF_API int keydiff_prefill_block(keydiff_cache_t *cache, const void *q, con
                           const void *v_new, int32_t Bt, int64_t pos0, void *out,
                           float *scores_out, void *stream);
 
+/* The block step of one layer of a model whose layers run one after the other, with its
+ * eviction left pending.  Attention of layer l + 1 does not depend on the eviction of layer l
+ * (Fig. 1: the eviction follows the attention; only the same layer's next block reads the
+ * compacted cache), and a selection keeps one compute unit per head busy with a chain of short
+ * stages while the attention fills the others: so this call appends, attends and scores
+ * `cache` as keydiff_prefill_block does, merges the attention partials so that `out` is complete
+ * in stream order, and leaves the selection and compaction of `cache` to be done
+ *   - inside the step_main launch of a later keydiff_prefill_block_deferred call that names
+ *     this cache as `carry` (same stream, same head_dim), or
+ *   - by keydiff_finish, or by any other call on `cache` (each finishes it first, on its own
+ *     stream argument or, for keydiff_destroy_cache, on the stream of the deferred call).
+ * `carry` is nullable and must differ from `cache`; if it has a pending eviction this call
+ * enqueues it (in the same launch when the shapes allow it, otherwise as a launch of its own
+ * before it), so after the call `carry` has none.  Until its eviction is enqueued the rows of
+ * `cache` are the n = len + Bt rows before compaction and its scratch buffer is in use: a
+ * cache used this way needs a scratch buffer of its own.  The ORDERED layout does not defer:
+ * there the call behaves like keydiff_prefill_block.  The retained set, the scores and `out`
+ * are those of keydiff_prefill_block bit for bit.                                          */
+KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const void *q, const void *k_new,
+                                   const void *v_new, int32_t Bt, int64_t pos0, void *out,
+                                   keydiff_cache_t *carry, void *stream);
+
+/* Enqueue the pending eviction of `cache` on `stream`, if it has one (else a no-op). */
+KEYDIFF_API int keydiff_finish(keydiff_cache_t *cache, void *stream);
+
 /* Generation phase: the block step with B = 1 (Background, block prompt
  * processing).  q [batch][n_q_heads][1][head_dim] and so on.                   */
 KEYDIFF_API int keydiff_decode_step(keydiff_cache_t *cache, const void *q, const void *k_new,
                         const void *v_new, int64_t pos, void *out, void *stream);
 
-/* KeyDiff scores of the rows currently cached, no mutation:
+/* KeyDiff scores of the rows currently cached, no mutation (a pending eviction is finished first):
  * scores_out float [batch][n_kv_heads][len], row order of the cache.
  * ESTATE if the cache is empty.                                                */
 KEYDIFF_API int keydiff_scores(const keydiff_cache_t *cache, float *scores_out, void *stream);
@@ -147,9 +172,11 @@ KEYDIFF_API int keydiff_cache_status(const keydiff_cache_t *cache, int32_t *stat
  * keydiff_profile_read synchronises, writes the summed milliseconds and launch
  * counts of each kernel class (arrays of KEYDIFF_NKERNELS, host) and resets.    */
 enum {
-    KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key sum + cosine scores */
+    KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key sum + cosine scores
+                              (+ the carried selection of another cache, if any)               */
     KEYDIFF_K_SCORE = 1,   /* step_score: cosine scores outside a block step (keydiff_scores)  */
-    KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction             */
+    KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction (either half
+                              alone when the eviction is deferred or finished on its own)      */
     KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
     KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */
     KEYDIFF_K_EVENT_PAIR = 5, /* no kernel: an empty event pair recorded once per profiled block

@@ -18,7 +18,8 @@ LAYOUT_ORDERED, LAYOUT_FILL = 0, 1
 KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux", "event_pair")
 
 EXPORTS = (
-    "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_decode_step",
+    "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_deferred",
+    "keydiff_finish", "keydiff_decode_step",
     "keydiff_scores", "keydiff_cache_len", "keydiff_cache_positions", "keydiff_cache_load",
     "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
     "keydiff_last_error", "keydiff_version",
@@ -73,6 +74,8 @@ def load_library() -> C.CDLL:
     L.keydiff_workspace_bytes.argtypes = [C.POINTER(_Config), szp, szp, szp, szp]
     L.keydiff_init_cache.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, C.POINTER(vp)]
     L.keydiff_prefill_block.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    L.keydiff_prefill_block_deferred.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    L.keydiff_finish.argtypes = [vp, vp]
     L.keydiff_decode_step.argtypes = [vp, vp, vp, vp, i64, vp, vp]
     L.keydiff_scores.argtypes = [vp, vp, vp]
     L.keydiff_cache_len.argtypes = [vp, C.POINTER(i32)]
@@ -155,6 +158,23 @@ class KeyDiffCache:
                                              scores_out.data_ptr() if scores_out is not None else None,
                                              _stream_ptr(stream)))
         return out
+
+    def prefill_block_deferred(self, q, k_new, v_new, pos0: int, out=None, carry=None, stream=None):
+        """The block step with its eviction left pending; `carry` is another KeyDiffCache whose
+        pending eviction this call takes along."""
+        import torch
+        Bt = k_new.shape[-2]
+        for t in (q, k_new, v_new):
+            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
+        if out is None:
+            out = torch.empty_like(q)
+        _check(self._L.keydiff_prefill_block_deferred(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
+                                                      int(pos0), out.data_ptr(),
+                                                      carry._h if carry is not None else None, _stream_ptr(stream)))
+        return out
+
+    def finish(self, stream=None):
+        _check(self._L.keydiff_finish(self._h, _stream_ptr(stream)))
 
     def decode_step(self, q, k_new, v_new, pos: int, out=None, stream=None):
         import torch

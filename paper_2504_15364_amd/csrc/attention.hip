@@ -39,6 +39,7 @@
 
 #include "kd_kernels.h"
 #include "kd_device.h"
+#include "kd_select.h"
 
 namespace kd {
 
@@ -100,7 +101,7 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
 // HELP: some waves of a workgroup may have no query row at all (few query rows: decode); such a
 // wave takes no part in the attention, it copies its share of every tile and scores rows.
 template <int D, int NW, int NQ, bool HELP>
-__global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
+__device__ __forceinline__ void step_main_body(const StepParams &p, const int block_id)
 {
     constexpr int NT = 64 * NW;   // threads
     constexpr int TM = 32 * NQ * NW;          // query rows per workgroup
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int BH = p.batch * p.hkv;
-    int id = blockIdx.x;
+    int id = block_id;
     const int bh = id % BH;
     id /= BH;
     const int mt = id % p.mtiles;
@@ -880,6 +881,34 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     }
 }
 
+template <int D, int NW, int NQ, bool HELP>
+__global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
+{
+    step_main_body<D, NW, NQ, HELP>(p, (int)blockIdx.x);
+}
+
+// step_main with passengers: the first `ncarry` workgroups run the pending selection and
+// compaction of another cache (one head each, parameters `cy`), the rest are the workgroups of
+// step_main proper.  A selection is a chain of short dependent stages that keeps one compute unit
+// busy per head for about half as long as the attention keeps the others busy: launched this way
+// it costs no time of its own.  The two caches share nothing, so no ordering between the two
+// kinds of workgroup is needed.
+template <int D>
+__global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepParams p, StepParams cy, int ncarry)
+{
+    if ((int)blockIdx.x < ncarry) {
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+        PostShared &sh = *reinterpret_cast<PostShared *>(smem);
+        uint32_t *evbits = reinterpret_cast<uint32_t *>(smem + carry_shared_bytes());
+        const int bh = (int)blockIdx.x;
+        int32_t *lists = cy.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (cy.n + 31) / 32)
+                                         : cy.lists + (size_t)bh * 4 * cy.B;
+        select_and_compact<D, SPT_CARRY, CARRY_THREADS>(cy, sh, evbits, lists, bh);
+        return;
+    }
+    step_main_body<D, 8, 1, false>(p, (int)blockIdx.x - ncarry);
+}
+
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
 
 hipError_t configure_main_kernels()
@@ -897,17 +926,20 @@ hipError_t configure_main_kernels()
     KD_SET((step_main_kernel<64, 8, 1, true>), 64)
     KD_SET((step_main_kernel<64, 4, 1, false>), 64)
     KD_SET((step_main_kernel<64, 4, 1, true>), 64)
+    KD_SET((step_main_carry_kernel<128>), 128)
+    KD_SET((step_main_carry_kernel<64>), 64)
 #undef KD_SET
     return hipSuccess;
 }
+
+// workgroups whose last waves have no query row at all run the variant in which those waves help
+static bool main_runs_help(const StepParams &p) { return p.mtiles * 32 * p.NW - p.G * p.Bt >= 32; }
 
 hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 {
     const int grid = p.batch * p.hkv * p.mtiles * p.splits;
     const size_t lds = main_lds_bytes(p.D);
-    // workgroups whose last waves have no query row at all run the variant in which those waves help
-    const int TM = 32 * p.NW;
-    const bool help = p.mtiles * TM - p.G * p.Bt >= 32;
+    const bool help = main_runs_help(p);
 #define KD_GO(DD, WW)                                                                                          \
     if (help) hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, true>), dim3(grid), dim3(64 * WW), lds, s, p);  \
     else hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, false>), dim3(grid), dim3(64 * WW), lds, s, p);
@@ -916,6 +948,26 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
     else if (p.D == 64 && p.NW == 8) { KD_GO(64, 8) }
     else if (p.D == 64 && p.NW == 4) { KD_GO(64, 4) }
 #undef KD_GO
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+bool can_carry(const StepParams &p, const StepParams &cy)
+{
+    const int ncarry = cy.batch * cy.hkv;
+    return p.NW == 8 && !main_runs_help(p) && p.D == cy.D && cy.do_evict && cy.layout == 1 &&
+           cy.n <= SPT_CARRY * CARRY_THREADS && cy.n <= 32 * CARRY_THREADS &&
+           carry_shared_bytes() + post_lds_bytes(cy.n, cy.N) <= main_lds_bytes(p.D) && ncarry > 0;
+}
+
+hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hipStream_t s)
+{
+    if (!can_carry(p, cy)) return hipErrorInvalidValue;
+    const int ncarry = cy.batch * cy.hkv;
+    const int grid = ncarry + p.batch * p.hkv * p.mtiles * p.splits;
+    const size_t lds = main_lds_bytes(p.D);
+    if (p.D == 128) hipLaunchKernelGGL((step_main_carry_kernel<128>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
+    else if (p.D == 64) hipLaunchKernelGGL((step_main_carry_kernel<64>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -13,111 +13,12 @@
 // position.  It then compacts the cache and takes the evicted keys out of ksum.
 #include "kd_kernels.h"
 #include "kd_device.h"
+#include "kd_select.h"
 
 namespace kd {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-
-constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
-constexpr int NWAVES = POST_THREADS / 64;
-constexpr int TAIL_WORDS = 72;                      // bitmap words the tail rows [N, n) may span on the fast path
-constexpr int SPT_SMALL = 12;                       // scores per thread: caches of up to 12288 rows
-constexpr int SPT_LARGE = MAX_CAP / POST_THREADS;   // ... and up to the limit
 constexpr int SCORE_WAVES = SCORE_THREADS / 64;
 
-// float -> unsigned key with the same order
-__device__ __forceinline__ uint32_t orderable(float s)
-{
-    const uint32_t b = __float_as_uint(s);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
-// monotone non-decreasing map of a score onto [0, HIST_BINS)
-__device__ __forceinline__ int score_bin(float s)
-{
-    const float f = floorf((s + 1.0f) * (float)(HIST_BINS / 2));
-    return (int)fminf(fmaxf(f, 0.f), (float)(HIST_BINS - 1));
-}
-
-struct PostShared {
-    uint32_t hist[HIST_BINS];  // score histogram of the head (a monotone map of the float)
-    uint32_t wave_tot[NWAVES];
-    uint64_t wave_tot64[NWAVES];
-    uint32_t radix_hist[256];
-    uint32_t sel_bin, sel_rank, sel_cnt;
-    int tb;           // threshold bin
-    uint32_t need;    // rows to evict from the threshold bin
-    uint32_t ncand, nev;
-    uint32_t cand_slot[CAND_MAX];
-    uint32_t cand_key[CAND_MAX];
-    int32_t cand_pos[CAND_MAX];
-    double colsum[NWAVES][128];
-    uint32_t tail_word[TAIL_WORDS], tail_base[TAIL_WORDS];  // mover bitmap words of rows >= N and movers before each
-};
-
-// value of the lane `ctrl` names (DPP), 0 where that lane lies outside the row or the row is masked out
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t dpp_fetch(uint32_t x)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, true);
-}
-
-// inclusive prefix sum over the 64 lanes of a wave, on the vector ALU alone: Hillis-Steele inside
-// each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and 2 into rows 1 and 3
-// (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31)
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
-{
-    x += dpp_fetch<0x111, 0xF>(x);
-    x += dpp_fetch<0x112, 0xF>(x);
-    x += dpp_fetch<0x114, 0xF>(x);
-    x += dpp_fetch<0x118, 0xF>(x);
-    x += dpp_fetch<0x142, 0xA>(x);
-    x += dpp_fetch<0x143, 0xC>(x);
-    return x;
-}
-__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t x)
-{
-#define KD_STEP64(CTRL, MASK)                                                                   \
-    x += ((uint64_t)dpp_fetch<CTRL, MASK>((uint32_t)(x >> 32)) << 32) | dpp_fetch<CTRL, MASK>((uint32_t)x);
-    KD_STEP64(0x111, 0xF)
-    KD_STEP64(0x112, 0xF)
-    KD_STEP64(0x114, 0xF)
-    KD_STEP64(0x118, 0xF)
-    KD_STEP64(0x142, 0xA)
-    KD_STEP64(0x143, 0xC)
-#undef KD_STEP64
-    return x;
-}
-
-// exclusive prefix sum over the workgroup (32-bit, or three packed 21-bit counters in 64 bits)
-template <typename T>
-__device__ __forceinline__ T block_exclusive_scan_t(T v, T *wave_tot, T *total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const T inc = wave_inclusive_scan(v);
-    __syncthreads();  // wave_tot free for reuse
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    T base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < NWAVES; ++w) {
-        const T t = wave_tot[w];
-        if (w < wave) base += t;
-        tot += t;
-    }
-    *total = tot;
-    return base + inc - v;
-}
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
-{
-    return block_exclusive_scan_t<uint32_t>(v, wave_tot, total);
-}
-__device__ __forceinline__ uint64_t block_exclusive_scan64(uint64_t v, uint64_t *wave_tot, uint64_t *total)
-{
-    return block_exclusive_scan_t<uint64_t>(v, wave_tot, total);
-}
 
 // ------------------------------------------------------------------------ scores
 struct ScoreShared {
@@ -206,386 +107,6 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
     }
 }
 
-// ---------------------------------------------------- slow path: radix select in a bin
-// More than CAND_MAX rows share the threshold bin (near-identical keys).  MSB-first
-// 8-bit radix select over the 64-bit key (orderable score : position) restricted to
-// that bin; reads scores and positions from memory on every pass.  Marks the
-// `need` largest in the evict bitmap.
-__device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const float *sc, const int32_t *pos,
-                                    uint32_t *evbits, int tb, uint32_t need)
-{
-    const int tid = threadIdx.x, lane = tid & 63;
-    uint64_t prefix = 0;
-    uint32_t rank = need;
-    int resolved = 0;
-    for (int pass = 0; pass < 8; ++pass) {
-        const int shift = 56 - 8 * pass;
-        for (int i = tid; i < 256; i += POST_THREADS) sh.radix_hist[i] = 0;
-        __syncthreads();
-        for (int i0 = 0; i0 < p.n; i0 += POST_THREADS) {
-            const int i = i0 + tid;
-            bool part = false;
-            uint32_t digit = 0;
-            if (i < p.n) {
-                const float s = sc[i];
-                const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
-                if (!exempt && score_bin(s) == tb) {
-                    const uint64_t key = ((uint64_t)orderable(s) << 32) | (uint32_t)pos[i];
-                    part = pass == 0 || (key >> (shift + 8)) == prefix;
-                    digit = (uint32_t)(key >> shift) & 255u;
-                }
-            }
-            const uint64_t active = __ballot(part);
-            if (active) {
-                const int leader = __ffsll((unsigned long long)active) - 1;
-                const uint32_t ld = __shfl(digit, leader);
-                const uint64_t same = __ballot(part && digit == ld);
-                if (lane == leader) atomicAdd(&sh.radix_hist[ld], (uint32_t)__popcll(same));
-                else if (part && digit != ld) atomicAdd(&sh.radix_hist[digit], 1u);
-            }
-        }
-        __syncthreads();
-        if (tid < 64) {
-            const uint32_t c0 = sh.radix_hist[4 * lane], c1 = sh.radix_hist[4 * lane + 1],
-                           c2 = sh.radix_hist[4 * lane + 2], c3 = sh.radix_hist[4 * lane + 3];
-            const uint32_t mine = c0 + c1 + c2 + c3;
-            uint32_t suf = mine;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t t = __shfl_down(suf, off);
-                if (lane + off < 64) suf += t;
-            }
-            const uint64_t reach = __ballot(suf >= rank);
-            const int owner = reach ? 63 - __clzll((unsigned long long)reach) : 0;
-            if (lane == owner) {
-                uint32_t above = suf - mine, bin, cnt;
-                if (above + c3 >= rank) { bin = 3; cnt = c3; }
-                else if ((above += c3) + c2 >= rank) { bin = 2; cnt = c2; }
-                else if ((above += c2) + c1 >= rank) { bin = 1; cnt = c1; }
-                else { above += c1; bin = 0; cnt = c0; }
-                sh.sel_bin = 4 * lane + bin;
-                sh.sel_rank = rank - above;
-                sh.sel_cnt = cnt;
-            }
-        }
-        __syncthreads();
-        prefix = (prefix << 8) | sh.sel_bin;
-        rank = sh.sel_rank;
-        resolved = 8 * (pass + 1);
-        const bool done = sh.sel_cnt == rank;
-        __syncthreads();
-        if (done) break;
-    }
-    for (int i = tid; i < p.n; i += POST_THREADS) {
-        const float s = sc[i];
-        const bool exempt = p.window_W > 0 && pos[i] >= p.window_pos_min;
-        if (!exempt && score_bin(s) == tb) {
-            const uint64_t key = ((uint64_t)orderable(s) << 32) | (uint32_t)pos[i];
-            if ((key >> (64 - resolved)) >= prefix) atomicOr(&evbits[i >> 5], 1u << (i & 31));
-        }
-    }
-    __syncthreads();
-}
-
-// ------------------------------------------------------------- select + compaction
-// `lists` holds three arrays of E row indices (evicted | holes | movers): in LDS when
-// they fit, else in the scratch buffer.
-// SPT: scores per thread the instantiation can hold (n <= SPT * POST_THREADS)
-template <int D, int SPT>
-__device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int32_t *lists, int bh)
-{
-    constexpr int UPR = D / 8;
-    // 16-byte units of the tail rows a thread keeps in registers (the large instantiation has none to spare)
-    constexpr int TAILU = SPT * POST_THREADS < MAX_CAP ? 8 : 0;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int E = p.n - p.N;
-    const float *sc = p.scores + (size_t)bh * p.cap;
-    int32_t *pos = p.pos + (size_t)bh * p.cap;
-    uint16_t *kb = p.k + (size_t)bh * p.cap * D;
-    uint16_t *vb = p.v + (size_t)bh * p.cap * D;
-
-    // ---- 0. every load that does not depend on the selection is issued here, so that the chain
-    // below costs one memory round trip now and one for the evicted rows later: the scores and
-    // positions of all rows, the running key sum, and (FILL layout) the K/V rows [N, n), the only
-    // ones that can move.
-    float sv[SPT];
-    int32_t sp[SPT];
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = k * POST_THREADS + tid;
-        sv[k] = 0.f;
-        sp[k] = 0;
-        if (k * POST_THREADS < p.n && i < p.n) {
-            sv[k] = sc[i];
-            sp[k] = pos[i];
-        }
-    }
-    const double ksum_old = tid < D ? p.ksum_next[(size_t)bh * D + tid] : 0.0;  // the sum step_main just wrote
-    const bool tail_regs = TAILU > 0 && p.layout == 1 && 2 * E * UPR <= TAILU * POST_THREADS;
-    u32x4 tailv[TAILU > 0 ? TAILU : 1];
-    if (tail_regs) {
-#pragma unroll
-        for (int q = 0; q < TAILU; ++q) {
-            const int w = q * POST_THREADS + tid;
-            tailv[q] = u32x4{0u, 0u, 0u, 0u};
-            if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
-                const int which = w >= E * UPR, rem = w - which * E * UPR;
-                tailv[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)(p.N + rem / UPR) * D + (rem % UPR) * 8);
-            }
-        }
-    }
-
-    // ---- 1. histogram of the non-exempt scores in LDS
-    const int nwords = (p.n + 31) / 32;
-    for (int i = tid; i < nwords; i += POST_THREADS) evbits[i] = 0;
-    for (int i = tid; i < HIST_BINS; i += POST_THREADS) sh.hist[i] = 0;
-    if (tid == 0) {
-        sh.ncand = 0;
-        sh.nev = 0;
-        sh.tb = 0;
-        sh.need = 0;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = k * POST_THREADS + tid;
-        if (k * POST_THREADS >= p.n) break;
-        if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) atomicAdd(&sh.hist[score_bin(sv[k])], 1u);
-    }
-    __syncthreads();
-
-    // ---- 2. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
-    uint32_t cnt[HIST_BINS / POST_THREADS];
-    uint32_t mine = 0;
-    const int top = HIST_BINS - 1 - (HIST_BINS / POST_THREADS) * tid;
-#pragma unroll
-    for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
-        cnt[j] = sh.hist[top - j];
-        mine += cnt[j];
-    }
-    uint32_t total;
-    uint32_t above = block_exclusive_scan(mine, sh.wave_tot, &total);
-    if (above < (uint32_t)E && above + mine >= (uint32_t)E) {
-#pragma unroll
-        for (int j = 0; j < HIST_BINS / POST_THREADS; ++j) {
-            if (above + cnt[j] >= (uint32_t)E) {
-                sh.tb = top - j;
-                sh.need = (uint32_t)E - above;
-                break;
-            }
-            above += cnt[j];
-        }
-    }
-    if (tid == 0 && total < (uint32_t)E) atomicOr(p.status, STATUS_SELECT_COUNT);  // cannot happen: E <= candidates
-    __syncthreads();
-    const int tb = sh.tb;
-    const uint32_t need = sh.need;
-
-    // above the bin -> evicted, inside it -> candidate for the exact ranking
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = k * POST_THREADS + tid;
-        if (k * POST_THREADS >= p.n) break;
-        // bin of the row, -1 if it cannot be evicted (exempt or past the end)
-        const int sb = (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) ? score_bin(sv[k]) : -1;
-        if (sb > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
-        else if (sb == tb) {
-            const uint32_t c = atomicAdd(&sh.ncand, 1u);
-            if (c < CAND_MAX) {
-                sh.cand_slot[c] = (uint32_t)i;
-                sh.cand_key[c] = orderable(sv[k]);
-                sh.cand_pos[c] = sp[k];
-            }
-        }
-    }
-    __syncthreads();
-    const uint32_t ncand = sh.ncand;
-
-    // ---- 3. exact ranking inside the bin by (score bits, position), largest first: a wave takes a
-    // candidate, its lanes compare it with 64 others at a time and count by ballot
-    if (ncand <= CAND_MAX) {
-        for (uint32_t c = wave; c < ncand; c += NWAVES) {   // uniform per wave
-            const uint32_t key = sh.cand_key[c];
-            const int32_t ps = sh.cand_pos[c];
-            uint32_t rank = 0;
-            for (uint32_t o0 = 0; o0 < ncand; o0 += 64) {
-                const uint32_t o = o0 + lane;
-                bool gt = false;
-                if (o < ncand) {
-                    const uint32_t ok = sh.cand_key[o];
-                    gt = (ok > key) || (ok == key && sh.cand_pos[o] > ps);
-                }
-                rank += (uint32_t)__popcll(__ballot(gt));
-            }
-            if (lane == 0 && rank < need) {
-                const uint32_t i = sh.cand_slot[c];
-                atomicOr(&evbits[i >> 5], 1u << (i & 31));
-            }
-        }
-        __syncthreads();
-    } else {
-        radix_select_in_bin(p, sh, sc, pos, evbits, tb, need);
-    }
-
-    // ---- 4. ordered lists: thread t owns bitmap word t = rows [32 t, 32 t + 32)
-    static_assert(MAX_CAP / 32 <= POST_THREADS, "one bitmap word per thread");
-    const int own0 = min(p.n, 32 * tid), own1 = min(p.n, own0 + 32);
-    const uint32_t valid = own1 - own0 == 32 ? 0xFFFFFFFFu : ((1u << (own1 - own0)) - 1u);
-    const uint32_t low = own0 + 32 <= p.N ? 0xFFFFFFFFu : (own0 >= p.N ? 0u : ((1u << (p.N - own0)) - 1u));  // rows < N
-    const uint32_t evw = tid < nwords ? (evbits[tid] & valid) : 0u;
-    const uint32_t holew = evw & low, movew = ~evw & ~low & valid;
-    uint64_t tot3;
-    const uint64_t ex3 = block_exclusive_scan64((uint64_t)__popc(evw) | ((uint64_t)__popc(holew) << 21) |
-                                                    ((uint64_t)__popc(movew) << 42),
-                                                sh.wave_tot64, &tot3);
-    constexpr uint64_t M21 = (1ull << 21) - 1;
-    uint32_t eb = (uint32_t)(ex3 & M21);
-    const uint32_t hm_h = (uint32_t)((ex3 >> 21) & M21), hm_m = (uint32_t)((ex3 >> 42) & M21);
-    const uint32_t tot_ev = (uint32_t)(tot3 & M21), nholes = (uint32_t)((tot3 >> 21) & M21),
-                   nmov = (uint32_t)((tot3 >> 42) & M21);
-    // an impossible count is reported and nothing is moved (keeps every index in range)
-    const bool sane = tot_ev == (uint32_t)E && nholes == nmov;
-    if (!sane) {
-        if (tid == 0) atomicOr(p.status, STATUS_SELECT_COUNT);
-        return;
-    }
-    // evicted rows | holes (evicted rows below N) | movers (kept rows from N on) | rank of tail row N + r
-    // among the movers (-1: evicted)
-    int32_t *evlist = lists, *holes = lists + E, *movers = lists + 2 * E, *mrank = lists + 3 * E;
-    const bool tail_par = E <= POST_THREADS && (nwords - (p.N >> 5)) <= TAIL_WORDS;
-    {
-        uint32_t hb = hm_h, mb = hm_m, e2 = eb;
-        for (uint32_t w = evw; w; w &= w - 1) {
-            const int i = own0 + __ffs(w) - 1;
-            evlist[e2++] = i;
-            if (i < p.N) holes[hb++] = i;
-            else mrank[i - p.N] = -1;
-        }
-        // The tail rows [N, n) sit in a few words that are mostly movers: those words and their
-        // mover counts before them go to LDS, and one thread per tail row finishes below.
-        const int tw = tid - (p.N >> 5);
-        if (tail_par) {
-            if (tw >= 0 && tid < nwords) {
-                sh.tail_word[tw] = movew;
-                sh.tail_base[tw] = mb;
-            }
-        } else {
-            for (uint32_t w = movew; w; w &= w - 1) {
-                const int i = own0 + __ffs(w) - 1;
-                mrank[i - p.N] = (int32_t)mb;
-                movers[mb++] = i;
-            }
-        }
-    }
-    __syncthreads();
-    if (tail_par && tid < E) {
-        const int row = p.N + tid, tw = (row >> 5) - (p.N >> 5), bit = row & 31;
-        const uint32_t mw = sh.tail_word[tw];
-        if ((mw >> bit) & 1u) {
-            const uint32_t r = sh.tail_base[tw] + (uint32_t)__popc(mw & ((1u << bit) - 1u));
-            mrank[tid] = (int32_t)r;
-            movers[r] = row;
-        }   // an evicted tail row got its -1 above
-    }
-    // (the ranks are first read after the barrier inside step 5)
-
-    // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
-    // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
-    {
-        constexpr int RPW = 64 / UPR;
-        const int u = lane % UPR, rl = lane / UPR;
-        double acc[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-        for (int rb = wave * RPW; rb < E; rb += NWAVES * RPW) {  // uniform per wave
-            const int r = rb + rl;
-            double x[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = 0.0;
-            if (r < E) {
-                const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)evlist[r] * D + u * 8);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    x[2 * i] = bf16_lo(w[i]);
-                    x[2 * i + 1] = bf16_hi(w[i]);
-                }
-            }
-            double inv = 1.0;
-            if (p.anchor_mode == 1) {  // unit key: x / |k|
-                double k2 = 0.0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
-                k2 = row_allreduce_f64<UPR>(k2);
-                const double nk = sqrt(k2);
-                inv = nk > 0.0 ? 1.0 / nk : 0.0;
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
-        }
-        // fold the rows of the wave (lanes with equal u), then the waves
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-#pragma unroll
-            for (int off = UPR; off < 64; off <<= 1) acc[i] += shfl_xor_f64(acc[i], off);
-        }
-        if (rl == 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sh.colsum[wave][u * 8 + i] = acc[i];
-        }
-        __syncthreads();   // also: every evicted row has been read before the compaction overwrites it
-        if (tid < D) {
-            double s = 0.0;
-#pragma unroll
-            for (int w = 0; w < NWAVES; ++w) s += sh.colsum[w][tid];
-            p.ksum_next[(size_t)bh * D + tid] = ksum_old - s;
-        }
-    }
-
-    // ---- 6. compaction
-    if (p.layout == 1) {
-        // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N).  Rows from N
-        // on belong to this step's block: row i holds token pos0 + (i - len).
-        if (tail_regs) {
-#pragma unroll
-            for (int q = 0; q < TAILU; ++q) {
-                const int w = q * POST_THREADS + tid;
-                if (q * POST_THREADS < 2 * E * UPR && w < 2 * E * UPR) {
-                    const int which = w >= E * UPR, rem = w - which * E * UPR;
-                    const int mr = mrank[rem / UPR];
-                    if (mr >= 0)
-                        *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)holes[mr] * D + (rem % UPR) * 8) = tailv[q];
-                }
-            }
-        } else {
-            const int nmove = (int)nholes;
-            for (int w = tid; w < nmove * UPR * 2; w += POST_THREADS) {
-                const int r = w / (UPR * 2), rem = w % (UPR * 2);
-                const int u = rem % UPR;
-                uint16_t *base_ptr = rem < UPR ? kb : vb;
-                const u32x4 val = *reinterpret_cast<const u32x4 *>(base_ptr + (size_t)movers[r] * D + u * 8);
-                *reinterpret_cast<u32x4 *>(base_ptr + (size_t)holes[r] * D + u * 8) = val;
-            }
-        }
-        for (int r = tid; r < (int)nholes; r += POST_THREADS) pos[holes[r]] = p.pos0 + (movers[r] - p.len);
-    } else {
-        // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here
-        // (all reads precede all writes), the K/V rows by compact_ordered_kernel.
-        int32_t mypos[32];
-        int32_t *dst = p.dstmap + (size_t)bh * p.cap;
-        for (int i = own0, j = 0; i < own1; ++i, ++j) mypos[j] = pos[i];
-        __syncthreads();
-        for (int i = own0, j = 0; i < own1; ++i, ++j) {
-            const bool ev = (evw >> j) & 1u;
-            if (ev) {
-                dst[i] = -1;
-                ++eb;
-            } else {
-                dst[i] = i - (int)eb;
-                pos[i - (int)eb] = mypos[j];
-            }
-        }
-    }
-}
 
 // ------------------------------------------------------------------------ merge
 template <int D>
@@ -672,7 +193,7 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
     uint32_t *evbits = reinterpret_cast<uint32_t *>(smem_raw);
     int32_t *lists = p.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (p.n + 31) / 32)
                                     : p.lists + (size_t)bh * 4 * p.B;
-    select_and_compact<D, SPT>(p, sh, evbits, lists, bh);
+    select_and_compact<D, SPT, POST_THREADS>(p, sh, evbits, lists, bh);
 }
 
 // ------------------------------------------------------------- ordered compaction

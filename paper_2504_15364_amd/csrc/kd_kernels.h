@@ -62,6 +62,10 @@ struct StepParams {
 
 hipError_t configure_kernels();      // one-time function attributes (dynamic LDS sizes)
 hipError_t launch_step_main(const StepParams &p, hipStream_t s);
+// step_main of `p` whose first workgroups run the selection and compaction `cy` describes (the
+// parameters of an earlier step of another cache, FILL layout); can_carry says whether the pair fits
+bool can_carry(const StepParams &p, const StepParams &cy);
+hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hipStream_t s);
 hipError_t launch_step_score(const StepParams &p, hipStream_t s);
 hipError_t launch_step_post(const StepParams &p, hipStream_t s);
 // flags: [BH][ceil(cap / ORD_ROWS)] int32 in zero-initialised device memory; epoch: a value no earlier launch used

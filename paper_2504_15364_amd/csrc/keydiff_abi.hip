@@ -104,6 +104,9 @@ struct keydiff_cache {
     int64_t next_pos;
     int32_t epoch;        // launches of the ordered compaction so far (its flags compare against it)
     int kpar;             // which half of the key-sum double buffer holds the current sum
+    bool pending;         // a deferred eviction (selection + compaction) has not been enqueued yet
+    kd::StepParams pend;  // ... the parameters of the step it belongs to
+    hipStream_t pend_stream;
     bool profiling;
     std::vector<ProfEvent> events;
     std::vector<hipEvent_t> pool;
@@ -192,7 +195,8 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
 }
 
 // M tiling (GQA-packed rows per KV head) and the number of key splits that fills the chip
-void plan_attention(const keydiff_cache *c, kd::StepParams &p)
+// `reserved`: compute units to leave to the workgroups of a carried selection
+void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
 {
     const int BH = p.batch * p.hkv;
     const int Mtot = p.G * p.Bt;
@@ -202,6 +206,10 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p)
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
     const int target = p.NW == 8 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
     int splits = (target + BH * p.mtiles - 1) / (BH * p.mtiles);
+    // one workgroup of 8 waves fills a compute unit: with passengers on board the attention takes
+    // what is left of the chip in a single round
+    if (reserved > 0 && p.NW == 8 && splits * BH * p.mtiles + reserved > target)
+        splits = (target - reserved) / (BH * p.mtiles);
     if (splits > p.ntiles) splits = p.ntiles;
     if (splits < 1) splits = 1;
     // partial rows must fit the scratch sized at init
@@ -212,6 +220,99 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p)
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+// the pending selection and compaction of `c` as a launch of its own
+int finish_pending(keydiff_cache *c, hipStream_t s)
+{
+    if (!c->pending) return KEYDIFF_OK;
+    kd::StepParams p = c->pend;
+    p.merge_wgs = 0;
+    ProfScope ps(c, KEYDIFF_K_POST, s);
+    KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (deferred selection)");
+    c->pending = false;
+    return KEYDIFF_OK;
+}
+
+int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v_new, int32_t Bt, int64_t pos0,
+               void *out, float *scores_out, bool defer, keydiff_cache *carry, hipStream_t s)
+{
+    if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
+        return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
+    if (Bt < 1 || Bt > c->cfg.block_B) return fail(KEYDIFF_ESHAPE, "Bt must lie in [1, block_B], got %d", Bt);
+    if (pos0 < 0 || pos0 + Bt > 0x7fffffffLL) return fail(KEYDIFF_ESHAPE, "positions must fit in int32");
+    if (carry == c) return fail(KEYDIFF_EINVAL, "a cache cannot carry its own eviction");
+    const keydiff_config_t &cf = c->cfg;
+    const int len = c->len, n = len + Bt, N = cf.budget_N;
+    const bool contiguous = c->contiguous && (c->next_pos < 0 || c->next_pos == pos0);
+    if (cf.window_W > 0 && n > N && !contiguous)
+        return fail(KEYDIFF_ESTATE, "the sliding window needs consecutive token positions across calls");
+    if (int rc = finish_pending(c, s)) return rc;   // this step reads the compacted cache
+
+    const bool evict = n > N;
+    kd::StepParams p = base_params(c, n);
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.out = static_cast<uint16_t *>(out);
+    p.scores_out = scores_out;
+    p.Bt = Bt;
+    p.len = len;
+    p.pos0 = (int32_t)pos0;
+    p.do_evict = evict;
+    p.do_score = evict || scores_out != nullptr;
+    if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
+
+    // a passenger rides only if the attention still fits the chip in one round beside it
+    bool riding = false;
+    if (carry && carry->pending) {
+        if (carry->pend_stream == s) {
+            const int seats = carry->cfg.batch * carry->cfg.n_kv_heads;
+            plan_attention(c, p, seats);
+            riding = kd::can_carry(p, carry->pend) &&
+                     p.batch * p.hkv * p.mtiles * p.splits + seats <= kTargetWorkgroups / 2;
+        }
+        if (!riding)
+            if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
+    }
+    if (!riding) plan_attention(c, p);
+    {
+        ProfScope ps(c, KEYDIFF_K_MAIN, s);
+        if (riding) {
+            KD_LAUNCH(kd::launch_step_main_carry(p, carry->pend, s), "step_main kernel (with carried selection)");
+            carry->pending = false;
+        } else {
+            KD_LAUNCH(kd::launch_step_main(p, s), "step_main kernel");
+        }
+    }
+    const bool deferred = defer && evict && cf.layout == KEYDIFF_LAYOUT_FILL;
+    if (deferred) {
+        if (p.merge_wgs > 0) {
+            kd::StepParams pm = p;
+            pm.do_evict = 0;   // the merge half of step_post only
+            ProfScope ps(c, KEYDIFF_K_POST, s);
+            KD_LAUNCH(kd::launch_step_post(pm, s), "step_post kernel (merge)");
+        }
+        c->pending = true;
+        c->pend = p;
+        c->pend_stream = s;
+    } else if (evict || p.merge_wgs > 0) {
+        ProfScope ps(c, KEYDIFF_K_POST, s);
+        KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
+    }
+    if (evict && cf.layout == KEYDIFF_LAYOUT_ORDERED) {
+        ProfScope ps(c, KEYDIFF_K_COMPACT, s);
+        c->epoch = c->epoch == 0x7fffffff ? 1 : c->epoch + 1;
+        KD_LAUNCH(kd::launch_compact_ordered(p, reinterpret_cast<int32_t *>(c->meta + c->L.off_oflags), c->epoch, s),
+                  "ordered compaction kernel");
+    }
+    if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
+    c->kpar ^= 1;   // step_main wrote the new key sum into the other half
+    c->len = evict ? N : n;
+    c->contiguous = contiguous;
+    c->next_pos = pos0 + Bt;
+    return KEYDIFF_OK;
+}
 
 }  // namespace
 
@@ -258,6 +359,8 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->profiling = false;
     c->kpar = 0;
     c->epoch = 0;
+    c->pending = false;
+    c->pend_stream = nullptr;
     static hipError_t configured = kd::configure_kernels();  // once per process
     hipError_t e = configured;
     if (e == hipSuccess)
@@ -274,6 +377,7 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
 void keydiff_destroy_cache(keydiff_cache_t *c)
 {
     if (!c) return;
+    (void)finish_pending(c, c->pend_stream);   // the caller's buffers end up compacted
     for (auto &ev : c->events) {
         (void)hipEventDestroy(ev.a);
         (void)hipEventDestroy(ev.b);
@@ -292,55 +396,19 @@ int keydiff_cache_len(const keydiff_cache_t *c, int32_t *len)
 int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
                           int64_t pos0, void *out, float *scores_out, void *stream)
 {
-    if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
-    if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
-        return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
-    if (Bt < 1 || Bt > c->cfg.block_B) return fail(KEYDIFF_ESHAPE, "Bt must lie in [1, block_B], got %d", Bt);
-    if (pos0 < 0 || pos0 + Bt > 0x7fffffffLL) return fail(KEYDIFF_ESHAPE, "positions must fit in int32");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const keydiff_config_t &cf = c->cfg;
-    const int BH = cf.batch * cf.n_kv_heads, D = cf.head_dim;
-    const int len = c->len, n = len + Bt, N = cf.budget_N;
-    const bool contiguous = c->contiguous && (c->next_pos < 0 || c->next_pos == pos0);
-    if (cf.window_W > 0 && n > N && !contiguous)
-        return fail(KEYDIFF_ESTATE, "the sliding window needs consecutive token positions across calls");
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, static_cast<hipStream_t>(stream));
+}
 
-    const bool evict = n > N;
-    kd::StepParams p = base_params(c, n);
-    p.q = static_cast<const uint16_t *>(q);
-    p.k_new = static_cast<const uint16_t *>(k_new);
-    p.v_new = static_cast<const uint16_t *>(v_new);
-    p.out = static_cast<uint16_t *>(out);
-    p.scores_out = scores_out;
-    p.Bt = Bt;
-    p.len = len;
-    p.pos0 = (int32_t)pos0;
-    p.do_evict = evict;
-    p.do_score = evict || scores_out != nullptr;
-    if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
-    plan_attention(c, p);
-    (void)BH;
-    (void)D;
-    {
-        ProfScope ps(c, KEYDIFF_K_MAIN, s);
-        KD_LAUNCH(kd::launch_step_main(p, s), "step_main kernel");
-    }
-    if (evict || p.merge_wgs > 0) {
-        ProfScope ps(c, KEYDIFF_K_POST, s);
-        KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
-    }
-    if (evict && cf.layout == KEYDIFF_LAYOUT_ORDERED) {
-        ProfScope ps(c, KEYDIFF_K_COMPACT, s);
-        c->epoch = c->epoch == 0x7fffffff ? 1 : c->epoch + 1;
-        KD_LAUNCH(kd::launch_compact_ordered(p, reinterpret_cast<int32_t *>(c->meta + c->L.off_oflags), c->epoch, s),
-                  "ordered compaction kernel");
-    }
-    if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
-    c->kpar ^= 1;   // step_main wrote the new key sum into the other half
-    c->len = evict ? N : n;
-    c->contiguous = contiguous;
-    c->next_pos = pos0 + Bt;
-    return KEYDIFF_OK;
+int keydiff_prefill_block_deferred(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
+                                   int64_t pos0, void *out, keydiff_cache_t *carry, void *stream)
+{
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, nullptr, true, carry, static_cast<hipStream_t>(stream));
+}
+
+int keydiff_finish(keydiff_cache_t *c, void *stream)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    return finish_pending(c, static_cast<hipStream_t>(stream));
 }
 
 int keydiff_decode_step(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int64_t pos,
@@ -354,8 +422,9 @@ int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
     if (!cc) return fail(KEYDIFF_EINVAL, "null pointer");
     if (cc->len == 0) return fail(KEYDIFF_ESTATE, "the cache is empty");
     if (!scores_out) return fail(KEYDIFF_EINVAL, "null pointer");
-    keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch and profiling events only
+    keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch, profiling events, a pending eviction
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (int rc = finish_pending(c, s)) return rc;
     kd::StepParams p = base_params(c, c->len);
     p.scores_out = scores_out;
     p.do_score = 1;
@@ -369,6 +438,7 @@ int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
 int keydiff_cache_positions(const keydiff_cache_t *c, int32_t *pos_out, void *stream)
 {
     if (!c || !pos_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (int rc = finish_pending(const_cast<keydiff_cache *>(c), static_cast<hipStream_t>(stream))) return rc;
     KD_LAUNCH(kd::launch_load_pos(reinterpret_cast<const int32_t *>(c->meta + c->L.off_pos), pos_out,
                                   c->cfg.batch * c->cfg.n_kv_heads, c->L.cap, c->len, 0,
                                   static_cast<hipStream_t>(stream)),
@@ -384,6 +454,7 @@ int keydiff_cache_load(keydiff_cache_t *c, const void *k, const void *v, const i
     if (len > 0 && (!k || !v || !pos)) return fail(KEYDIFF_EINVAL, "null pointer");
     if (len > 0 && (misaligned(k) || misaligned(v))) return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (int rc = finish_pending(c, s)) return rc;
     const int BH = c->cfg.batch * c->cfg.n_kv_heads, D = c->cfg.head_dim;
     KD_LAUNCH(kd::launch_load_rows(static_cast<const uint16_t *>(k), c->k, BH, c->L.cap, D, len, s), "cache load");
     KD_LAUNCH(kd::launch_load_rows(static_cast<const uint16_t *>(v), c->v, BH, c->L.cap, D, len, s), "cache load");
@@ -405,6 +476,7 @@ int keydiff_cache_status(const keydiff_cache_t *c, int32_t *status_out, void *st
 {
     if (!c || !status_out) return fail(KEYDIFF_EINVAL, "null pointer");
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (int rc = finish_pending(const_cast<keydiff_cache *>(c), s)) return rc;
     hipError_t e = hipMemcpyAsync(status_out, c->meta + c->L.off_status, 4, hipMemcpyDeviceToHost, s);
     if (e != hipSuccess) return hip_fail(e, "status copy");
     e = hipStreamSynchronize(s);

@@ -234,6 +234,100 @@ def test_largest_capacity():
     cache.close()
 
 
+
+# ---- deferred eviction: the selection of one layer rides in the attention launch of the next ----
+def run_layers_deferred(w, N, B, nlayers, seeds, check_every, expect_ride, **kw):
+    """Layers run in turn on every block, each carrying the pending eviction of the one before it
+    (the first carries the last one's from the previous block).  Attention is checked on every
+    call; the cache states every `check_every` blocks (reading a state finishes its pending
+    eviction in a launch of its own) and at the end."""
+    layers = [make_pair(w, N, B, **kw) for _ in range(nlayers)]
+    datas = [make_layer(w, seed=s) for s in seeds]
+    for c, _ in layers:
+        c.profile_enable(True)
+    evicting = 0
+    for bi, steps in enumerate(zip(*(blocks(d, B) for d in datas))):
+        for li, (t, Bt, q, k, v) in enumerate(steps):
+            cache, oc = layers[li]
+            carry = layers[li - 1][0] if nlayers > 1 else None
+            out = cache.prefill_block_deferred(to_dev(q), to_dev(k), to_dev(v), t, carry=carry)
+            ref, _, ev = oc.prefill_block(q, k, v, t)
+            err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+            assert err <= ATTN_ATOL, f"attention error {err}, layer {li}, block at token {t}"
+            evicting += int(ev > 0 and li == 0)
+        if check_every and bi % check_every == check_every - 1:
+            for li, (cache, oc) in enumerate(layers):
+                check_state(cache, oc, f"layer {li} after block {bi}")
+    for li, (cache, oc) in enumerate(layers):
+        check_state(cache, oc, f"layer {li} at the end")
+        assert cache.status() == 0
+    counts = [c.profile_read() for c, _ in layers]
+    for c, _ in layers:
+        c.close()
+    if expect_ride is not None:
+        # step_post launches of a layer: one merge per block step with several key splits, plus one
+        # per eviction that did NOT ride (finished in a launch of its own)
+        merges = [cnt["step_main"][1] for cnt in counts]
+        posts = [cnt["step_post"][1] for cnt in counts]
+        alone = sum(p - m for p, m in zip(posts, merges))
+        if expect_ride:
+            # only what the state checks and the end of the run forced out
+            forced = nlayers * ((len(list(blocks(datas[0], B))) // check_every if check_every else 0) + 1)
+            assert 0 <= alone <= forced, (posts, merges, forced)
+            assert evicting * nlayers - alone > 0, "no eviction rode along"
+        else:
+            assert alone >= evicting * nlayers - nlayers, (posts, merges)
+
+
+def test_deferred_eviction_rides_the_next_layers_attention():
+    # G * B = 512 rows per KV head: 8-wave workgroups, several key splits, the carrying kernel
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1536)
+    run_layers_deferred(w, 768, 128, 3, seeds=(41, 42, 43), check_every=0, expect_ride=True, layout=kd.LAYOUT_FILL)
+
+
+def test_deferred_eviction_with_states_read_in_between():
+    # reading a cache finishes its eviction alone: riding and stand-alone finishes interleave
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1280)
+    run_layers_deferred(w, 640, 128, 2, seeds=(44, 45), check_every=3, expect_ride=True, layout=kd.LAYOUT_FILL,
+                        anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY, window_W=64)
+
+
+def test_deferred_eviction_where_nothing_can_ride():
+    # 4-wave workgroups (G * B = 144 rows) have no carrying variant, and the ORDERED layout does not
+    # defer at all: both must give the plain call's results
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=500)
+    run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=0, expect_ride=False, layout=kd.LAYOUT_FILL)
+    run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=2, expect_ride=None, layout=kd.LAYOUT_ORDERED)
+
+
+def test_deferred_eviction_single_cache_and_other_entry_points():
+    # no carrier: finish(), scores(), a plain block step and destroy each complete a pending eviction
+    w = get_config("toy")
+    N, B = w.budget_N, w.block_B
+    data = make_layer(w, seed=48)
+    cache, oc = make_pair(w, N, B, layout=kd.LAYOUT_FILL)
+    for i, (t, Bt, q, k, v) in enumerate(blocks(data, B)):
+        if i % 2 == 0:
+            out = cache.prefill_block_deferred(to_dev(q), to_dev(k), to_dev(v), t)
+        else:
+            out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)   # finishes the pending one first
+        ref, _, ev = oc.prefill_block(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
+        if i % 4 == 0:
+            cache.finish()
+            cache.finish()   # nothing pending: a no-op
+        if i % 4 == 2 and ev > 0:
+            sc = cache.scores().cpu().numpy()
+            osc = oc.scores()
+            order = np.argsort(cache.positions().cpu().numpy(), axis=-1, kind="stable")
+            assert np.allclose(np.take_along_axis(sc, order, axis=-1), osc, rtol=SCORE_RTOL, atol=SCORE_ATOL)
+        check_state(cache, oc, f"block {i}")
+    with pytest.raises(kd.KeyDiffError):
+        cache.prefill_block_deferred(to_dev(q), to_dev(k), to_dev(v), t + Bt, carry=cache)
+    assert cache.status() == 0
+    cache.close()
+
+
 def test_zero_key_and_tiny_keys_hit_the_eps_clamp():
     hq, hkv, d, N, B = 2, 1, 64, 40, 16
     w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=64)
