@@ -130,8 +130,9 @@ KEYDIFF_API int keydiff_prefill_block(keydiff_cache_t *cache, const void *q, con
  * before it), so after the call `carry` has none.  Until its eviction is enqueued the rows of
  * `cache` are the n = len + Bt rows before compaction and its scratch buffer is in use: a
  * cache used this way needs a scratch buffer of its own.  The ORDERED layout does not defer:
- * there the call behaves like keydiff_prefill_block.  The retained set, the scores and `out`
- * are those of keydiff_prefill_block bit for bit.                                          */
+ * there the call behaves like keydiff_prefill_block.  The scores and the retained set are those
+ * of keydiff_prefill_block bit for bit; `out` may differ in the last bf16 bit, because the
+ * keys are cut into a different number of ranges when passengers take part of the chip.    */
 KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const void *q, const void *k_new,
                                    const void *v_new, int32_t Bt, int64_t pos0, void *out,
                                    keydiff_cache_t *carry, void *stream);

@@ -136,8 +136,17 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     const int sp = id / p.mtiles;
     const int b = bh / p.hkv, kvh = bh % p.hkv;
     const int Mtot = p.G * p.Bt;
-    const int t0 = (int)(((long)sp * p.ntiles) / p.splits);
-    const int t1 = (int)(((long)(sp + 1) * p.ntiles) / p.splits);
+    // Key range of this split.  The tiles that take rows of the block (causal mask, a second source,
+    // decisions per copy) cost more than a plain tile of cached keys: the ranges are balanced with
+    // such a tile counted as edge_cost plain ones.
+    const int tplain = min(p.ntiles, p.len / TILE_KEYS);
+    const int ctotal = tplain + (p.ntiles - tplain) * p.edge_cost;
+    auto tile_at = [&](int i) {   // first tile of split i
+        const int c = (int)(((long)i * ctotal) / p.splits);
+        return c <= tplain ? c : tplain + (c - tplain) / p.edge_cost;
+    };
+    const int t0 = tile_at(sp);
+    const int t1 = sp + 1 == p.splits ? p.ntiles : tile_at(sp + 1);
     const int ntl = t1 - t0;
 
     const uint16_t *kcache = p.k + (size_t)bh * p.cap * D;

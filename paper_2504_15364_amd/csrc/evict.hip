@@ -18,6 +18,7 @@
 namespace kd {
 
 constexpr int SCORE_WAVES = SCORE_THREADS / 64;
+constexpr int MERGE_THREADS = 256;   // workgroup size of the stand-alone merge
 
 
 // ------------------------------------------------------------------------ scores
@@ -118,18 +119,11 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     const int d4 = (int)(gid % (D / 4));
     const size_t row = gid / (D / 4);
     if (row >= rows) return;
-    // the loads of a batch of splits are issued together: a serial chain would cost a memory
-    // round trip per split
-    constexpr int MB = 8;
+    // One memory round trip: the (max, sum) pairs and the partial rows of a batch of splits are
+    // requested together; only with more splits than a batch holds does a second batch follow, and
+    // the running result is then rescaled to the larger reference (as inside the attention).
+    constexpr int MB = 16;
     float mx = -INFINITY;
-    for (int s0 = 0; s0 < p.splits; s0 += MB) {
-        float2 ml[MB];
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-            ml[i] = s0 + i < p.splits ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
-#pragma unroll
-        for (int i = 0; i < MB; ++i) mx = fmaxf(mx, ml[i].x);
-    }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float L = 0.f;
     for (int s0 = 0; s0 < p.splits; s0 += MB) {
@@ -141,6 +135,18 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
             const f16x4 zero = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
             ml[i] = live ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
             o[i] = live ? *reinterpret_cast<const f16x4 *>(p.part_o + ((size_t)(s0 + i) * rows + row) * D + 4 * d4) : zero;
+        }
+        float bm = ml[0].x;
+#pragma unroll
+        for (int i = 1; i < MB; ++i) bm = fmaxf(bm, ml[i].x);
+        if (bm > mx) {
+            const float down = mx == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mx - bm);
+            acc.x *= down;
+            acc.y *= down;
+            acc.z *= down;
+            acc.w *= down;
+            L *= down;
+            mx = bm;
         }
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
@@ -163,6 +169,14 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     o[2] = (__bf16)(acc.z * inv);
     o[3] = (__bf16)(acc.w * inv);
     *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
+}
+
+// The merge as a kernel of its own (a step whose eviction is deferred has nothing else to run
+// here): small workgroups, so that the rows spread over every compute unit.
+template <int D>
+__global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(StepParams p)
+{
+    merge_rows<D>(p, (size_t)blockIdx.x * MERGE_THREADS + threadIdx.x);
 }
 
 // step_score: every workgroup scores SCORE_ROWS rows of one head.  The launch boundary after it
@@ -390,6 +404,14 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
 {
     const int grid = (p.do_evict ? p.batch * p.hkv : 0) + p.merge_wgs;
     if (grid == 0) return hipSuccess;
+    if (!p.do_evict) {   // merge only
+        const size_t threads = (size_t)p.batch * p.hkv * p.G * p.Bt * (p.D / 4);
+        const int mgrid = (int)((threads + MERGE_THREADS - 1) / MERGE_THREADS);
+        if (p.D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);
+        else if (p.D == 64) hipLaunchKernelGGL((merge_kernel<64>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     const size_t lds = post_lds_bytes(p.n, p.N);
     const bool small = p.n <= SPT_SMALL * POST_THREADS;
     if (p.D == 128 && small) hipLaunchKernelGGL((step_post_kernel<128, SPT_SMALL>), dim3(grid), dim3(POST_THREADS), lds, s, p);

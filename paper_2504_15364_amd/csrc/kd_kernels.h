@@ -50,6 +50,8 @@ struct StepParams {
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
+    int edge_cost;                   // weight (in plain tiles, >= 1) of a tile holding rows of the block when
+                                     // the key tiles are divided over the splits
     int score_chunks;                // step_score workgroups per head
     int lists_in_lds;                // selection lists live in LDS (else in `lists`)
     int merge_wgs;                   // merge workgroups in step_post (0 when splits == 1)

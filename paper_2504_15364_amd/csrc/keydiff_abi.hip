@@ -183,6 +183,7 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.B = cf.block_B;
     p.cap = c->L.cap;
     p.splits = 1;
+    p.edge_cost = 1;
     p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
     if (p.score_chunks < 1) p.score_chunks = 1;
     p.lists_in_lds = kd::lists_fit_lds(n, cf.budget_N) ? 1 : 0;
@@ -215,6 +216,16 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     // partial rows must fit the scratch sized at init
     while (splits > 1 && (long)splits * BH * Mtot > c->L.max_part_rows) --splits;
     p.splits = splits;
+    // a tile with rows of the block counts as up to three plain ones when the tiles are dealt out
+    // (measured: the steps around such tiles take about that much longer); every split must still
+    // span at least one tile, which a span of 2 * edge_cost cost units guarantees
+    const int tplain = p.len / kd::TILE_KEYS < p.ntiles ? p.len / kd::TILE_KEYS : p.ntiles;
+    p.edge_cost = 1;
+    for (int e = 3; e > 1; --e)
+        if ((tplain + e * (p.ntiles - tplain)) / splits >= 2 * e) {
+            p.edge_cost = e;
+            break;
+        }
     const size_t merge_threads = (size_t)BH * Mtot * (p.D / 4);
     p.merge_wgs = splits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
