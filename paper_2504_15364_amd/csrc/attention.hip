@@ -419,39 +419,45 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ap + 8 * ROWB));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // The 32 NQ exponentials a lane owes per tile are cut into 8 NQ slices of 4: slice i covers block
-    // (i / 2) % NQ, 16-key chunk i / (2 NQ), accumulator elements 8 (chunk % 2) + 4 (i % 2) .. + 3 of
-    // key group chunk / 2.  A slice goes through three steps one pipeline step apart, so that no
-    // instruction waits for the one before it: F scale and shift, E exponential, C round to bf16
-    // (the B operand of the second MFMA) and add the rounded weights to the row sum.
-    auto slice_F = [&](const f32x16 (&s)[NQ][2], int i, float (&arg)[4]) {
-        const int a = (i >> 1) % NQ, kc = i / (2 * NQ), kg = kc >> 1, cc = kc & 1, hf = i & 1;
+    // The 32 NQ exponentials a lane owes per tile are cut into 32 NQ / SL slices of SL: slice i covers
+    // block (i / (8 / SL)) % NQ, 16-key chunk kc = i / (8 NQ / SL), accumulator elements
+    // 8 (kc % 2) + SL (i % (8 / SL)) .. + SL - 1 of key group kc / 2.  A slice goes through three steps
+    // one pipeline step apart, so that no instruction waits for the one before it: F scale and shift,
+    // E exponential, C round to bf16 (the B operand of the second MFMA) and add the rounded weights to
+    // the row sum.  Small slices spread the vector work evenly between the MFMAs: a wave gets the
+    // matrix pipe every other MFMA slot, and what does not fit between two of its MFMAs delays the next.
+    constexpr int SL = 2;              // exponentials per slice (2 or 4)
+    constexpr int SPC = 8 / SL;        // slices per 16-key chunk and query block
+    auto slice_F = [&](const f32x16 (&s)[NQ][2], int i, float (&arg)[SL]) {
+        const int a = (i / SPC) % NQ, kc = i / (SPC * NQ), kg = kc >> 1, cc = kc & 1, part = i % SPC;
         const float nmuse = mref[a] == -INFINITY ? 0.f : -mref[a];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            arg[r] = __builtin_fmaf(s[a][kg][8 * cc + 4 * hf + r], p.scale_log2e, nmuse);
+        for (int r = 0; r < SL; ++r) {
+            arg[r] = __builtin_fmaf(s[a][kg][8 * cc + SL * part + r], p.scale_log2e, nmuse);
             asm volatile("" : "+v"(arg[r]));   // computed here, not where the optimiser finds its use
         }
     };
-    auto slice_E = [&](const float (&arg)[4], float (&ex)[4]) {
+    auto slice_E = [&](const float (&arg)[SL], float (&ex)[SL]) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < SL; ++r) {
             ex[r] = __builtin_amdgcn_exp2f(arg[r]);
             asm volatile("" : "+v"(ex[r]));
         }
     };
-    auto slice_C = [&](const float (&ex)[4], int i, bf16x8 (&pk)[NQ][4]) {
-        const int a = (i >> 1) % NQ, kc = i / (2 * NQ), hf = i & 1;
+    auto slice_C = [&](const float (&ex)[SL], int i, bf16x8 (&pk)[NQ][4]) {
+        const int a = (i / SPC) % NQ, kc = i / (SPC * NQ), part = i % SPC;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < SL / 2; ++r) {
+            const int e0 = SL * part + 2 * r;   // element pair inside the 8 of this lane's chunk
             bf16x2 pr;
             pr[0] = (__bf16)ex[2 * r];
             pr[1] = (__bf16)ex[2 * r + 1];
-            pk[a][kc][4 * hf + 2 * r] = pr[0];
-            pk[a][kc][4 * hf + 2 * r + 1] = pr[1];
+            pk[a][kc][e0] = pr[0];
+            pk[a][kc][e0 + 1] = pr[1];
             const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-            lrun[a][r] = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun[a][r], false);
-            asm volatile("" : "+v"(lrun[a][r]));
+            const int chain = (e0 >> 1) & 1;    // the row sum runs in two chains
+            lrun[a][chain] = __builtin_amdgcn_fdot2_f32_bf16(pr, one, lrun[a][chain], false);
+            asm volatile("" : "+v"(lrun[a][chain]));
         }
     };
 
@@ -648,7 +654,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     //   then the cosine score of tile t's rows if this workgroup owns them.
     // The scheduling barriers pin that order.  Tiles t + 2 and t + 3 are in flight meanwhile.
     // COPY: 0 no tile left to fetch, 1 the tile to fetch lies entirely in the cache, 2 decide per copy
-    auto step = [&](int t, auto next_tag, auto masked_tag, auto copy_tag) {
+    auto step = [&](int t, f32x16 (&sc)[NQ][2], f32x16 (&sn)[NQ][2], auto next_tag, auto masked_tag, auto copy_tag) {
         constexpr bool NEXT = decltype(next_tag)::value, MASKED = decltype(masked_tag)::value;
         constexpr int COPY = decltype(copy_tag)::value;
         constexpr int NA = 2 * NC, NB = 4 * NDB;
@@ -656,23 +662,13 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         // The exponential slices are spread evenly over stage A and the first half of stage B (whose
         // second half multiplies with the weights computed last): group g runs in slot g SLOTS / NG,
         // slots [0, NA) being the steps of stage A and [NA, SLOTS) steps of stage B.
-        constexpr int NS = 8 * NQ;                 // exponential slices per tile
+        constexpr int NS = 32 * NQ / SL;           // exponential slices per tile
         constexpr int SLOTS = NA + NB / 2;
         constexpr int SPG = NS > SLOTS ? 2 : 1;    // slices per group
         constexpr int NG = NS / SPG;
         auto slot_of = [](int g) { return g * SLOTS / NG; };
-        // the max scan of stage B (16 / NB accumulator elements per step) overwrites tile t's logits:
-        // every group must have read its logits (F, one beat before its own) by then
-        constexpr bool order_ok = [] {
-            for (int g = 1; g < NG; ++g) {
-                const int sl = SPG * g, kc = sl / (2 * NQ), e0 = 8 * (kc & 1) + 4 * (sl & 1);
-                if ((g - 1) * SLOTS / NG > NA + e0 / (16 / NB)) return false;
-            }
-            return true;
-        }();
-        static_assert(order_ok, "an exponential group would read logits the max scan already replaced");
         // one pipeline beat: E of group g, C of group g - 1, F of group g + 1
-        auto beat = [&](int g, float (&arg)[2][SPG][4], float (&ex)[2][SPG][4], bf16x8 (&pk)[NQ][4]) {
+        auto beat = [&](int g, float (&arg)[2][SPG][SL], float (&ex)[2][SPG][SL], bf16x8 (&pk)[NQ][4]) {
             if (g < NG) {
 #pragma unroll
                 for (int e = 0; e < SPG; ++e) slice_E(arg[g & 1][e], ex[g & 1][e]);
@@ -683,16 +679,15 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             }
             if (g + 1 < NG) {
 #pragma unroll
-                for (int e = 0; e < SPG; ++e) slice_F(s, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
+                for (int e = 0; e < SPG; ++e) slice_F(sc, SPG * (g + 1) + e, arg[(g + 1) & 1][e]);
             }
         };
         constexpr int KAHEAD = 2, VAHEAD = 2;  // fragment reads run this many MFMA groups ahead (deeper spills)
         const unsigned char *tV = smem + (size_t)(t % STAGES) * 2 * TILE_B + TILE_B;
         const unsigned char *tK = smem + (size_t)((t + 1) % STAGES) * 2 * TILE_B;
-        f32x16 sn[NQ][2];
         bf16x8 pk[NQ][4];
         bf16x8 kf[KAHEAD + 1], vf[VAHEAD + 1];
-        float arg[2][SPG][4], ex[2][SPG][4];
+        float arg[2][SPG][SL], ex[2][SPG][SL];
         if (NEXT) {
             // tile t + 1 has landed when at most the copies of tile t + 2 remain; the barrier
             // publishes every wave's part and retires the buffer tile t - 1 used
@@ -716,7 +711,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             for (int i = 0; i < KAHEAD; ++i) kf[i] = read_k(tK, i);
         }
 #pragma unroll
-        for (int e = 0; e < SPG; ++e) slice_F(s, e, arg[0][e]);
+        for (int e = 0; e < SPG; ++e) slice_F(sc, e, arg[0][e]);
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
@@ -749,9 +744,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             if (j + VAHEAD < NB) vf[(j + VAHEAD) % (VAHEAD + 1)] = read_v(tV, j + VAHEAD);
-            // remaining exponential groups; the last beat only rounds the last group's weights.  A
-            // group's logits are read (F) before the max scan below overwrites them: its first
-            // element 8 cc + 4 hf is overwritten in step (8 cc + 4 hf) / PER, F runs a beat earlier.
+            // remaining exponential groups; the last beat only rounds the last group's weights
 #pragma unroll
             for (int g = 0; g <= NG; ++g)
                 if ((g < NG ? slot_of(g) : slot_of(NG - 1) + 1) == NA + j) beat(g, arg, ex, pk);
@@ -766,10 +759,8 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #pragma unroll
                     for (int r = 0; r < PER; ++r) {
                         const int e = PER * j + r;
-                        s[a][0][e] = sn[a][0][e];   // tile t's logits are dead: all their slices ran in stage A
-                        s[a][1][e] = sn[a][1][e];
-                        mch[a][e & 1] = e < 2 ? max3_raw(s[a][0][e], s[a][1][e], s[a][0][e])
-                                              : max3_raw(mch[a][e & 1], s[a][0][e], s[a][1][e]);
+                        mch[a][e & 1] = e < 2 ? max3_raw(sn[a][0][e], sn[a][1][e], sn[a][0][e])
+                                              : max3_raw(mch[a][e & 1], sn[a][0][e], sn[a][1][e]);
                     }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -788,11 +779,30 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // (edge tiles: causal mask, rows from the block, partial tiles); then the last tile.
     using T_ = std::true_type;
     using F_ = std::false_type;
+    // The logits of tile t + 1 are formed in one array while those of tile t are consumed from the
+    // other; the hot loop runs two steps per iteration with the roles swapped, the other loops move
+    // the new logits back (32 register moves per lane that the hot loop is spared).
+    f32x16 s2[NQ][2];
+    auto step1 = [&](int t, auto next_tag, auto masked_tag, auto copy_tag) {
+        step(t, s, s2, next_tag, masked_tag, copy_tag);
+        if (decltype(next_tag)::value) {
+#pragma unroll
+            for (int a = 0; a < NQ; ++a) {
+                s[a][0] = s2[a][0];
+                s[a][1] = s2[a][1];
+            }
+        }
+    };
     int t = t0;
-    for (; t + STAGES - 1 < min(tint, t1); ++t) step(t, T_{}, F_{}, std::integral_constant<int, 1>{});
+    const int lim1 = min(tint, t1);
+    for (; t + STAGES < lim1; t += 2) {
+        step(t, s, s2, T_{}, F_{}, std::integral_constant<int, 1>{});
+        step(t + 1, s2, s, T_{}, F_{}, std::integral_constant<int, 1>{});
+    }
+    for (; t + STAGES - 1 < lim1; ++t) step1(t, T_{}, F_{}, std::integral_constant<int, 1>{});
     if (t + STAGES - 1 >= t1)
-        for (; t + 1 < tint; ++t) step(t, T_{}, F_{}, std::integral_constant<int, 0>{});
-    for (; t + 1 < t1; ++t) step(t, T_{}, T_{}, std::integral_constant<int, 2>{});
+        for (; t + 1 < tint; ++t) step1(t, T_{}, F_{}, std::integral_constant<int, 0>{});
+    for (; t + 1 < t1; ++t) step1(t, T_{}, T_{}, std::integral_constant<int, 2>{});
 
     // ---- append (Eq. 5): this workgroup's slice of the block's rows.  The attention reads the
     // block straight from k_new / v_new, so nothing waits for the append: when the slice is small
@@ -807,7 +817,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         aval = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)(j0 + rem / UPR) * D + (rem % UPR) * 8);
     }
 
-    if (ntl > 0) step(t, F_{}, F_{}, std::integral_constant<int, 0>{});
+    if (ntl > 0) step1(t, F_{}, F_{}, std::integral_constant<int, 0>{});
     if (scoring) flush_scores();
 
     if (small) {
