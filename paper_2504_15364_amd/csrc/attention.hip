@@ -142,7 +142,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     const int tplain = min(p.ntiles, p.len / TILE_KEYS);
     const int ctotal = tplain + (p.ntiles - tplain) * p.edge_cost;
     auto tile_at = [&](int i) {   // first tile of split i
-        const int c = (int)(((long)i * ctotal) / p.splits);
+        const int c = (int)(((unsigned)i * (unsigned)ctotal) / (unsigned)p.splits);   // < 2^31: at most 512 splits x 1536 cost units
         return c <= tplain ? c : tplain + (c - tplain) / p.edge_cost;
     };
     const int t0 = tile_at(sp);
@@ -235,12 +235,24 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     unsigned char *qwave = smem + (size_t)((t0 + 2 + qhalf) % STAGES) * 2 * TILE_B + (qoff - qhalf * 2 * TILE_B);
     {
         const char *qhead = reinterpret_cast<const char *>(p.q + (size_t)(b * p.hq + kvh * p.G) * p.Bt * D);
+        const int m0 = mt * TM + wave * QROWS;   // first row of the wave
+        if (m0 + QROWS <= Mtot) {
+            // every row exists: one base address for the wave, a 32-bit offset per lane and copy
+            const int r0 = lane / UPR;
 #pragma unroll
-        for (int i = 0; i < QBYTES / 1024; ++i) {
-            const int r = RPL * i + lane / UPR;                       // row inside the wave's block
-            const int m = min(mt * TM + wave * QROWS + r, Mtot - 1);  // rows past the end repeat the last one
-            async_copy16((uint32_t)(uintptr_t)qwave + 1024u * i,
-                         qhead + (size_t)m * ROWB + (((lane % UPR) ^ (r & (UPR - 1))) * 16));
+            for (int i = 0; i < QBYTES / 1024; ++i) {
+                const int r = RPL * i + r0;
+                async_copy16((uint32_t)(uintptr_t)qwave + 1024u * i, qhead + (size_t)m0 * ROWB,
+                             (uint32_t)(r * ROWB + (((lane % UPR) ^ (r & (UPR - 1))) * 16)));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < QBYTES / 1024; ++i) {
+                const int r = RPL * i + lane / UPR;                       // row inside the wave's block
+                const int m = min(m0 + r, Mtot - 1);                      // rows past the end repeat the last one
+                async_copy16((uint32_t)(uintptr_t)qwave + 1024u * i,
+                             qhead + (size_t)m * ROWB + (((lane % UPR) ^ (r & (UPR - 1))) * 16));
+            }
         }
     }
     if (ntl > 1) issue_tile(t0 + 1);
@@ -643,7 +655,9 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
                 mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
         }
-        if (need_sum) __syncthreads();   // the anchor is complete before any row is scored
+        // The anchor is complete before any row is scored: the barrier that opens the first step of
+        // the loop publishes it; a range of a single tile has no such step.
+        if (need_sum && ntl == 1) __syncthreads();
     }
     // ---- the tile loop, software pipelined by hand (at most two waves share a SIMD: little else
     // hides a latency).  Iteration t:
@@ -808,7 +822,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // block straight from k_new / v_new, so nothing waits for the append: when the slice is small
     // its loads are issued here, fly during the last tile, and are stored after it.
     const int W = p.mtiles * p.splits, widx = sp * p.mtiles + mt;
-    const int j0 = (int)(((long)widx * p.Bt) / W), j1 = (int)(((long)(widx + 1) * p.Bt) / W);
+    const int j0 = (int)(((unsigned)widx * (unsigned)p.Bt) / (unsigned)W), j1 = (int)(((unsigned)(widx + 1) * (unsigned)p.Bt) / (unsigned)W);
     const int arows = j1 - j0;
     const bool small = arows * UPR * 2 <= NT;
     u32x4 aval = {0u, 0u, 0u, 0u};
@@ -837,12 +851,37 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // the key sum after this step, for step_post and for the next step
     if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
 
-    // ---- output.  Accumulator element e of d-block db is d = 32 db + 8 (e / 4) + 4 h + e % 4 of
-    // query l32: 8-byte pieces of 32 different rows, which as direct stores would cost one memory
-    // transaction per piece.  Each wave transposes its 32 NQ rows through a private piece of LDS
-    // (the two ring buffers no tile occupies after the last barrier) and stores whole rows, 16
-    // bytes per lane; the rows of a wave are contiguous in memory in both output forms.
-    if (active) {
+    // ---- output
+    if (active && p.splits > 1) {
+        // Partials leave in the accumulator's own layout, as whole 512-byte slabs with no detour
+        // through LDS: slab (db, jj) of a 32-row block holds, for lane (h, l32), the four values
+        // d = 32 db + 8 jj + 4 h .. + 3 of row l32.  Only the merge reads them, in the same order.
+        constexpr int SLABS = D / 8;
+        const int nblk = (Mtot + 31) / 32;
+#pragma unroll
+        for (int a = 0; a < NQ; ++a) {
+            const float lsum = lrun[a][0] + lrun[a][1];
+            const float ltot = lsum + __shfl_xor(lsum, 32);
+            const float inv = ltot > 0.f ? 1.f / ltot : 0.f;   // a row of a split may see no key at all
+            const int blk = (mt * TM + wave * (32 * NQ)) / 32 + a;
+            _Float16 *base = p.part_o + ((((size_t)sp * BH + bh) * nblk + blk) * SLABS * 64 + lane) * 4;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    f16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * inv);
+                    *reinterpret_cast<f16x4 *>(base + (size_t)(4 * db + jj) * 64 * 4) = o;
+                }
+            if (h == 0 && valid[a]) p.part_ml[(size_t)sp * BH * Mtot + (size_t)bh * Mtot + mrow[a]] = make_float2(mref[a], ltot);
+        }
+    } else if (active) {
+        // A single split writes the bf16 output itself.  Accumulator element e of d-block db is
+        // d = 32 db + 8 (e / 4) + 4 h + e % 4 of query l32: 8-byte pieces of 32 different rows, which as
+        // direct stores would cost one memory transaction per piece.  Each wave transposes its 32 NQ
+        // rows through a private piece of LDS (the two ring buffers no tile occupies after the last
+        // barrier) and stores whole rows, 16 bytes per lane.
         constexpr int WROWS = 32 * NQ, WBYTES = WROWS * ROWB;
         static_assert(NW * WBYTES <= 2 * 2 * TILE_B, "the transposition uses two ring buffers");
         // stages (t1 + 1) % STAGES and t1 % STAGES: tiles t1 - 3 and t1 - 4 (or never filled)
@@ -851,13 +890,11 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             const int half = off / (2 * TILE_B);
             return smem + (size_t)((t1 + 1 - half + STAGES) % STAGES) * 2 * TILE_B + (off - half * 2 * TILE_B);
         };
-        const bool direct = p.splits == 1;
-        float ltot[NQ];
 #pragma unroll
         for (int a = 0; a < NQ; ++a) {
             const float lsum = lrun[a][0] + lrun[a][1];
-            ltot[a] = lsum + __shfl_xor(lsum, 32);
-            const float inv = ltot[a] > 0.f ? 1.f / ltot[a] : 0.f;   // a row of a split may see no key at all
+            const float ltot = lsum + __shfl_xor(lsum, 32);
+            const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
             const int row = 32 * a + l32;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
@@ -865,31 +902,15 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 for (int jj = 0; jj < 4; ++jj) {
                     // 16-byte unit 4 db + jj of the row, swizzled by the row; lane half h takes 8 bytes
                     unsigned char *dst = stage_ptr(region + row * ROWB + (((4 * db + jj) ^ (row & (UPR - 1))) * 16) + 8 * h);
-                    if (direct) {
-                        bf16x4 o;
+                    bf16x4 o;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[a][db][4 * jj + r] * inv);
-                        *reinterpret_cast<bf16x4 *>(dst) = o;
-                    } else {
-                        f16x4 o;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * inv);
-                        *reinterpret_cast<f16x4 *>(dst) = o;
-                    }
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(oacc[a][db][4 * jj + r] * inv);
+                    *reinterpret_cast<bf16x4 *>(dst) = o;
                 }
         }
-        // rows of this wave: m = mbase .. mbase + WROWS - 1
+        // rows of this wave: m = mbase .. mbase + WROWS - 1, contiguous in `out`
         const int mbase = mt * TM + wave * WROWS;
-        unsigned char *gbase;
-        if (direct) {
-            gbase = reinterpret_cast<unsigned char *>(p.out + ((size_t)(b * p.hq + kvh * p.G) * p.Bt + mbase) * D);
-        } else {
-            const size_t prow = (size_t)sp * BH * Mtot + (size_t)bh * Mtot + mbase;
-            gbase = reinterpret_cast<unsigned char *>(p.part_o + prow * D);
-#pragma unroll
-            for (int a = 0; a < NQ; ++a)
-                if (h == 0 && valid[a]) p.part_ml[prow + 32 * a + l32] = make_float2(mref[a], ltot[a]);
-        }
+        unsigned char *gbase = reinterpret_cast<unsigned char *>(p.out + ((size_t)(b * p.hq + kvh * p.G) * p.Bt + mbase) * D);
         constexpr int RPI = 1024 / ROWB;   // rows one wave-wide 16-byte-per-lane store covers
 #pragma unroll
         for (int i = 0; i < WBYTES / 1024; ++i) {

@@ -110,22 +110,32 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
 
 
 // ------------------------------------------------------------------------ merge
+// Thread gid takes four output values: step_main leaves a partial in its accumulator layout -- per
+// 32-row block D/8 slabs of 512 bytes, slab 4 db + jj holding for lane (h, l32) the values
+// d = 32 db + 8 jj + 4 h .. + 3 of row l32 -- and consecutive threads read consecutive lanes of a slab.
 template <int D>
 __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
 {
+    constexpr int SLABS = D / 8;
     const int BH = p.batch * p.hkv;
     const int Mtot = p.G * p.Bt;
+    const int nblk = (Mtot + 31) / 32;
     const size_t rows = (size_t)BH * Mtot;
-    const int d4 = (int)(gid % (D / 4));
-    const size_t row = gid / (D / 4);
-    if (row >= rows) return;
+    const int L = (int)(gid % 64), slab = (int)((gid / 64) % SLABS);
+    const size_t blkid = gid / (64 * SLABS);   // (head, 32-row block)
+    if (blkid >= (size_t)BH * nblk) return;
+    const int bh = (int)(blkid / nblk), m = (int)(blkid % nblk) * 32 + (L & 31);
+    if (m >= Mtot) return;
+    const size_t row = (size_t)bh * Mtot + m;
+    const size_t pstride = (size_t)BH * nblk * SLABS * 64 * 4;          // halfs per split
+    const _Float16 *pbase = p.part_o + ((blkid * SLABS + slab) * 64 + L) * 4;
     // One memory round trip: the (max, sum) pairs and the partial rows of a batch of splits are
     // requested together; only with more splits than a batch holds does a second batch follow, and
     // the running result is then rescaled to the larger reference (as inside the attention).
     constexpr int MB = 16;
     float mx = -INFINITY;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float L = 0.f;
+    float Lsum = 0.f;
     for (int s0 = 0; s0 < p.splits; s0 += MB) {
         float2 ml[MB];
         f16x4 o[MB];
@@ -134,7 +144,7 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
             const bool live = s0 + i < p.splits;
             const f16x4 zero = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
             ml[i] = live ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
-            o[i] = live ? *reinterpret_cast<const f16x4 *>(p.part_o + ((size_t)(s0 + i) * rows + row) * D + 4 * d4) : zero;
+            o[i] = live ? *reinterpret_cast<const f16x4 *>(pbase + (size_t)(s0 + i) * pstride) : zero;
         }
         float bm = ml[0].x;
 #pragma unroll
@@ -145,7 +155,7 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
             acc.y *= down;
             acc.z *= down;
             acc.w *= down;
-            L *= down;
+            Lsum *= down;
             mx = bm;
         }
 #pragma unroll
@@ -156,19 +166,19 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
             acc.y += w * (float)o[i][1];
             acc.z += w * (float)o[i][2];
             acc.w += w * (float)o[i][3];
-            L += w;
+            Lsum += w;
         }
     }
-    const float inv = 1.f / L;
-    const int bh = (int)(row / Mtot), m = (int)(row % Mtot);
+    const float inv = 1.f / Lsum;
     const int b = bh / p.hkv, kvh = bh % p.hkv;
     const int g = m / p.Bt, j = m % p.Bt;
+    const int d0 = 8 * slab + 4 * (L >> 5);
     bf16x4 o;
     o[0] = (__bf16)(acc.x * inv);
     o[1] = (__bf16)(acc.y * inv);
     o[2] = (__bf16)(acc.z * inv);
     o[3] = (__bf16)(acc.w * inv);
-    *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + 4 * d4) = o;
+    *reinterpret_cast<bf16x4 *>(p.out + ((size_t)(b * p.hq + kvh * p.G + g) * p.Bt + j) * D + d0) = o;
 }
 
 // The merge as a kernel of its own (a step whose eviction is deferred has nothing else to run
@@ -405,7 +415,7 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
     const int grid = (p.do_evict ? p.batch * p.hkv : 0) + p.merge_wgs;
     if (grid == 0) return hipSuccess;
     if (!p.do_evict) {   // merge only
-        const size_t threads = (size_t)p.batch * p.hkv * p.G * p.Bt * (p.D / 4);
+        const size_t threads = (size_t)p.batch * p.hkv * ((p.G * p.Bt + 31) / 32) * (p.D / 8) * 64;
         const int mgrid = (int)((threads + MERGE_THREADS - 1) / MERGE_THREADS);
         if (p.D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);
         else if (p.D == 64) hipLaunchKernelGGL((merge_kernel<64>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);

@@ -42,7 +42,8 @@ struct StepParams {
                                      // step_main (+ the block's keys), then by step_post (- the evicted keys)
     int32_t *status;
     // scratch
-    _Float16 *part_o;                // [splits][BH * G * Bt][D] partial outputs, each normalised by its row sum
+    _Float16 *part_o;                // [splits][BH][blocks of 32 rows][D/8 slabs][64 lanes][4] partial outputs in the
+                                     // MFMA accumulator layout, each normalised by its row sum
     float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1

@@ -68,10 +68,10 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_status = off;  off += 256;
     L.off_oflags = off;  off += align256(BH * ((L.cap + kd::ORD_ROWS - 1) / kd::ORD_ROWS) * 4);  // ordered compaction
     L.meta_bytes = off;
-    // split-KV partial rows: splits * BH * G * Bt never exceeds this (see plan_attention)
+    // split-KV partial rows: splits * BH * (G * Bt rounded up to 32) never exceeds this (see plan_attention)
     const int max_mtiles = (G * c->block_B + 127) / 128;
     const size_t by_tiles = (kTargetWorkgroups + BH * max_mtiles + BH) * 256;
-    const size_t by_rows = (kTargetWorkgroups + 2 * BH) * (size_t)G * c->block_B;
+    const size_t by_rows = (kTargetWorkgroups + 2 * BH) * (size_t)((G * c->block_B + 31) / 32 * 32);   // blocks of 32 rows
     L.max_part_rows = (int)(by_tiles < by_rows ? by_tiles : by_rows);
     const size_t chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
     off = 0;
@@ -214,7 +214,8 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     if (splits > p.ntiles) splits = p.ntiles;
     if (splits < 1) splits = 1;
     // partial rows must fit the scratch sized at init
-    while (splits > 1 && (long)splits * BH * Mtot > c->L.max_part_rows) --splits;
+    const int Mpad = (Mtot + 31) / 32 * 32;   // partials are stored in blocks of 32 rows
+    while (splits > 1 && (long)splits * BH * Mpad > c->L.max_part_rows) --splits;
     p.splits = splits;
     // a tile with rows of the block counts as up to three plain ones when the tiles are dealt out
     // (measured: the steps around such tiles take about that much longer); every split must still
@@ -226,7 +227,7 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
             p.edge_cost = e;
             break;
         }
-    const size_t merge_threads = (size_t)BH * Mtot * (p.D / 4);
+    const size_t merge_threads = (size_t)BH * (Mpad / 32) * (p.D / 8) * 64;
     p.merge_wgs = splits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
 
