@@ -69,7 +69,7 @@ def counter(root, name, copy_bytes):
                   f"-> {factor:.2f} bytes per count")
     print(f"{'kernel':64s} {'n':>6s} {'mean ' + name:>20s} {'calibrated bytes':>18s}")
     for k, v in sorted(agg.items()):
-        if "step_" not in k and "compact" not in k:
+        if "step_" not in k and "compact" not in k and "merge" not in k:
             continue
         m = sum(v) / len(v)
         cal = f"{m * factor:18.0f}" if factor else f"{'-':>18s}"
