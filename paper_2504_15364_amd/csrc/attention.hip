@@ -100,7 +100,7 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
 // NQ: 32-row query blocks per wave; every K / V fragment read from LDS feeds one MFMA per block.
 // HELP: some waves of a workgroup may have no query row at all (few query rows: decode); such a
 // wave takes no part in the attention, it copies its share of every tile and scores rows.
-template <int D, int NW, int NQ, bool HELP>
+template <int D, int NW, int NQ, bool HELP, bool ALT>
 __device__ __forceinline__ void step_main_body(const StepParams &p, const int block_id)
 {
     constexpr int NT = 64 * NW;   // threads
@@ -217,25 +217,34 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // the wave's piece of the two ring buffers that tiles t0 + 2 and t0 + 3 will use later (with
     // the K swizzle), and read from there into registers.  Loading the B-operand layout directly
     // would touch 32 rows per instruction.
+    // ALT (a HELP kernel whose workgroup has a single wave's worth of query rows: decode): waves 0 and 1
+    // both hold those rows and take alternate key tiles -- in every step one of them forms S^T of its
+    // next tile while the other turns the logits of its current tile into weights and multiplies
+    // with V, so the two halves of a step run side by side on two SIMDs.  Each keeps its own
+    // running maximum, row sum and output and writes them as a partial of its own: to the merge
+    // the two look like two more key splits (p.psplits = 2 p.splits).
+    static_assert(!ALT || HELP, "alternating waves are a mode of the kernel with helper waves");
+    constexpr bool alt = ALT;
+    const int wave_q = alt ? 0 : wave;                // whose query rows this wave holds
     int mrow[NQ], qg[NQ], qj[NQ], vis[NQ];
     bool valid[NQ];
     bf16x8 qreg[NQ][NC];
 #pragma unroll
     for (int a = 0; a < NQ; ++a) {
-        mrow[a] = mt * TM + wave * (32 * NQ) + 32 * a + l32;
+        mrow[a] = mt * TM + wave_q * (32 * NQ) + 32 * a + l32;
         valid[a] = mrow[a] < Mtot;
         qg[a] = valid[a] ? mrow[a] / p.Bt : 0;
         qj[a] = valid[a] ? mrow[a] % p.Bt : 0;
         vis[a] = p.len + qj[a] + 1;  // rows [0, vis) are visible: all cached rows, block rows 0..j
     }
-    const bool active = !HELP || mt * TM + wave * (32 * NQ) < Mtot;   // wave uniform
+    const bool active = !HELP || (alt ? wave < 2 : mt * TM + wave * (32 * NQ) < Mtot);   // wave uniform
     constexpr int QROWS = 32 * NQ, QBYTES = QROWS * ROWB;
     static_assert(NW * QBYTES <= 2 * 2 * TILE_B && (2 * TILE_B) % QBYTES == 0, "query staging uses two ring buffers");
     const int qoff = wave * QBYTES, qhalf = qoff / (2 * TILE_B);
     unsigned char *qwave = smem + (size_t)((t0 + 2 + qhalf) % STAGES) * 2 * TILE_B + (qoff - qhalf * 2 * TILE_B);
     {
         const char *qhead = reinterpret_cast<const char *>(p.q + (size_t)(b * p.hq + kvh * p.G) * p.Bt * D);
-        const int m0 = mt * TM + wave * QROWS;   // first row of the wave
+        const int m0 = mt * TM + wave_q * QROWS;   // first row of the wave
         if (m0 + QROWS <= Mtot) {
             // every row exists: one base address for the wave, a 32-bit offset per lane and copy
             const int r0 = lane / UPR;
@@ -555,7 +564,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // Which waves score when some have no query rows: only those, so that the waves carrying the
     // attention do not also carry the score.  A scoring wave takes the passes (RPP consecutive rows
     // each) sidx, sidx + nscore, ... of every tile its workgroup owns.
-    const int nactive = HELP ? min(NW, (Mtot - mt * TM + 32 * NQ - 1) / (32 * NQ)) : NW;
+    const int nactive = !HELP ? NW : alt ? 2 : min(NW, (Mtot - mt * TM + 32 * NQ - 1) / (32 * NQ));
     const int nscore = nactive < NW ? NW - nactive : NW;
     const int sidx = nactive < NW ? wave - nactive : wave;   // negative: this wave does not score
     auto score_tile_shared = [&](int t) {
@@ -646,7 +655,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             sq = row_allreduce_f64<16>(sq);
             if ((lane & 15) == 0) red[wave][lane >> 4] = sq;
         }
-        if (active) {
+        if (active && !(alt && wave == 1)) {   // (ALT: tile t0 is wave 0's; wave 1 starts with t0 + 1 inside the loop)
             qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
             if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
             float mloc[NQ];
@@ -720,6 +729,43 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             if (scoring && t % p.mtiles == mt) score_tile(t);
             return;
         }
+        if constexpr (ALT) {
+            // this wave's half of the step: the tile after this one is mine -> its logits; this tile is
+            // mine -> its weights and the product with V
+            if (NEXT) {
+#pragma unroll
+                for (int c = 0; c < LPW; ++c) {
+                    if (COPY == 1) issue_copy_cached(t + STAGES - 1, c);
+                    if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
+                }
+            }
+            const bool mine = ((t - t0) & 1) == wave;   // wave uniform
+            if (mine) {
+#pragma unroll
+                for (int g = 0; g < NS; ++g) {
+                    slice_F(s, g, arg[g & 1][0]);
+                    slice_E(arg[g & 1][0], ex[g & 1][0]);
+                    slice_C(ex[g & 1][0], g, pk);
+                    if (g & 1) __builtin_amdgcn_sched_barrier(0);   // two slices in flight, not all sixteen
+                }
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int kc = j / NDB, db = j % NDB;
+                    const bf16x8 v = read_v(tV, j);
+#pragma unroll
+                    for (int a = 0; a < NQ; ++a)
+                        oacc[a][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, pk[a][kc], oacc[a][db], 0, 0, 0);
+                    if (j & 1) __builtin_amdgcn_sched_barrier(0);
+                }
+            } else if (NEXT) {
+                qk_tile(tK, s);
+                if (MASKED) mask_tile(s, (t + 1) * TILE_KEYS);
+                float mloc[NQ];
+                tile_max(s, mloc);
+                new_reference(mloc);
+            }
+            return;
+        } else {
         if (NEXT) {
 #pragma unroll
             for (int i = 0; i < KAHEAD; ++i) kf[i] = read_k(tK, i);
@@ -787,6 +833,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         if (NEXT) {
             new_reference(mloc);
         }
+        }   // !ALT
     };
     // Four loops, so that the common iterations carry no decisions: (1) tile t + 1 unmasked and tile
     // t + 3 entirely cached; (2) tile t + 1 unmasked, nothing left to fetch; (3) the general case
@@ -799,7 +846,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     f32x16 s2[NQ][2];
     auto step1 = [&](int t, auto next_tag, auto masked_tag, auto copy_tag) {
         step(t, s, s2, next_tag, masked_tag, copy_tag);
-        if (decltype(next_tag)::value) {
+        if (!ALT && decltype(next_tag)::value) {   // (alternating waves keep their logits in s throughout)
 #pragma unroll
             for (int a = 0; a < NQ; ++a) {
                 s[a][0] = s2[a][0];
@@ -852,7 +899,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
 
     // ---- output
-    if (active && p.splits > 1) {
+    if (active && p.psplits > 1) {
         // Partials leave in the accumulator's own layout, as whole 512-byte slabs with no detour
         // through LDS: slab (db, jj) of a 32-row block holds, for lane (h, l32), the four values
         // d = 32 db + 8 jj + 4 h .. + 3 of row l32.  Only the merge reads them, in the same order.
@@ -863,8 +910,9 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             const float lsum = lrun[a][0] + lrun[a][1];
             const float ltot = lsum + __shfl_xor(lsum, 32);
             const float inv = ltot > 0.f ? 1.f / ltot : 0.f;   // a row of a split may see no key at all
-            const int blk = (mt * TM + wave * (32 * NQ)) / 32 + a;
-            _Float16 *base = p.part_o + ((((size_t)sp * BH + bh) * nblk + blk) * SLABS * 64 + lane) * 4;
+            const int blk = (mt * TM + wave_q * (32 * NQ)) / 32 + a;
+            const int spo = alt ? 2 * sp + wave : sp;   // ALT: the two waves' results are two partials
+            _Float16 *base = p.part_o + ((((size_t)spo * BH + bh) * nblk + blk) * SLABS * 64 + lane) * 4;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -874,7 +922,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                     for (int r = 0; r < 4; ++r) o[r] = (_Float16)(oacc[a][db][4 * jj + r] * inv);
                     *reinterpret_cast<f16x4 *>(base + (size_t)(4 * db + jj) * 64 * 4) = o;
                 }
-            if (h == 0 && valid[a]) p.part_ml[(size_t)sp * BH * Mtot + (size_t)bh * Mtot + mrow[a]] = make_float2(mref[a], ltot);
+            if (h == 0 && valid[a]) p.part_ml[(size_t)spo * BH * Mtot + (size_t)bh * Mtot + mrow[a]] = make_float2(mref[a], ltot);
         }
     } else if (active) {
         // A single split writes the bf16 output itself.  Accumulator element e of d-block db is
@@ -909,7 +957,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 }
         }
         // rows of this wave: m = mbase .. mbase + WROWS - 1, contiguous in `out`
-        const int mbase = mt * TM + wave * WROWS;
+        const int mbase = mt * TM + wave_q * WROWS;
         unsigned char *gbase = reinterpret_cast<unsigned char *>(p.out + ((size_t)(b * p.hq + kvh * p.G) * p.Bt + mbase) * D);
         constexpr int RPI = 1024 / ROWB;   // rows one wave-wide 16-byte-per-lane store covers
 #pragma unroll
@@ -921,10 +969,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     }
 }
 
-template <int D, int NW, int NQ, bool HELP>
+template <int D, int NW, int NQ, bool HELP, bool ALT>
 __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 {
-    step_main_body<D, NW, NQ, HELP>(p, (int)blockIdx.x);
+    step_main_body<D, NW, NQ, HELP, ALT>(p, (int)blockIdx.x);
 }
 
 // step_main with passengers: the first `ncarry` workgroups run the pending selection and
@@ -946,7 +994,7 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepPara
         select_and_compact<D, SPT_CARRY, CARRY_THREADS>(cy, sh, evbits, lists, bh);
         return;
     }
-    step_main_body<D, 8, 1, false>(p, (int)blockIdx.x - ncarry);
+    step_main_body<D, 8, 1, false, false>(p, (int)blockIdx.x - ncarry);
 }
 
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
@@ -958,14 +1006,16 @@ hipError_t configure_main_kernels()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             (int)main_lds_bytes(D));                                               \
     if (e != hipSuccess) return e;
-    KD_SET((step_main_kernel<128, 8, 1, false>), 128)
-    KD_SET((step_main_kernel<128, 8, 1, true>), 128)
-    KD_SET((step_main_kernel<128, 4, 1, false>), 128)
-    KD_SET((step_main_kernel<128, 4, 1, true>), 128)
-    KD_SET((step_main_kernel<64, 8, 1, false>), 64)
-    KD_SET((step_main_kernel<64, 8, 1, true>), 64)
-    KD_SET((step_main_kernel<64, 4, 1, false>), 64)
-    KD_SET((step_main_kernel<64, 4, 1, true>), 64)
+    KD_SET((step_main_kernel<128, 8, 1, false, false>), 128)
+    KD_SET((step_main_kernel<128, 8, 1, true, false>), 128)
+    KD_SET((step_main_kernel<128, 8, 1, true, true>), 128)
+    KD_SET((step_main_kernel<128, 4, 1, false, false>), 128)
+    KD_SET((step_main_kernel<128, 4, 1, true, false>), 128)
+    KD_SET((step_main_kernel<64, 8, 1, false, false>), 64)
+    KD_SET((step_main_kernel<64, 8, 1, true, false>), 64)
+    KD_SET((step_main_kernel<64, 8, 1, true, true>), 64)
+    KD_SET((step_main_kernel<64, 4, 1, false, false>), 64)
+    KD_SET((step_main_kernel<64, 4, 1, true, false>), 64)
     KD_SET((step_main_carry_kernel<128>), 128)
     KD_SET((step_main_carry_kernel<64>), 64)
 #undef KD_SET
@@ -980,10 +1030,14 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
     const int grid = p.batch * p.hkv * p.mtiles * p.splits;
     const size_t lds = main_lds_bytes(p.D);
     const bool help = main_runs_help(p);
+    const bool alt = p.psplits != p.splits;   // two waves share the key tiles: planned only for 8-wave helper launches
+    if (alt && !(help && p.NW == 8 && p.psplits == 2 * p.splits)) return hipErrorInvalidValue;
 #define KD_GO(DD, WW)                                                                                          \
-    if (help) hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, true>), dim3(grid), dim3(64 * WW), lds, s, p);  \
-    else hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, false>), dim3(grid), dim3(64 * WW), lds, s, p);
-    if (p.D == 128 && p.NW == 8) { KD_GO(128, 8) }
+    if (help) hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, true, false>), dim3(grid), dim3(64 * WW), lds, s, p);  \
+    else hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, false, false>), dim3(grid), dim3(64 * WW), lds, s, p);
+    if (alt && p.D == 128) hipLaunchKernelGGL((step_main_kernel<128, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
+    else if (alt && p.D == 64) hipLaunchKernelGGL((step_main_kernel<64, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 128 && p.NW == 8) { KD_GO(128, 8) }
     else if (p.D == 128 && p.NW == 4) { KD_GO(128, 4) }
     else if (p.D == 64 && p.NW == 8) { KD_GO(64, 8) }
     else if (p.D == 64 && p.NW == 4) { KD_GO(64, 4) }

@@ -136,12 +136,12 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     float mx = -INFINITY;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float Lsum = 0.f;
-    for (int s0 = 0; s0 < p.splits; s0 += MB) {
+    for (int s0 = 0; s0 < p.psplits; s0 += MB) {
         float2 ml[MB];
         f16x4 o[MB];
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-            const bool live = s0 + i < p.splits;
+            const bool live = s0 + i < p.psplits;
             const f16x4 zero = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
             ml[i] = live ? p.part_ml[(size_t)(s0 + i) * rows + row] : make_float2(-INFINITY, 0.f);
             o[i] = live ? *reinterpret_cast<const f16x4 *>(pbase + (size_t)(s0 + i) * pstride) : zero;

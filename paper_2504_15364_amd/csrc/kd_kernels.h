@@ -42,20 +42,22 @@ struct StepParams {
                                      // step_main (+ the block's keys), then by step_post (- the evicted keys)
     int32_t *status;
     // scratch
-    _Float16 *part_o;                // [splits][BH][blocks of 32 rows][D/8 slabs][64 lanes][4] partial outputs in the
+    _Float16 *part_o;                // [psplits][BH][blocks of 32 rows][D/8 slabs][64 lanes][4] partial outputs in the
                                      // MFMA accumulator layout, each normalised by its row sum
-    float2 *part_ml;                 // [splits][BH * G * Bt]    (reference max in log2 units, row sum)
+    float2 *part_ml;                 // [psplits][BH * G * Bt]    (reference max in log2 units, row sum)
     float *scores;                   // [BH][cap]
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
     int32_t *lists;                  // [BH][4 * B] evicted rows | holes | movers | mover rank of each tail row
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
+    int psplits;                     // partials per output row the merge adds up: splits, or 2 * splits when two
+                                     // waves of a workgroup take alternate tiles of its key range (decode)
     int edge_cost;                   // weight (in plain tiles, >= 1) of a tile holding rows of the block when
                                      // the key tiles are divided over the splits
     int score_chunks;                // step_score workgroups per head
     int lists_in_lds;                // selection lists live in LDS (else in `lists`)
-    int merge_wgs;                   // merge workgroups in step_post (0 when splits == 1)
+    int merge_wgs;                   // merge workgroups in step_post (0 when psplits == 1)
     int do_score, do_evict;
     int anchor_mode, layout, window_W;
     int32_t pos0, window_pos_min;

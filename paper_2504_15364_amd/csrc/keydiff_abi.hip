@@ -71,7 +71,8 @@ Layout make_layout(const keydiff_config_t *c)
     // split-KV partial rows: splits * BH * (G * Bt rounded up to 32) never exceeds this (see plan_attention)
     const int max_mtiles = (G * c->block_B + 127) / 128;
     const size_t by_tiles = (kTargetWorkgroups + BH * max_mtiles + BH) * 256;
-    const size_t by_rows = (kTargetWorkgroups + 2 * BH) * (size_t)((G * c->block_B + 31) / 32 * 32);   // blocks of 32 rows
+    const size_t Mpad_max = (size_t)((G * c->block_B + 31) / 32 * 32);                               // blocks of 32 rows
+    const size_t by_rows = (kTargetWorkgroups + 2 * BH) * Mpad_max * (G * c->block_B <= 32 ? 2 : 1);  // two partials per workgroup
     L.max_part_rows = (int)(by_tiles < by_rows ? by_tiles : by_rows);
     const size_t chunks = (L.cap + kd::CHUNK_ROWS - 1) / kd::CHUNK_ROWS;
     off = 0;
@@ -183,6 +184,7 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     p.B = cf.block_B;
     p.cap = c->L.cap;
     p.splits = 1;
+    p.psplits = 1;
     p.edge_cost = 1;
     p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
     if (p.score_chunks < 1) p.score_chunks = 1;
@@ -201,7 +203,10 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
 {
     const int BH = p.batch * p.hkv;
     const int Mtot = p.G * p.Bt;
-    p.NW = (Mtot % 256 == 0 || Mtot > 512) ? 8 : 4;   // waves of 32 query rows per workgroup
+    // With at most one wave's worth of query rows (decode) two waves of a workgroup share the key
+    // tiles of its range between them and the rest copy and score: eight waves, so that six score.
+    const bool alt = Mtot <= 32;
+    p.NW = (Mtot % 256 == 0 || Mtot > 512 || alt) ? 8 : 4;   // waves of 32 query rows per workgroup
     const int TM = 32 * p.NW;
     p.mtiles = (Mtot + TM - 1) / TM;
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
@@ -215,8 +220,10 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     if (splits < 1) splits = 1;
     // partial rows must fit the scratch sized at init
     const int Mpad = (Mtot + 31) / 32 * 32;   // partials are stored in blocks of 32 rows
-    while (splits > 1 && (long)splits * BH * Mpad > c->L.max_part_rows) --splits;
+    const int per = alt ? 2 : 1;              // partials a workgroup leaves per row
+    while (splits > 1 && (long)per * splits * BH * Mpad > c->L.max_part_rows) --splits;
     p.splits = splits;
+    p.psplits = per * splits;
     // a tile with rows of the block counts as up to three plain ones when the tiles are dealt out
     // (measured: the steps around such tiles take about that much longer); every split must still
     // span at least one tile, which a span of 2 * edge_cost cost units guarantees
@@ -228,7 +235,7 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
             break;
         }
     const size_t merge_threads = (size_t)BH * (Mpad / 32) * (p.D / 8) * 64;
-    p.merge_wgs = splits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
+    p.merge_wgs = p.psplits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
