@@ -741,21 +741,29 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             }
             const bool mine = ((t - t0) & 1) == wave;   // wave uniform
             if (mine) {
+                // per 16-key chunk: its V^T fragments are requested, its weights formed (the MFMAs of
+                // the chunk before run meanwhile), then its MFMAs issued
+                constexpr int SPK = NS / 4;   // slices per chunk (NQ == 1)
+                static_assert(NQ == 1, "the alternating mode is written for one query block per wave");
+                bf16x8 vfr[2][NDB];
 #pragma unroll
-                for (int g = 0; g < NS; ++g) {
-                    slice_F(s, g, arg[g & 1][0]);
-                    slice_E(arg[g & 1][0], ex[g & 1][0]);
-                    slice_C(ex[g & 1][0], g, pk);
-                    if (g & 1) __builtin_amdgcn_sched_barrier(0);   // two slices in flight, not all sixteen
-                }
+                for (int db = 0; db < NDB; ++db) vfr[0][db] = read_v(tV, db);
 #pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    const int kc = j / NDB, db = j % NDB;
-                    const bf16x8 v = read_v(tV, j);
+                for (int kc = 0; kc < 4; ++kc) {
+                    if (kc + 1 < 4) {
 #pragma unroll
-                    for (int a = 0; a < NQ; ++a)
-                        oacc[a][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, pk[a][kc], oacc[a][db], 0, 0, 0);
-                    if (j & 1) __builtin_amdgcn_sched_barrier(0);
+                        for (int db = 0; db < NDB; ++db) vfr[(kc + 1) & 1][db] = read_v(tV, (kc + 1) * NDB + db);
+                    }
+#pragma unroll
+                    for (int g = kc * SPK; g < (kc + 1) * SPK; ++g) {
+                        slice_F(s, g, arg[g & 1][0]);
+                        slice_E(arg[g & 1][0], ex[g & 1][0]);
+                        slice_C(ex[g & 1][0], g, pk);
+                    }
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+                        oacc[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kc & 1][db], pk[0][kc], oacc[0][db], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             } else if (NEXT) {
                 qk_tile(tK, s);

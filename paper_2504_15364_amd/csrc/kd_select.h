@@ -244,8 +244,85 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
     }
 
-    // ---- 1. histogram of the non-exempt scores in LDS
     const int nwords = (p.n + 31) / 32;
+    if (E == 1) {
+        // ---- 1'. a single row to evict (the generation phase): the arg-max by (score bits, position)
+        // replaces histogram, threshold and ranking
+        for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
+        uint64_t best = 0;   // 0: no row (every real key is larger: orderable() of a finite score is > 0)
+        int besti = -1;
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) {
+            const int i = k * THREADS + tid;
+            if (k * THREADS >= p.n) break;
+            if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) {
+                const uint64_t key = ((uint64_t)orderable(sv[k]) << 32) | (uint32_t)sp[k];
+                if (key > best) {
+                    best = key;
+                    besti = i;
+                }
+            }
+        }
+        uint64_t wbest = best;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)wbest, off), hi = __shfl_xor((uint32_t)(wbest >> 32), off);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            wbest = o > wbest ? o : wbest;
+        }
+        if (lane == 0) sh.wave_tot64[wave] = wbest;
+        __syncthreads();   // also: the bitmap is clear
+        uint64_t gbest = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) gbest = sh.wave_tot64[w] > gbest ? sh.wave_tot64[w] : gbest;
+        // positions are unique within a head, so exactly one thread holds the winning key
+        if (besti >= 0 && best == gbest) {
+            atomicOr(&evbits[besti >> 5], 1u << (besti & 31));
+            sh.tb = besti;
+        }
+        __syncthreads();
+        if (p.layout == 1 && tail_regs && gbest != 0) {
+            // FILL with the one tail row (row N, this step's token) in registers: the rest of the work
+            // is one row read and at most one row moved, done here without lists
+            const int e = sh.tb;
+            double x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = 0.0;
+            if (tid < UPR) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)e * D + tid * 8);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[2 * i] = bf16_lo(w[i]);
+                    x[2 * i + 1] = bf16_hi(w[i]);
+                }
+            }
+            if (p.anchor_mode == 1 && tid < 64) {  // unit key: x / |k|; the row's UPR lanes are the first of wave 0
+                double k2 = 0.0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
+                k2 = row_allreduce_f64<UPR>(k2);
+                const double nk = sqrt(k2);
+                const double inv = nk > 0.0 ? 1.0 / nk : 0.0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] *= inv;
+            }
+            if (tid < UPR) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sh.colsum[0][tid * 8 + i] = x[i];
+            }
+            // the evicted key has been read: its slot may take the tail row (the thread that read
+            // unit u of K is the one that writes unit u of K)
+            if (e != p.N && tid < 2 * UPR) {
+                const int which = tid >= UPR, unit = tid - which * UPR;
+                *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)e * D + unit * 8) = tailv[0];
+                if (tid == 0) pos[e] = p.pos0 + (p.N - p.len);
+            }
+            __syncthreads();
+            if (tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_old - sh.colsum[0][tid];
+            return;
+        }
+    } else {
+    // ---- 1. histogram of the non-exempt scores in LDS
     for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
     for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
     if (tid == 0) {
@@ -335,6 +412,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     } else {
         radix_select_in_bin<THREADS>(p, sh, sc, pos, evbits, tb, need);
     }
+    }   // E > 1
 
     // ---- 4. ordered lists: thread t owns bitmap word t = rows [32 t, 32 t + 32)
     const int own0 = min(p.n, 32 * tid), own1 = min(p.n, own0 + 32);

@@ -159,6 +159,26 @@ def test_decode_steps_batch(layout):
     assert cache.status() == 0
 
 
+@pytest.mark.parametrize("kw", [dict(anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY), dict(window_W=12),
+                                dict(anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY, window_W=30)])
+def test_decode_steps_unit_anchor_and_window(kw):
+    # one eviction per step takes the arg-max path of the selection: cover its unit-key sum update and
+    # the window exemption (also the step whose own token is the one evicted)
+    w = get_config("decode_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=160, batch=2)
+    N = 96
+    seqs = [make_layer(w, seed=19, seq=s) for s in range(w.batch)]
+    cache, oc = make_pair(w, N, 1, batch=w.batch, layout=kd.LAYOUT_FILL, **kw)
+    for t in range(w.prompt_T):
+        q, k, v = (np.stack([s[x][t][:, None, :] for s in seqs]) for x in ("q", "k", "v"))
+        out = cache.decode_step(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.decode_step(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
+        if t % 16 == 0 or t > 150:
+            check_state(cache, oc, f"decode step {t}")
+    check_state(cache, oc, "end of decode")
+    assert cache.status() == 0
+
+
 @pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
 def test_ties_keep_the_lower_position(layout):
     # identical keys: every score is equal, so each step must evict the highest positions
