@@ -95,3 +95,45 @@ def test_decode_8b_shape_batch16():
     order = np.argsort(cache.positions().cpu().numpy(), axis=-1, kind="stable")
     assert np.allclose(np.take_along_axis(got, order, -1), oc.scores(), rtol=SCORE_RTOL, atol=SCORE_ATOL)
     assert cache.status() == 0
+
+
+def test_llama31_8b_shape_deferred_eviction_across_layers():
+    # the headline workload the way bench.py runs it by default: caches loaded at the budget, then
+    # steady-state block steps through several layers, every layer's eviction carried by the next
+    # layer's attention launch.  Attention is checked on sampled calls, the caches at the end.
+    w = get_config("llama31_8b")
+    B, N, L, steps = w.block_B, w.budget_N, 3, 5
+    T = N + steps * B
+    layers = []
+    for l in range(L):
+        data = make_layer(w, seed=91, layer=l, t1=T)
+        cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=kd.LAYOUT_FILL))
+        oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B)
+        K0 = data["k"][:N].transpose(1, 0, 2)[None].copy()
+        V0 = data["v"][:N].transpose(1, 0, 2)[None].copy()
+        P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (1, w.n_kv_heads, N)).copy()
+        cache.load(to_dev(K0), to_dev(V0), torch.from_numpy(P0).cuda())
+        oc.load(K0, V0, P0)
+        cache.profile_enable(True)
+        layers.append((data, cache, oc, *(dev_blocks(data[x][N:], B) for x in ("q", "k", "v"))))
+    sampled = {(0, 0), (2, 1), (steps - 1, L - 1)}
+    for i in range(steps):
+        for l, (data, cache, oc, dq, dk, dv) in enumerate(layers):
+            t = N + i * B
+            out = cache.prefill_block_deferred(dq[i], dk[i], dv[i], t, carry=layers[l - 1][1])
+            q = block_of(data["q"], t, B)[None] if (i, l) in sampled else None
+            ref, _, ev = oc.prefill_block(q, block_of(data["k"], t, B)[None], block_of(data["v"], t, B)[None], t)
+            assert ev == B
+            if q is not None:
+                err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+                assert err <= ATTN_ATOL, f"attention error {err}, step {i}, layer {l}"
+    alone = 0
+    for l, (data, cache, oc, *_rest) in enumerate(layers):
+        pos, K, V = rows_by_position(cache)   # finishes what is still pending (the last layer's last eviction)
+        assert np.array_equal(pos, oc.positions()), f"retained set of layer {l} differs"
+        assert np.array_equal(K, oc.keys()) and np.array_equal(V, oc.values())
+        assert cache.status() == 0
+        cnt = cache.profile_read()
+        alone += cnt["step_post"][1] - cnt["step_main"][1]   # step_post launches beyond the one merge per step
+        cache.close()
+    assert alone == 1, f"{alone} evictions ran in a launch of their own; only the very last one should"
