@@ -206,7 +206,7 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     // With at most one wave's worth of query rows (decode) two waves of a workgroup share the key
     // tiles of its range between them and the rest copy and score: eight waves, so that six score.
     const bool alt = Mtot <= 32;
-    p.NW = (Mtot % 256 == 0 || Mtot > 512 || alt) ? 8 : 4;   // waves of 32 query rows per workgroup
+    p.NW = (Mtot > 256 || Mtot % 256 == 0 || alt) ? 8 : 4;   // waves of 32 query rows per workgroup
     const int TM = 32 * p.NW;
     p.mtiles = (Mtot + TM - 1) / TM;
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
