@@ -8,8 +8,11 @@
 // Work decomposition.  All G * Bt query rows that share one KV head form the M
 // dimension (GQA packing): a workgroup of NW waves owns 32 * NQ * NW of them and a
 // contiguous range of 64-key tiles (split-KV); the splits are merged by
-// log-sum-exp in step_post.  Workgroup ids map KV heads round-robin so that the
-// workgroups of one head share an XCD and its L2.
+// log-sum-exp in step_post (or the merge kernel).  Workgroup ids map KV heads
+// round-robin so that the workgroups of one head share an XCD and its L2.
+// Variants: HELP (few query rows: waves without one copy tiles and score rows), ALT on
+// top of it (one wave's worth of rows: two waves take alternate key tiles), and the
+// carrying kernel whose first workgroups run another cache's pending selection.
 //
 // Data path.  K and V tiles stream global -> LDS asynchronously
 // (global_load_lds_dwordx4: lane i's 16 bytes land at LDS base + 16 i, no VGPRs)

@@ -1,12 +1,14 @@
 // Internal launcher interface between the C-ABI host layer and the gfx950 kernels.
 //
-// One block step is three launches:
+// One block step is two launches:
 //   step_main  append (Eq. 5) + split-KV flash attention partials (Eq. 1-2)
 //              + running key sum S' = S + sum of the block's keys (the anchor is S' / n)
 //              + cosine score of every row, taken from the K tiles while they sit in LDS
 //   step_post  merge of the attention partials  ||  selection of the rows to evict
 //              and compaction, one workgroup per head (Eq. 6-7)
 // plus, for the ORDERED layout only, one more launch that shifts rows in place.
+// With the eviction deferred the second launch is the merge alone, and the selection and
+// compaction ride in the step_main launch of the next cache (launch_step_main_carry).
 // step_score scores a cache outside a block step (keydiff_scores).
 #pragma once
 #include <hip/hip_runtime.h>
