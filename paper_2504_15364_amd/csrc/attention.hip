@@ -93,6 +93,21 @@ __device__ __forceinline__ float max3_raw(float a, float b, float c)
     return r;
 }
 
+// Lane i and lane i ^ 32 hold the two halves of a query's keys (accumulator rows 4 h + ...).  One
+// v_permlane32_swap hands each the other's value without a trip through LDS: of the pair it
+// returns, element 0 is x with its upper 32 lanes replaced by x's lower 32, element 1 is x with its
+// lower 32 lanes replaced by x's upper 32, so in every lane the two elements are {x[i], x[i ^ 32]}.
+__device__ __forceinline__ float max_halves(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return max3_raw(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[0]));
+}
+__device__ __forceinline__ float sum_halves(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_copies()  // at most N of this wave's copies still in flight
 {
@@ -399,7 +414,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         bool need[NQ];
 #pragma unroll
         for (int a = 0; a < NQ; ++a) {
-            mtile[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+            mtile[a] = max_halves(mloc[a]) * p.scale_log2e;
             need[a] = mtile[a] > mref[a] + RESCALE_SLACK;
         }
         bool any = false;
@@ -665,7 +680,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             tile_max(s, mloc);
 #pragma unroll
             for (int a = 0; a < NQ; ++a)   // first reference: nothing accumulated yet, nothing to rescale
-                mref[a] = max3_raw(mloc[a], __shfl_xor(mloc[a], 32), mloc[a]) * p.scale_log2e;
+                mref[a] = max_halves(mloc[a]) * p.scale_log2e;
         }
         // The anchor is complete before any row is scored: the barrier that opens the first step of
         // the loop publishes it; a range of a single tile has no such step.
@@ -919,7 +934,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #pragma unroll
         for (int a = 0; a < NQ; ++a) {
             const float lsum = lrun[a][0] + lrun[a][1];
-            const float ltot = lsum + __shfl_xor(lsum, 32);
+            const float ltot = sum_halves(lsum);
             const float inv = ltot > 0.f ? 1.f / ltot : 0.f;   // a row of a split may see no key at all
             const int blk = (mt * TM + wave_q * (32 * NQ)) / 32 + a;
             const int spo = alt ? 2 * sp + wave : sp;   // ALT: the two waves' results are two partials
@@ -952,7 +967,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #pragma unroll
         for (int a = 0; a < NQ; ++a) {
             const float lsum = lrun[a][0] + lrun[a][1];
-            const float ltot = lsum + __shfl_xor(lsum, 32);
+            const float ltot = sum_halves(lsum);
             const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
             const int row = 32 * a + l32;
 #pragma unroll
