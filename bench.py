@@ -181,12 +181,23 @@ def main():
                 a[0] += ms
                 a[1] += cnt
             c.profile_enable(False)
-        # an event pair with nothing between it costs time by itself: the library records one such
-        # pair per profiled step, and its average is taken off every kernel's bracket
+        # What the two event records of a bracket add to it is not known a priori.  An event pair with
+        # nothing between it (the library records one per profiled step) is an upper bound: two
+        # back-to-back records serialise, while next to a kernel most of their processing hides
+        # behind it -- taking the whole pair off makes the kernels shorter than rocprofv3 sees them
+        # and leaves gaps between them that its trace does not show.  The brackets of a step's
+        # launches, back to back on one stream, must add up to the step's wall-clock time measured
+        # above without any event: the excess, split evenly over the launches, is the overhead
+        # taken off (never more than the empty pair).
         pair = tot.pop("event_pair", [0.0, 0])
         pair_us = pair[0] / pair[1] * 1e3 if pair[1] else 0.0
-        kernels = {k: {"avg_us": v[0] / v[1] * 1e3 - pair_us, "launches": v[1],
-                       "event_bracket_us": v[0] / v[1] * 1e3, "empty_event_pair_us": pair_us}
+        layer_steps = args.profile_steps * L
+        bracket_sum_us = sum(v[0] for v in tot.values()) * 1e3 / layer_steps    # per layer-step
+        launches_per_layer_step = sum(v[1] for v in tot.values()) / layer_steps
+        overhead_us = min(pair_us, max(0.0, (bracket_sum_us - us_per_layer_step) / launches_per_layer_step))
+        kernels = {k: {"avg_us": v[0] / v[1] * 1e3 - overhead_us, "launches": v[1],
+                       "event_bracket_us": v[0] / v[1] * 1e3, "event_overhead_us": overhead_us,
+                       "empty_event_pair_us": pair_us}
                    for k, v in tot.items() if v[1]}
     assert all(c.status() == 0 for c in caches)
 

@@ -43,3 +43,12 @@ def test_bad_configs_are_rejected_with_a_message(kw, code):
     with pytest.raises(kd.KeyDiffError) as e:
         kd.workspace_bytes(kd.KeyDiffConfig(**base))
     assert e.value.code == code and len(str(e.value)) > 20
+
+
+def test_null_handles_are_rejected_before_anything_is_enqueued():
+    # argument checks precede every launch: with no GPU in the process these calls still return errors
+    lib = kd.load_library()
+    assert lib.keydiff_finish(None, None) == kd.EINVAL
+    assert lib.keydiff_prefill_block_deferred(None, None, None, None, 1, 0, None, None, None) == kd.EINVAL
+    assert lib.keydiff_prefill_block(None, None, None, None, 1, 0, None, None, None) == kd.EINVAL
+    assert b"null" in lib.keydiff_last_error()
