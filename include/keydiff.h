@@ -18,7 +18,8 @@
  *   - Tensors are bf16, innermost dimension head_dim contiguous, 16-byte aligned:
  *       q, out        [batch][n_q_heads ][Bt][head_dim]
  *       k_new, v_new  [batch][n_kv_heads][Bt][head_dim]
- *       k/v cache     [batch][n_kv_heads][budget_N + block_B][head_dim]
+ *       k/v cache     [batch][n_kv_heads][cap][head_dim], cap = budget_N + block_B
+ *                     rounded up to a multiple of four rows
  *     q and k arrive as the model produced them (rotary embedding already
  *     applied by the caller); keys are scored exactly as they sit in the cache.
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
@@ -77,7 +78,8 @@ typedef struct {
     int32_t n_kv_heads;
     int32_t head_dim;      /* 64 or 128                                                       */
     int32_t budget_N;      /* cache budget N (Background, "KV Cache Eviction Methods")        */
-    int32_t block_B;       /* largest block size B (Eq. 5); capacity is N + B rows per head   */
+    int32_t block_B;       /* largest block size B (Eq. 5); capacity is N + B rows per head
+                              (rounded up to a multiple of four)                               */
     int32_t anchor_mode;   /* KEYDIFF_ANCHOR_*                                                */
     int32_t window_W;      /* most recent tokens exempt from eviction (Method, "KeyDiff with
                               Sliding Window"); 0 = plain KeyDiff; must be < budget_N          */

@@ -135,7 +135,7 @@ class KeyDiffCache:
             _check(self._L.keydiff_init_cache(C.byref(c), self._k.data_ptr(), self._v.data_ptr(),
                                               self._meta.data_ptr(), self._scratch.data_ptr(),
                                               _stream_ptr(stream), C.byref(self._h)))
-        self.cap = cfg.budget_N + cfg.block_B
+        self.cap = (cfg.budget_N + cfg.block_B + 3) & ~3   # rows per head of the cache buffers (see keydiff.h)
 
     def close(self):
         if getattr(self, "_h", None):

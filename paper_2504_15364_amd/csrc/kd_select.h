@@ -15,6 +15,8 @@ namespace kd {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int MAX_SELECT_WAVES = POST_THREADS / 64;   // PostShared is laid out for the largest workgroup
@@ -217,16 +219,27 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     // below costs one memory round trip now and one for the evicted rows later: the scores and
     // positions of all rows, the running key sum, and (FILL layout) the K/V rows [N, n), the only
     // ones that can move.
+    // A thread takes groups of four consecutive rows (one 16-byte load each for scores and positions:
+    // the memory pipeline spends the same time on a wave's load whatever its width): slot k of a
+    // thread is row 4 ((k / 4) THREADS + tid) + k % 4.  The buffers hold a multiple of four rows.
+    static_assert(SPT % 4 == 0, "slots come in groups of four");
+    auto row_of = [&](int k) { return 4 * ((k >> 2) * THREADS + tid) + (k & 3); };
+    auto group_live = [&](int k) { return 4 * (k >> 2) * THREADS < p.n; };   // uniform: some thread has rows there
     float sv[SPT];
     int32_t sp[SPT];
 #pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = k * THREADS + tid;
-        sv[k] = 0.f;
-        sp[k] = 0;
-        if (k * THREADS < p.n && i < p.n) {
-            sv[k] = sc[i];
-            sp[k] = pos[i];
+    for (int g = 0; g < SPT / 4; ++g) {
+        const int r0 = 4 * (g * THREADS + tid);
+        f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
+        i32x4 p4 = {0, 0, 0, 0};
+        if (4 * g * THREADS < p.n && r0 < p.n) {
+            s4 = *reinterpret_cast<const f32x4 *>(sc + r0);
+            p4 = *reinterpret_cast<const i32x4 *>(pos + r0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sv[4 * g + j] = s4[j];
+            sp[4 * g + j] = p4[j];
         }
     }
     const double ksum_old = tid < D ? p.ksum_next[(size_t)bh * D + tid] : 0.0;  // the sum step_main just wrote
@@ -253,8 +266,8 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         int besti = -1;
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
-            const int i = k * THREADS + tid;
-            if (k * THREADS >= p.n) break;
+            const int i = row_of(k);
+            if (!group_live(k)) break;
             if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) {
                 const uint64_t key = ((uint64_t)orderable(sv[k]) << 32) | (uint32_t)sp[k];
                 if (key > best) {
@@ -334,8 +347,8 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < SPT; ++k) {
-        const int i = k * THREADS + tid;
-        if (k * THREADS >= p.n) break;
+        const int i = row_of(k);
+        if (!group_live(k)) break;
         if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) atomicAdd(&sh.hist[score_bin(sv[k])], 1u);
     }
     __syncthreads();
@@ -370,8 +383,8 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     // above the bin -> evicted, inside it -> candidate for the exact ranking
 #pragma unroll
     for (int k = 0; k < SPT; ++k) {
-        const int i = k * THREADS + tid;
-        if (k * THREADS >= p.n) break;
+        const int i = row_of(k);
+        if (!group_live(k)) break;
         // bin of the row, -1 if it cannot be evicted (exempt or past the end)
         const int sb = (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) ? score_bin(sv[k]) : -1;
         if (sb > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
@@ -483,30 +496,37 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         double acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-        for (int rb = wave * RPW; rb < E; rb += NWAVES * RPW) {  // uniform per wave
-            const int r = rb + rl;
-            double x[8];
+        // the rows of up to EV_BATCH rounds are requested together: one memory round trip, not one per round
+        constexpr int EV_BATCH = 4;
+        for (int rb0 = wave * RPW; rb0 < E; rb0 += EV_BATCH * NWAVES * RPW) {  // uniform per wave
+            u32x4 wv[EV_BATCH];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = 0.0;
-            if (r < E) {
-                const u32x4 w = *reinterpret_cast<const u32x4 *>(kb + (size_t)evlist[r] * D + u * 8);
+            for (int b = 0; b < EV_BATCH; ++b) {
+                const int r = rb0 + b * NWAVES * RPW + rl;
+                wv[b] = u32x4{0u, 0u, 0u, 0u};
+                if (r < E) wv[b] = *reinterpret_cast<const u32x4 *>(kb + (size_t)evlist[r] * D + u * 8);
+            }
+#pragma unroll
+            for (int b = 0; b < EV_BATCH; ++b) {
+                if (rb0 + b * NWAVES * RPW >= E) break;   // uniform
+                double x[8];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    x[2 * i] = bf16_lo(w[i]);
-                    x[2 * i + 1] = bf16_hi(w[i]);
+                    x[2 * i] = bf16_lo(wv[b][i]);
+                    x[2 * i + 1] = bf16_hi(wv[b][i]);
                 }
-            }
-            double inv = 1.0;
-            if (p.anchor_mode == 1) {  // unit key: x / |k|
-                double k2 = 0.0;
+                double inv = 1.0;
+                if (p.anchor_mode == 1) {  // unit key: x / |k|
+                    double k2 = 0.0;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
-                k2 = row_allreduce_f64<UPR>(k2);
-                const double nk = sqrt(k2);
-                inv = nk > 0.0 ? 1.0 / nk : 0.0;
-            }
+                    for (int i = 0; i < 8; ++i) k2 += x[i] * x[i];
+                    k2 = row_allreduce_f64<UPR>(k2);
+                    const double nk = sqrt(k2);
+                    inv = nk > 0.0 ? 1.0 / nk : 0.0;
+                }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
+                for (int i = 0; i < 8; ++i) acc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
+            }
         }
         // fold the rows of the wave (lanes with equal u), then the waves
 #pragma unroll

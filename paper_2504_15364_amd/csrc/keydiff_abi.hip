@@ -60,7 +60,7 @@ Layout make_layout(const keydiff_config_t *c)
     const size_t BH = (size_t)c->batch * c->n_kv_heads;
     const int G = c->n_q_heads / c->n_kv_heads;
     const int D = c->head_dim;
-    L.cap = c->budget_N + c->block_B;
+    L.cap = (c->budget_N + c->block_B + 3) & ~3;   // rows per head, a multiple of four (16-byte loads of scores and positions)
     L.k_bytes = align256(BH * L.cap * D * 2);
     size_t off = 0;
     L.off_pos = off;     off += align256(BH * L.cap * 4);
