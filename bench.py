@@ -57,6 +57,117 @@ def to_blocks(bits: np.ndarray, B: int):
     return t.view(T // B, B, H, d).permute(0, 2, 1, 3).contiguous().unsqueeze(1)
 
 
+def bench_decode(args, w):
+    """The generation phase (block size 1): a batch of sequences, caches at the budget, one token and
+    one eviction per sequence, KV head and step.  HBM-bound: K and V cross it once per step."""
+    import torch
+
+    import paper_2504_15364_amd as kd
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    N, D, Hq, Hkv, batch = w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch
+    n_steps = args.warmup + args.steps + args.profile_steps + (0 if args.no_cpu_baseline else args.cpu_steps)
+    t0 = time.time()
+    with ThreadPoolExecutor(min(16, os.cpu_count() or 1)) as ex:
+        seqs = list(ex.map(lambda s_: make_layer(w, seed=args.seed + 1000 * 5, seq=s_, t1=N + n_steps), range(batch)))
+    log(f"[bench] generated {batch} sequences x {N + n_steps} tokens in {time.time() - t0:.1f}s")
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def token(t):   # [batch][heads][1][d] bit patterns of token t of every sequence
+        return tuple(np.stack([s_[x][t][:, None, :] for s_ in seqs]) for x in ("q", "k", "v"))
+
+    cache = kd.KeyDiffCache(kd.KeyDiffConfig(batch, Hq, Hkv, D, N, 1, layout=kd.LAYOUT_FILL))
+    K0 = np.stack([s_["k"][:N].transpose(1, 0, 2) for s_ in seqs])
+    V0 = np.stack([s_["v"][:N].transpose(1, 0, 2) for s_ in seqs])
+    P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (batch, Hkv, N)).copy()
+    cache.load(dev(K0), dev(V0), torch.from_numpy(P0).cuda())
+    toks = [tuple(dev(x) for x in token(N + i)) for i in range(args.warmup + args.steps + args.profile_steps)]
+    out = torch.empty((batch, Hq, 1, D), dtype=torch.bfloat16, device="cuda")
+    i = 0
+    for _ in range(args.warmup):
+        cache.decode_step(*toks[i], N + i, out=out)
+        i += 1
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        cache.decode_step(*toks[i], N + i, out=out)
+        i += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    us_step = elapsed / args.steps * 1e6
+
+    kernels = {}
+    if args.profile_steps > 0:
+        cache.profile_enable(True)
+        for _ in range(args.profile_steps):
+            cache.decode_step(*toks[i], N + i, out=out)
+            i += 1
+        torch.cuda.synchronize()
+        tot = {k: list(v) for k, v in cache.profile_read().items()}
+        cache.profile_enable(False)
+        pair = tot.pop("event_pair", [0.0, 0])
+        pair_us = pair[0] / pair[1] * 1e3 if pair[1] else 0.0
+        bracket_sum_us = sum(v[0] for v in tot.values()) * 1e3 / args.profile_steps
+        launches = sum(v[1] for v in tot.values()) / args.profile_steps
+        overhead_us = min(pair_us, max(0.0, (bracket_sum_us - us_step) / launches))   # see the prefill path
+        kernels = {k: {"avg_us": v[0] / v[1] * 1e3 - overhead_us, "launches": v[1],
+                       "event_bracket_us": v[0] / v[1] * 1e3, "event_overhead_us": overhead_us,
+                       "empty_event_pair_us": pair_us} for k, v in tot.items() if v[1]}
+    assert cache.status() == 0
+
+    n = N + 1
+    kv_bytes = 2.0 * batch * Hkv * n * D * 2                       # K and V once
+    bytes_step = kv_bytes + 2 * batch * Hq * D * 2 + batch * Hkv * n * 4 + 4 * batch * Hkv * D * 2
+    roofline = None
+    if "step_main" in kernels:
+        t_main = kernels["step_main"]["avg_us"] * 1e-6
+        achieved = kv_bytes / t_main / 1e9
+        roofline = {"bound": "hbm", "kernel": "step_main_kernel (helper waves, alternating tiles)", "achieved": achieved,
+                    "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS,
+                    "traffic": measured_traffic(w.name, "fill"), "bytes_per_launch": kv_bytes,
+                    "avg_launch_us": kernels["step_main"]["avg_us"]}
+    t_min = bytes_step / (PEAK_HBM_GBPS * 1e9)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from synth import bf16_bits_to_f32
+        oc = oracle.OracleCache(batch, Hq, Hkv, D, N, 1)
+        oc.load(K0, V0, P0)
+        ref = kd.KeyDiffCache(kd.KeyDiffConfig(batch, Hq, Hkv, D, N, 1, layout=kd.LAYOUT_FILL))
+        ref.load(dev(K0), dev(V0), torch.from_numpy(P0).cuda())
+        tc, worst = 0.0, 0.0
+        for s_ in range(args.cpu_steps):
+            q, k, v = token(N + s_)
+            t1 = time.perf_counter()
+            o_ref, _, _ = oc.decode_step(q, k, v, N + s_)
+            tc += time.perf_counter() - t1
+            got = ref.decode_step(dev(q), dev(k), dev(v), N + s_)
+            worst = max(worst, float(np.abs(bf16_bits_to_f32(got.view(torch.int16).cpu().numpy().view(np.uint16)) - o_ref).max()))
+            assert np.array_equal(np.sort(ref.positions().cpu().numpy(), axis=-1), oc.positions()), "retained set differs"
+        cpu = {"value": batch * args.cpu_steps / tc, "unit": "tokens/s/layer",
+               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+               "sample": f"{args.cpu_steps} decode steps of the {batch} sequences (fp64, OpenMP over heads x rows)",
+               "us_per_step": tc / args.cpu_steps * 1e6, "max_abs_attention_diff_vs_gpu": worst,
+               "retained_sets_identical": True}
+
+    print(json.dumps({
+        "metric": f"generated tokens/sec per layer (KeyDiff decode step, batch {batch}) at N={N}",
+        "value": batch / (us_step * 1e-6), "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": us_step * 1e-3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "budget_N": N,
+                   "block_B": 1, "batch": batch, "layers": 1, "layout": "fill", "tokens_per_step": batch,
+                   "step": "one decode step of every sequence of the batch on one layer"},
+        "us_per_layer_step": us_step,
+        "step_roofline": {"binding": "hbm", "t_min_us": t_min * 1e6, "frac": t_min / (us_step * 1e-6),
+                          "bytes": bytes_step},
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +194,8 @@ def main():
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     w = get_config(args.workload)
+    if w.block_B == 1:
+        return bench_decode(args, w)
     L = args.layers or w.n_layers
     B, N, D, Hq, Hkv = w.block_B, w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads
     fill_blocks = N // B
