@@ -1001,13 +1001,14 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
     step_main_body<D, NW, NQ, HELP, ALT>(p, (int)blockIdx.x);
 }
 
-// step_main with passengers: the first `ncarry` workgroups run the pending selection and
+// step_main with passengers (8-wave workgroups, with or without helper waves, not the alternating
+// mode): the first `ncarry` workgroups run the pending selection and
 // compaction of another cache (one head each, parameters `cy`), the rest are the workgroups of
 // step_main proper.  A selection is a chain of short dependent stages that keeps one compute unit
 // busy per head for about half as long as the attention keeps the others busy: launched this way
 // it costs no time of its own.  The two caches share nothing, so no ordering between the two
 // kinds of workgroup is needed.
-template <int D>
+template <int D, bool HELP>
 __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepParams p, StepParams cy, int ncarry)
 {
     if ((int)blockIdx.x < ncarry) {
@@ -1020,7 +1021,7 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepPara
         select_and_compact<D, SPT_CARRY, CARRY_THREADS>(cy, sh, evbits, lists, bh);
         return;
     }
-    step_main_body<D, 8, 1, false, false>(p, (int)blockIdx.x - ncarry);
+    step_main_body<D, 8, 1, HELP, false>(p, (int)blockIdx.x - ncarry);
 }
 
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
@@ -1042,8 +1043,10 @@ hipError_t configure_main_kernels()
     KD_SET((step_main_kernel<64, 8, 1, true, true>), 64)
     KD_SET((step_main_kernel<64, 4, 1, false, false>), 64)
     KD_SET((step_main_kernel<64, 4, 1, true, false>), 64)
-    KD_SET((step_main_carry_kernel<128>), 128)
-    KD_SET((step_main_carry_kernel<64>), 64)
+    KD_SET((step_main_carry_kernel<128, false>), 128)
+    KD_SET((step_main_carry_kernel<128, true>), 128)
+    KD_SET((step_main_carry_kernel<64, false>), 64)
+    KD_SET((step_main_carry_kernel<64, true>), 64)
 #undef KD_SET
     return hipSuccess;
 }
@@ -1075,7 +1078,7 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 bool can_carry(const StepParams &p, const StepParams &cy)
 {
     const int ncarry = cy.batch * cy.hkv;
-    return p.NW == 8 && !main_runs_help(p) && p.D == cy.D && cy.do_evict && cy.layout == 1 &&
+    return p.NW == 8 && p.psplits == p.splits && p.D == cy.D && cy.do_evict && cy.layout == 1 &&
            cy.n <= SPT_CARRY * CARRY_THREADS && cy.n <= 32 * CARRY_THREADS &&
            carry_shared_bytes() + post_lds_bytes(cy.n, cy.N) <= main_lds_bytes(p.D) && ncarry > 0;
 }
@@ -1086,8 +1089,13 @@ hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hip
     const int ncarry = cy.batch * cy.hkv;
     const int grid = ncarry + p.batch * p.hkv * p.mtiles * p.splits;
     const size_t lds = main_lds_bytes(p.D);
-    if (p.D == 128) hipLaunchKernelGGL((step_main_carry_kernel<128>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
-    else if (p.D == 64) hipLaunchKernelGGL((step_main_carry_kernel<64>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
+    const bool help = main_runs_help(p);
+#define KD_GO(DD)                                                                                                   \
+    if (help) hipLaunchKernelGGL((step_main_carry_kernel<DD, true>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry); \
+    else hipLaunchKernelGGL((step_main_carry_kernel<DD, false>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
+    if (p.D == 128) { KD_GO(128) }
+    else if (p.D == 64) { KD_GO(64) }
+#undef KD_GO
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

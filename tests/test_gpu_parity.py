@@ -320,6 +320,40 @@ def test_deferred_eviction_where_nothing_can_ride():
     run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=2, expect_ride=None, layout=kd.LAYOUT_ORDERED)
 
 
+def test_deferred_eviction_rides_a_launch_with_helper_waves():
+    # G * B = 384 rows per KV head: 8-wave workgroups of which the second row tile fills only half,
+    # so the attention runs its helper-wave variant; passengers ride in that one too
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=1280)
+    run_layers_deferred(w, 384, 128, 2, seeds=(51, 52), check_every=0, expect_ride=True, layout=kd.LAYOUT_FILL)
+
+
+def test_deferred_eviction_on_another_stream_is_finished_on_its_own():
+    # a carrier on a different stream cannot take the eviction along: it is enqueued on the stream of
+    # the call that deferred it, and both caches still end up right
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1024)
+    N, B = 512, 128
+    a, oa = make_pair(w, N, B, layout=kd.LAYOUT_FILL)
+    b, ob = make_pair(w, N, B, layout=kd.LAYOUT_FILL)
+    da, db = make_layer(w, seed=53), make_layer(w, seed=54)
+    side = torch.cuda.Stream()
+    for (t, Bt, qa, ka, va), (_, _, qb, kb, vb) in zip(blocks(da, B), blocks(db, B)):
+        out_a = a.prefill_block_deferred(to_dev(qa), to_dev(ka), to_dev(va), t)
+        ref_a, _, _ = oa.prefill_block(qa, ka, va, t)
+        tq, tk, tv = to_dev(qb), to_dev(kb), to_dev(vb)
+        torch.cuda.synchronize()            # the inputs are there before the side stream reads them
+        with torch.cuda.stream(side):
+            out_b = b.prefill_block_deferred(tq, tk, tv, t, carry=a, stream=side)
+        ref_b, _, _ = ob.prefill_block(qb, kb, vb, t)
+        torch.cuda.synchronize()
+        assert np.abs(bf16_out_to_f32(out_a) - ref_a).max() <= ATTN_ATOL
+        assert np.abs(bf16_out_to_f32(out_b) - ref_b).max() <= ATTN_ATOL
+        b.finish(stream=side)
+        torch.cuda.synchronize()
+        check_state(a, oa, f"cache on the main stream, token {t}")
+        check_state(b, ob, f"cache on the side stream, token {t}")
+    assert a.status() == 0 and b.status() == 0
+
+
 def test_deferred_eviction_single_cache_and_other_entry_points():
     # no carrier: finish(), scores(), a plain block step and destroy each complete a pending eviction
     w = get_config("toy")
