@@ -211,7 +211,9 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     p.mtiles = (Mtot + TM - 1) / TM;
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
     const int target = p.NW == 8 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
-    int splits = (target + BH * p.mtiles - 1) / (BH * p.mtiles);
+    // 8-wave workgroups run one per compute unit: rounding the split count up would push the last
+    // workgroups into a second round that doubles the kernel's duration
+    int splits = p.NW == 8 ? target / (BH * p.mtiles) : (target + BH * p.mtiles - 1) / (BH * p.mtiles);
     // one workgroup of 8 waves fills a compute unit: with passengers on board the attention takes
     // what is left of the chip in a single round
     if (reserved > 0 && p.NW == 8 && splits * BH * p.mtiles + reserved > target)
