@@ -1036,13 +1036,9 @@ hipError_t configure_main_kernels()
     KD_SET((step_main_kernel<128, 8, 1, false, false>), 128)
     KD_SET((step_main_kernel<128, 8, 1, true, false>), 128)
     KD_SET((step_main_kernel<128, 8, 1, true, true>), 128)
-    KD_SET((step_main_kernel<128, 4, 1, false, false>), 128)
-    KD_SET((step_main_kernel<128, 4, 1, true, false>), 128)
     KD_SET((step_main_kernel<64, 8, 1, false, false>), 64)
     KD_SET((step_main_kernel<64, 8, 1, true, false>), 64)
     KD_SET((step_main_kernel<64, 8, 1, true, true>), 64)
-    KD_SET((step_main_kernel<64, 4, 1, false, false>), 64)
-    KD_SET((step_main_kernel<64, 4, 1, true, false>), 64)
     KD_SET((step_main_carry_kernel<128, false>), 128)
     KD_SET((step_main_carry_kernel<128, true>), 128)
     KD_SET((step_main_carry_kernel<64, false>), 64)
@@ -1067,9 +1063,7 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
     if (alt && p.D == 128) hipLaunchKernelGGL((step_main_kernel<128, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
     else if (alt && p.D == 64) hipLaunchKernelGGL((step_main_kernel<64, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
     else if (p.D == 128 && p.NW == 8) { KD_GO(128, 8) }
-    else if (p.D == 128 && p.NW == 4) { KD_GO(128, 4) }
     else if (p.D == 64 && p.NW == 8) { KD_GO(64, 8) }
-    else if (p.D == 64 && p.NW == 4) { KD_GO(64, 4) }
 #undef KD_GO
     else return hipErrorInvalidValue;
     return hipGetLastError();

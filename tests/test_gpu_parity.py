@@ -313,10 +313,12 @@ def test_deferred_eviction_with_states_read_in_between():
 
 
 def test_deferred_eviction_where_nothing_can_ride():
-    # 4-wave workgroups (G * B = 144 rows) have no carrying variant, and the ORDERED layout does not
-    # defer at all: both must give the plain call's results
+    # with a single wave's worth of query rows per head the attention runs its alternating-waves mode,
+    # which has no carrying variant, and the ORDERED layout does not defer at all: both must give the
+    # plain call's results
+    w = get_config("llama32_3b").small(n_q_heads=4, n_kv_heads=2, head_dim=128, prompt_T=240)
+    run_layers_deferred(w, 80, 8, 2, seeds=(46, 47), check_every=0, expect_ride=False, layout=kd.LAYOUT_FILL)
     w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=500)
-    run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=0, expect_ride=False, layout=kd.LAYOUT_FILL)
     run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=2, expect_ride=None, layout=kd.LAYOUT_ORDERED)
 
 
