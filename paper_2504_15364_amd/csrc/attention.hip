@@ -213,10 +213,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             async_copy16(dst, reinterpret_cast<const char *>(src) + (off0 - crow0 * ROWB));
         }
     };
-    auto issue_tile = [&](int t) {
-#pragma unroll
-        for (int c = 0; c < LPW; ++c) issue_copy(t, c);
-    };
+
     // the same for a tile known to lie entirely in the cache: no decisions left, a handful of
     // scalar instructions per copy
     auto issue_copy_cached = [&](int t, int c) {
@@ -225,6 +222,15 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         const uint32_t dst = lds0 + (uint32_t)((t % STAGES) * 2 * TILE_B) + (isv ? TILE_B : 0) + 1024u * (wave + NW * i);
         const uint16_t *src = (isv ? vcache : kcache) + ((size_t)t * TILE_KEYS + (size_t)i * CSTEP) * D;
         async_copy16(dst, src, isv ? voff0 : koff_of(i));
+    };
+    auto issue_tile = [&](int t) {
+        if ((t + 1) * TILE_KEYS <= p.len) {   // uniform: the whole tile lies in the cache
+#pragma unroll
+            for (int c = 0; c < LPW; ++c) issue_copy_cached(t, c);
+        } else {
+#pragma unroll
+            for (int c = 0; c < LPW; ++c) issue_copy(t, c);
+        }
     };
     // tile t0 first, then the queries, then tile t0 + 1: one memory round trip covers all three
     if (ntl > 0) issue_tile(t0);
