@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2504_15364_amd as kd
 from helpers import (ATTN_ATOL, SCORE_ATOL, SCORE_RTOL, bf16_out_to_f32, blocks, rows_by_position, to_dev)
-from synth import f32_to_bf16_bits, get_config, make_layer
+from synth import block_of, f32_to_bf16_bits, get_config, make_layer
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -138,6 +138,36 @@ def test_budget_not_reached_only_appends():
         assert ev == 0 and np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL
     assert cache.len == 96
     check_state(cache, oc, "no eviction")
+
+
+def test_prefill_of_a_batch_of_sequences():
+    # several independent sequences in one call: per-sequence caches, positions and retained sets
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=480, batch=3)
+    N, B = 200, 48
+    seqs = [make_layer(w, seed=61, seq=s_) for s_ in range(w.batch)]
+    cache, oc = make_pair(w, N, B, batch=w.batch, layout=kd.LAYOUT_FILL)
+    for t in range(0, w.prompt_T, B):
+        q, k, v = (np.stack([block_of(s_[x], t, B) for s_ in seqs]) for x in ("q", "k", "v"))
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, _ = oc.prefill_block(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
+        check_state(cache, oc, f"batch of {w.batch}, token {t}")
+    assert cache.status() == 0
+
+
+def test_more_heads_than_compute_units():
+    # batch x KV heads x row tiles beyond the 256 compute units: one key split, workgroups in rounds
+    w = get_config("toy").small(n_q_heads=2, n_kv_heads=2, head_dim=64, prompt_T=96, batch=150)
+    N, B = 48, 16
+    seqs = [make_layer(w, seed=62, seq=s_) for s_ in range(w.batch)]
+    cache, oc = make_pair(w, N, B, batch=w.batch, layout=kd.LAYOUT_FILL)
+    for t in range(0, w.prompt_T, B):
+        q, k, v = (np.stack([block_of(s_[x], t, B) for s_ in seqs]) for x in ("q", "k", "v"))
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, _ = oc.prefill_block(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
+    check_state(cache, oc, "300 heads")
+    assert cache.status() == 0
 
 
 @pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
