@@ -414,6 +414,29 @@ def test_deferred_eviction_single_cache_and_other_entry_points():
     cache.close()
 
 
+def test_very_large_logits_stay_finite():
+    # queries x 16 and keys x 8 (exact in bf16): logits 128 times larger, softmax close to an arg-max and
+    # reference maxima that jump by hundreds between tiles -- the lazy rescale must keep everything finite
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1024)
+    data = make_layer(w, seed=63)
+    def scaled(bits, by):   # multiply bf16 bit patterns by a power of two: add to the exponent field
+        e = (bits >> 7) & 0xFF
+        out = bits.copy()
+        nz = e != 0
+        out[nz] = (bits[nz] & 0x807F) | (((e[nz].astype(np.int32) + by).clip(1, 254).astype(np.uint16)) << 7)
+        return out
+    data = dict(data, q=scaled(data["q"], 4), k=scaled(data["k"], 3))
+    cache, oc = make_pair(w, 512, 128, layout=kd.LAYOUT_FILL)
+    for t, Bt, q, k, v in blocks(data, 128):
+        out = cache.prefill_block(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, _ = oc.prefill_block(q, k, v, t)
+        got = bf16_out_to_f32(out)
+        assert np.isfinite(got).all(), t
+        assert np.abs(got - ref).max() <= ATTN_ATOL, t
+        check_state(cache, oc, f"token {t}")
+    assert cache.status() == 0
+
+
 def test_zero_key_and_tiny_keys_hit_the_eps_clamp():
     hq, hkv, d, N, B = 2, 1, 64, 40, 16
     w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=64)
