@@ -359,6 +359,13 @@ def test_deferred_eviction_rides_a_launch_with_helper_waves():
     run_layers_deferred(w, 384, 128, 2, seeds=(51, 52), check_every=0, expect_ride=True, layout=kd.LAYOUT_FILL)
 
 
+def test_deferred_eviction_head_dim_64():
+    # the 64-wide instantiation of the carrying kernel (its LDS holds the selection's workspace with
+    # little to spare at this head size)
+    w = get_config("toy").small(n_q_heads=8, n_kv_heads=2, head_dim=64, prompt_T=1024)
+    run_layers_deferred(w, 448, 64, 3, seeds=(71, 72, 73), check_every=4, expect_ride=True, layout=kd.LAYOUT_FILL)
+
+
 def test_deferred_eviction_on_another_stream_is_finished_on_its_own():
     # a carrier on a different stream cannot take the eviction along: it is enqueued on the stream of
     # the call that deferred it, and both caches still end up right
