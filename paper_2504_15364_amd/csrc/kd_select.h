@@ -575,19 +575,26 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         for (int r = tid; r < (int)nholes; r += THREADS) pos[holes[r]] = p.pos0 + (movers[r] - p.len);
     } else {
         // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here
-        // (all reads precede all writes), the K/V rows by compact_ordered_kernel.
-        int32_t mypos[32];
-        int32_t *dst = p.dstmap + (size_t)bh * p.cap;
-        for (int i = own0, j = 0; i < own1; ++i, ++j) mypos[j] = pos[i];
+        // (they were all read into registers at the start), the K/V rows by compact_ordered_kernel.
+        // Every thread handles the rows it loaded (groups of four consecutive rows: coalesced), with
+        // the evicted count before a row taken from the bitmap and the per-word counts of the scan.
+        uint32_t *word_base = sh.cand_slot;   // the candidate arrays are free by now; nwords <= CAND_MAX
+        static_assert(MAX_CAP / 32 <= CAND_MAX, "one count per bitmap word");
+        if (tid < nwords) word_base[tid] = eb;
         __syncthreads();
-        for (int i = own0, j = 0; i < own1; ++i, ++j) {
-            const bool ev = (evw >> j) & 1u;
-            if (ev) {
-                dst[i] = -1;
-                ++eb;
-            } else {
-                dst[i] = i - (int)eb;
-                pos[i - (int)eb] = mypos[j];
+        int32_t *dst = p.dstmap + (size_t)bh * p.cap;
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) {
+            const int i = row_of(k);
+            if (!group_live(k)) break;
+            if (i < p.n) {
+                const uint32_t word = evbits[i >> 5], bit = (uint32_t)i & 31u;
+                if ((word >> bit) & 1u) dst[i] = -1;
+                else {
+                    const int to = i - (int)(word_base[i >> 5] + (uint32_t)__popc(word & ((1u << bit) - 1u)));
+                    dst[i] = to;
+                    pos[to] = sp[k];
+                }
             }
         }
     }
