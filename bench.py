@@ -226,7 +226,7 @@ def main():
         dv.append(to_blocks(layers[l]["v"], B))
         outs.append(torch.empty_like(dq[l][0]))
 
-    deferred = args.eviction == "deferred" and args.layout == "fill" and L > 1
+    deferred = args.eviction == "deferred" and L > 1
 
     def run_block(i):
         for l in range(L):

@@ -131,8 +131,9 @@ KEYDIFF_API int keydiff_prefill_block(keydiff_cache_t *cache, const void *q, con
  * enqueues it (in the same launch when the shapes allow it, otherwise as a launch of its own
  * before it), so after the call `carry` has none.  Until its eviction is enqueued the rows of
  * `cache` are the n = len + Bt rows before compaction and its scratch buffer is in use: a
- * cache used this way needs a scratch buffer of its own.  The ORDERED layout does not defer:
- * there the call behaves like keydiff_prefill_block.  The scores and the retained set are those
+ * cache used this way needs a scratch buffer of its own.  In the ORDERED layout only the
+ * selection rides; the stable row shift of `carry` follows as a launch of its own, enqueued by
+ * the same call.  The scores and the retained set are those
  * of keydiff_prefill_block bit for bit; `out` may differ in the last bf16 bit, because the
  * keys are cut into a different number of ranges when passengers take part of the chip.    */
 KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const void *q, const void *k_new,

@@ -1078,7 +1078,7 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 bool can_carry(const StepParams &p, const StepParams &cy)
 {
     const int ncarry = cy.batch * cy.hkv;
-    return p.NW == 8 && p.psplits == p.splits && p.D == cy.D && cy.do_evict && cy.layout == 1 &&
+    return p.NW == 8 && p.psplits == p.splits && p.D == cy.D && cy.do_evict &&
            cy.n <= SPT_CARRY * CARRY_THREADS && cy.n <= 32 * CARRY_THREADS &&
            carry_shared_bytes() + post_lds_bytes(cy.n, cy.N) <= main_lds_bytes(p.D) && ncarry > 0;
 }

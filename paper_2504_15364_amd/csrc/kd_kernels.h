@@ -70,7 +70,8 @@ struct StepParams {
 hipError_t configure_kernels();      // one-time function attributes (dynamic LDS sizes)
 hipError_t launch_step_main(const StepParams &p, hipStream_t s);
 // step_main of `p` whose first workgroups run the selection and compaction `cy` describes (the
-// parameters of an earlier step of another cache, FILL layout); can_carry says whether the pair fits
+// parameters of an earlier step of another cache; for the ORDERED layout the caller still launches
+// the row shift afterwards); can_carry says whether the pair fits
 bool can_carry(const StepParams &p, const StepParams &cy);
 hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hipStream_t s);
 hipError_t launch_step_score(const StepParams &p, hipStream_t s);

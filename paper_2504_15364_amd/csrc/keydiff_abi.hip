@@ -244,15 +244,28 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
+// ORDERED layout: the stable row shift that follows a selection, by the destination map it wrote
+int compact_ordered(keydiff_cache *c, const kd::StepParams &p, hipStream_t s)
+{
+    ProfScope ps(c, KEYDIFF_K_COMPACT, s);
+    c->epoch = c->epoch == 0x7fffffff ? 1 : c->epoch + 1;
+    KD_LAUNCH(kd::launch_compact_ordered(p, reinterpret_cast<int32_t *>(c->meta + c->L.off_oflags), c->epoch, s),
+              "ordered compaction kernel");
+    return KEYDIFF_OK;
+}
+
 // the pending selection and compaction of `c` as a launch of its own
 int finish_pending(keydiff_cache *c, hipStream_t s)
 {
     if (!c->pending) return KEYDIFF_OK;
     kd::StepParams p = c->pend;
     p.merge_wgs = 0;
-    ProfScope ps(c, KEYDIFF_K_POST, s);
-    KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (deferred selection)");
+    {
+        ProfScope ps(c, KEYDIFF_K_POST, s);
+        KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (deferred selection)");
+    }
     c->pending = false;
+    if (c->cfg.layout == KEYDIFF_LAYOUT_ORDERED) return compact_ordered(c, p, s);
     return KEYDIFF_OK;
 }
 
@@ -308,7 +321,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
             KD_LAUNCH(kd::launch_step_main(p, s), "step_main kernel");
         }
     }
-    const bool deferred = defer && evict && cf.layout == KEYDIFF_LAYOUT_FILL;
+    const bool deferred = defer && evict;
     if (deferred) {
         if (p.merge_wgs > 0) {
             kd::StepParams pm = p;
@@ -323,12 +336,12 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
         ProfScope ps(c, KEYDIFF_K_POST, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
     }
-    if (evict && cf.layout == KEYDIFF_LAYOUT_ORDERED) {
-        ProfScope ps(c, KEYDIFF_K_COMPACT, s);
-        c->epoch = c->epoch == 0x7fffffff ? 1 : c->epoch + 1;
-        KD_LAUNCH(kd::launch_compact_ordered(p, reinterpret_cast<int32_t *>(c->meta + c->L.off_oflags), c->epoch, s),
-                  "ordered compaction kernel");
-    }
+    if (evict && !deferred && cf.layout == KEYDIFF_LAYOUT_ORDERED)
+        if (int rc = compact_ordered(c, p, s)) return rc;
+    // a selection that rode in this step's launch wrote its destination map: the rows of an ORDERED
+    // carrier's cache are shifted now, after this step's output is complete
+    if (riding && carry->cfg.layout == KEYDIFF_LAYOUT_ORDERED)
+        if (int rc = compact_ordered(carry, carry->pend, s)) return rc;
     if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
     c->kpar ^= 1;   // step_main wrote the new key sum into the other half
     c->len = evict ? N : n;

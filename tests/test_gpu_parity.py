@@ -344,12 +344,22 @@ def test_deferred_eviction_with_states_read_in_between():
 
 def test_deferred_eviction_where_nothing_can_ride():
     # with a single wave's worth of query rows per head the attention runs its alternating-waves mode,
-    # which has no carrying variant, and the ORDERED layout does not defer at all: both must give the
-    # plain call's results
+    # which has no carrying variant: every eviction is finished in a launch of its own, in both
+    # layouts, with the plain call's results
     w = get_config("llama32_3b").small(n_q_heads=4, n_kv_heads=2, head_dim=128, prompt_T=240)
     run_layers_deferred(w, 80, 8, 2, seeds=(46, 47), check_every=0, expect_ride=False, layout=kd.LAYOUT_FILL)
-    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=500)
-    run_layers_deferred(w, 200, 48, 2, seeds=(46, 47), check_every=2, expect_ride=None, layout=kd.LAYOUT_ORDERED)
+    run_layers_deferred(w, 80, 8, 2, seeds=(48, 49), check_every=0, expect_ride=False, layout=kd.LAYOUT_ORDERED)
+
+
+def test_deferred_eviction_ordered_layout_rides_and_shifts_afterwards():
+    # ORDERED layout: the selection rides in the next layer's attention launch, the stable row shift
+    # follows in a launch of its own; rows stay in position order (check_state reads them by row)
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1536)
+    run_layers_deferred(w, 768, 128, 3, seeds=(61, 62, 63), check_every=5, expect_ride=True, layout=kd.LAYOUT_ORDERED)
+    # ragged last block, helper-wave variant, unit-key anchor and window
+    w = get_config("llama32_3b").small(n_q_heads=6, n_kv_heads=2, head_dim=128, prompt_T=1100)
+    run_layers_deferred(w, 384, 128, 2, seeds=(64, 65), check_every=0, expect_ride=True, layout=kd.LAYOUT_ORDERED,
+                        anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY, window_W=32)
 
 
 def test_deferred_eviction_rides_a_launch_with_helper_waves():
