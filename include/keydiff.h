@@ -179,14 +179,16 @@ enum {
     KEYDIFF_K_MAIN = 0,    /* step_main: append + attention partials + key sum + cosine scores
                               (+ the carried selection of another cache, if any)               */
     KEYDIFF_K_SCORE = 1,   /* step_score: cosine scores outside a block step (keydiff_scores)  */
-    KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction (either half
-                              alone when the eviction is deferred or finished on its own)      */
+    KEYDIFF_K_POST = 2,    /* step_post: partial merge || selection and compaction of the step (the
+                              merge alone when the eviction is deferred)                       */
     KEYDIFF_K_COMPACT = 3, /* stable in-place row shift (ORDERED layout only)                  */
     KEYDIFF_K_AUX = 4,     /* cache load helpers                                               */
     KEYDIFF_K_EVENT_PAIR = 5, /* no kernel: an empty event pair recorded once per profiled block
                               step; its time is what the two records themselves add to every
                               class above, to be subtracted by the reader                      */
-    KEYDIFF_NKERNELS = 6
+    KEYDIFF_K_SELECT = 6,  /* step_post as the selection and compaction alone: a deferred eviction
+                              that no attention launch carried                                 */
+    KEYDIFF_NKERNELS = 7
 };
 KEYDIFF_API int keydiff_profile_enable(keydiff_cache_t *cache, int32_t enable);
 KEYDIFF_API int keydiff_profile_read(keydiff_cache_t *cache, float *ms_out, int32_t *launches_out);

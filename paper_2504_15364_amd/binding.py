@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libkeydiff.so")
 OK, EINVAL, ESHAPE, ESTATE, EHIP = 0, -1, -2, -3, -4
 ANCHOR_MEAN_KEY, ANCHOR_MEAN_UNIT_KEY = 0, 1
 LAYOUT_ORDERED, LAYOUT_FILL = 0, 1
-KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux", "event_pair")
+KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux", "event_pair", "select_alone")
 
 EXPORTS = (
     "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_deferred",

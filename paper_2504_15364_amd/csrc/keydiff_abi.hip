@@ -261,7 +261,7 @@ int finish_pending(keydiff_cache *c, hipStream_t s)
     kd::StepParams p = c->pend;
     p.merge_wgs = 0;
     {
-        ProfScope ps(c, KEYDIFF_K_POST, s);
+        ProfScope ps(c, KEYDIFF_K_SELECT, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (deferred selection)");
     }
     c->pending = false;

@@ -134,6 +134,6 @@ def test_llama31_8b_shape_deferred_eviction_across_layers():
         assert np.array_equal(K, oc.keys()) and np.array_equal(V, oc.values())
         assert cache.status() == 0
         cnt = cache.profile_read()
-        alone += cnt["step_post"][1] - cnt["step_main"][1]   # step_post launches beyond the one merge per step
+        alone += cnt["select_alone"][1]
         cache.close()
     assert alone == 1, f"{alone} evictions ran in a launch of their own; only the very last one should"

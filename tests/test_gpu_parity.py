@@ -315,18 +315,14 @@ def run_layers_deferred(w, N, B, nlayers, seeds, check_every, expect_ride, **kw)
     for c, _ in layers:
         c.close()
     if expect_ride is not None:
-        # step_post launches of a layer: one merge per block step with several key splits, plus one
-        # per eviction that did NOT ride (finished in a launch of its own)
-        merges = [cnt["step_main"][1] for cnt in counts]
-        posts = [cnt["step_post"][1] for cnt in counts]
-        alone = sum(p - m for p, m in zip(posts, merges))
+        alone = sum(cnt["select_alone"][1] for cnt in counts)   # evictions finished in a launch of their own
         if expect_ride:
             # only what the state checks and the end of the run forced out
             forced = nlayers * ((len(list(blocks(datas[0], B))) // check_every if check_every else 0) + 1)
-            assert 0 <= alone <= forced, (posts, merges, forced)
+            assert 0 <= alone <= forced, (alone, forced)
             assert evicting * nlayers - alone > 0, "no eviction rode along"
         else:
-            assert alone >= evicting * nlayers - nlayers, (posts, merges)
+            assert alone >= evicting * nlayers - nlayers, alone
 
 
 def test_deferred_eviction_rides_the_next_layers_attention():
