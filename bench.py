@@ -229,11 +229,11 @@ def main():
     deferred = args.eviction == "deferred" and L > 1
 
     def run_block(i):
+        if deferred:   # one call: layer l takes along the eviction layer l - 1 left pending (layer 0: the last layer's)
+            kd.prefill_block_layers(caches, [t[i] for t in dq], [t[i] for t in dk], [t[i] for t in dv], i * B, out=outs)
+            return
         for l in range(L):
-            if deferred:   # layer l takes along the eviction layer l - 1 left pending (layer 0: the last layer's)
-                caches[l].prefill_block_deferred(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l], carry=caches[l - 1])
-            else:
-                caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
+            caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
 
     def finish_all():   # the one eviction still pending belongs to the timed work
         if deferred:
@@ -377,7 +377,7 @@ def main():
         wq, wk, wv = ([to_blocks(f[x], B) for f in full] for x in ("q", "k", "v"))
         del full
         wcs = [kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=layout)) for _ in range(L)]
-        wout = torch.empty_like(wq[0][0])
+        wouts = [torch.empty_like(wq[0][0]) for _ in range(L)]
         nb = w.prompt_T // B
         empty_kv = torch.empty((w.batch, Hkv, 0, D), dtype=torch.bfloat16, device="cuda")
         empty_pos = torch.empty((w.batch, Hkv, 0), dtype=torch.int32, device="cuda")
@@ -387,11 +387,12 @@ def main():
             torch.cuda.synchronize()
             t_w = time.perf_counter()
             for b_ in range(nb):
+                if deferred:
+                    kd.prefill_block_layers(wcs, [t[b_] for t in wq], [t[b_] for t in wk], [t[b_] for t in wv], b_ * B,
+                                            out=wouts)
+                    continue
                 for l in range(L):
-                    if deferred:
-                        wcs[l].prefill_block_deferred(wq[l][b_], wk[l][b_], wv[l][b_], b_ * B, out=wout, carry=wcs[l - 1])
-                    else:
-                        wcs[l].prefill_block(wq[l][b_], wk[l][b_], wv[l][b_], b_ * B, out=wout)
+                    wcs[l].prefill_block(wq[l][b_], wk[l][b_], wv[l][b_], b_ * B, out=wouts[l])
             for wc in wcs:
                 wc.finish()
             torch.cuda.synchronize()

@@ -140,6 +140,21 @@ KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const voi
                                    const void *v_new, int32_t Bt, int64_t pos0, void *out,
                                    keydiff_cache_t *carry, void *stream);
 
+/* One block through every layer of a model (Eq. 5 applied per layer, Fig. 1's four steps in each):
+ * caches, q, k_new, v_new and out are host arrays of n_layers pointers, the tensors of layer l
+ * shaped as for keydiff_prefill_block; Bt and pos0 are the block's, the same in every layer.
+ * Equivalent to keydiff_prefill_block_deferred on layer 0, 1, ... in turn with the layer before it
+ * as `carry` (for layer 0 the last layer, whose eviction from the previous block is still
+ * pending): every layer's selection and compaction runs inside the next layer's attention
+ * launch, and the last layer's stays pending until the next block (or keydiff_finish, or any
+ * other call on that cache).  With n_layers == 1 nothing can be carried and the eviction is
+ * enqueued at the start of the next call on the cache.  All pointers are checked before
+ * anything is enqueued; an error met later (a state error of one layer) leaves the layers
+ * before it enqueued and returns that layer's code.  The caches must be distinct.          */
+KEYDIFF_API int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers,
+                                 const void *const *q, const void *const *k_new, const void *const *v_new,
+                                 int32_t Bt, int64_t pos0, void *const *out, void *stream);
+
 /* Enqueue the pending eviction of `cache` on `stream`, if it has one (else a no-op). */
 KEYDIFF_API int keydiff_finish(keydiff_cache_t *cache, void *stream);
 

@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     KeyDiffConfig,
     KeyDiffError,
     load_library,
+    prefill_block_layers,
 )

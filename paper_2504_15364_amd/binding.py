@@ -19,7 +19,7 @@ KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux"
 
 EXPORTS = (
     "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_deferred",
-    "keydiff_finish", "keydiff_decode_step",
+    "keydiff_prefill_block_layers", "keydiff_finish", "keydiff_decode_step",
     "keydiff_scores", "keydiff_cache_len", "keydiff_cache_positions", "keydiff_cache_load",
     "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
     "keydiff_last_error", "keydiff_version",
@@ -75,6 +75,8 @@ def load_library() -> C.CDLL:
     L.keydiff_init_cache.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, C.POINTER(vp)]
     L.keydiff_prefill_block.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     L.keydiff_prefill_block_deferred.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    pp = C.POINTER(vp)
+    L.keydiff_prefill_block_layers.argtypes = [pp, i32, pp, pp, pp, i32, i64, pp, vp]
     L.keydiff_finish.argtypes = [vp, vp]
     L.keydiff_decode_step.argtypes = [vp, vp, vp, vp, i64, vp, vp]
     L.keydiff_scores.argtypes = [vp, vp, vp]
@@ -113,6 +115,28 @@ def _stream_ptr(stream):
         import torch
         return torch.cuda.current_stream().cuda_stream
     return getattr(stream, "cuda_stream", stream)
+
+
+def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=None):
+    """One block through the layers of a model: `caches`, `q`, `k_new`, `v_new` (and `out`) are
+    sequences with one entry per layer; every layer's eviction rides in the next layer's launch."""
+    import torch
+    n = len(caches)
+    assert n >= 1 and len(q) == len(k_new) == len(v_new) == n
+    Bt = k_new[0].shape[-2]
+    for c, tq, tk, tv in zip(caches, q, k_new, v_new):
+        for t in (tq, tk, tv):
+            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == c.device
+        assert tk.shape[-2] == Bt
+    if out is None:
+        out = [torch.empty_like(t) for t in q]
+    arr = lambda ptrs: (C.c_void_p * n)(*ptrs)
+    L = caches[0]._L
+    _check(L.keydiff_prefill_block_layers(arr([c._h.value for c in caches]), n,
+                                          arr([t.data_ptr() for t in q]), arr([t.data_ptr() for t in k_new]),
+                                          arr([t.data_ptr() for t in v_new]), Bt, int(pos0),
+                                          arr([t.data_ptr() for t in out]), _stream_ptr(stream)))
+    return out
 
 
 class KeyDiffCache:

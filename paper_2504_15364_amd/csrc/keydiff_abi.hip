@@ -441,6 +441,27 @@ int keydiff_prefill_block_deferred(keydiff_cache_t *c, const void *q, const void
     return block_step(c, q, k_new, v_new, Bt, pos0, out, nullptr, true, carry, static_cast<hipStream_t>(stream));
 }
 
+int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q,
+                                 const void *const *k_new, const void *const *v_new, int32_t Bt, int64_t pos0,
+                                 void *const *out, void *stream)
+{
+    if (!caches || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (n_layers < 1) return fail(KEYDIFF_ESHAPE, "n_layers must be positive, got %d", n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        if (!caches[l] || !q[l] || !k_new[l] || !v_new[l] || !out[l])
+            return fail(KEYDIFF_EINVAL, "null pointer for layer %d", l);
+        for (int m = 0; m < l; ++m)
+            if (caches[m] == caches[l]) return fail(KEYDIFF_EINVAL, "layers %d and %d share a cache", m, l);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int l = 0; l < n_layers; ++l) {
+        // layer 0 takes along what the last layer left pending at the previous block
+        keydiff_cache *carry = n_layers > 1 ? caches[(l + n_layers - 1) % n_layers] : nullptr;
+        if (int rc = block_step(caches[l], q[l], k_new[l], v_new[l], Bt, pos0, out[l], nullptr, true, carry, s)) return rc;
+    }
+    return KEYDIFF_OK;
+}
+
 int keydiff_finish(keydiff_cache_t *c, void *stream)
 {
     if (!c) return fail(KEYDIFF_EINVAL, "null pointer");

@@ -52,3 +52,9 @@ def test_null_handles_are_rejected_before_anything_is_enqueued():
     assert lib.keydiff_prefill_block_deferred(None, None, None, None, 1, 0, None, None, None) == kd.EINVAL
     assert lib.keydiff_prefill_block(None, None, None, None, 1, 0, None, None, None) == kd.EINVAL
     assert b"null" in lib.keydiff_last_error()
+    import ctypes as C
+    none4 = (C.c_void_p * 4)()
+    assert lib.keydiff_prefill_block_layers(None, 4, none4, none4, none4, 1, 0, none4, None) == kd.EINVAL
+    assert lib.keydiff_prefill_block_layers(none4, 0, none4, none4, none4, 1, 0, none4, None) == kd.ESHAPE
+    assert lib.keydiff_prefill_block_layers(none4, 4, none4, none4, none4, 1, 0, none4, None) == kd.EINVAL
+    assert b"layer 0" in lib.keydiff_last_error()

@@ -358,6 +358,46 @@ def test_deferred_eviction_ordered_layout_rides_and_shifts_afterwards():
                         anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY, window_W=32)
 
 
+def test_block_through_all_layers_in_one_call():
+    # keydiff_prefill_block_layers: one call per block enqueues every layer, each carrying the one
+    # before it; layer 0 carries the last layer's eviction of the previous block
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1408)
+    N, B, nl = 640, 128, 4
+    layers = [make_pair(w, N, B, layout=kd.LAYOUT_FILL) for _ in range(nl)]
+    datas = [make_layer(w, seed=81 + l) for l in range(nl)]
+    caches = [c for c, _ in layers]
+    for c in caches:
+        c.profile_enable(True)
+    evicting = 0
+    for steps in zip(*(blocks(d, B) for d in datas)):
+        t = steps[0][0]
+        outs = kd.prefill_block_layers(caches, [to_dev(s[2]) for s in steps], [to_dev(s[3]) for s in steps],
+                                       [to_dev(s[4]) for s in steps], t)
+        for (cache, oc), (_, Bt, q, k, v), out in zip(layers, steps, outs):
+            ref, _, ev = oc.prefill_block(q, k, v, t)
+            err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+            assert err <= ATTN_ATOL, f"attention error {err} in block at token {t}"
+        evicting += int(ev > 0)
+    alone = 0
+    for li, (cache, oc) in enumerate(layers):
+        check_state(cache, oc, f"layer {li} at the end")
+        assert cache.status() == 0
+        alone += cache.profile_read()["select_alone"][1]
+        cache.close()
+    assert evicting > 2 and alone == 1, (evicting, alone)   # only the last layer's last eviction ran alone
+    # a single layer: nothing to carry, same results
+    (cache, oc), data = make_pair(w, N, B, layout=kd.LAYOUT_ORDERED), make_layer(w, seed=90)
+    for t, Bt, q, k, v in blocks(data, B):
+        out, = kd.prefill_block_layers([cache], [to_dev(q)], [to_dev(k)], [to_dev(v)], t)
+        ref, _, _ = oc.prefill_block(q, k, v, t)
+        assert float(np.abs(bf16_out_to_f32(out) - ref).max()) <= ATTN_ATOL
+    check_state(cache, oc, "single layer")
+    # argument errors are reported before anything is enqueued
+    with pytest.raises(kd.KeyDiffError):
+        kd.prefill_block_layers([cache, cache], [to_dev(q)] * 2, [to_dev(k)] * 2, [to_dev(v)] * 2, 0)
+    cache.close()
+
+
 def test_deferred_eviction_rides_a_launch_with_helper_waves():
     # G * B = 384 rows per KV head: 8-wave workgroups of which the second row tile fills only half,
     # so the attention runs its helper-wave variant; passengers ride in that one too
