@@ -39,11 +39,11 @@ class Workload:
 CONFIGS = {
     # correctness config: the oracle runs the whole prompt in seconds
     "toy": Workload("toy", 4, 1, 64, 1024, 32, 256),
-    "llama32_3b": Workload("llama32_3b", 24, 8, 128, 16384, 128, 4096, rope_theta=500000.0),
+    "llama32_3b": Workload("llama32_3b", 24, 8, 128, 16384, 128, 4096, n_layers=28, rope_theta=500000.0),
     # headline: timed per block step, summed over 32 layers with a fresh seed per layer
     "llama31_8b": Workload("llama31_8b", 32, 8, 128, 32768, 128, 8192, n_layers=32,
                            rope_theta=500000.0),
-    "qwen25_7b": Workload("qwen25_7b", 28, 4, 128, 32768, 256, 8192, rope_theta=1.0e6,
+    "qwen25_7b": Workload("qwen25_7b", 28, 4, 128, 32768, 256, 8192, n_layers=28, rope_theta=1.0e6,
                           outlier_p=0.01, outlier_scale=8.0, outlier_channels=4),
     "decode_8b": Workload("decode_8b", 32, 8, 128, 8192 + 1024, 1, 8192, batch=16,
                           rope_theta=500000.0, decode_steps=1024),
