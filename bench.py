@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--layers", type=int, default=0, help="0 = the workload's layer count")
+    ap.add_argument("--budget", type=int, default=0,
+                    help="cache budget N (a multiple of the block size); 0 = the workload's (the paper's budgets: 2K-8K)")
     ap.add_argument("--layout", choices=["fill", "ordered"], default="fill")
     ap.add_argument("--eviction", choices=["deferred", "immediate"], default="deferred",
                     help="deferred: the selection and compaction of layer l runs inside the attention launch "
@@ -196,6 +198,10 @@ def main():
     w = get_config(args.workload)
     if w.block_B == 1:
         return bench_decode(args, w)
+    if args.budget:
+        if args.budget % w.block_B or args.budget < w.block_B:
+            sys.exit(f"--budget must be a positive multiple of the block size {w.block_B}")
+        w = w.small(budget_N=args.budget, prompt_T=max(w.prompt_T, 4 * args.budget))
     L = args.layers or w.n_layers
     B, N, D, Hq, Hkv = w.block_B, w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads
     fill_blocks = N // B
