@@ -911,26 +911,8 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     }
 
     if (ntl > 0) step1(t, F_{}, F_{}, std::integral_constant<int, 0>{});
-    if (scoring) flush_scores();
 
-    if (small) {
-        if (tid < arows * UPR * 2) {
-            const int which = tid >= arows * UPR, rem = tid - which * arows * UPR;
-            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j0 + rem / UPR) * D + (rem % UPR) * 8) = aval;
-        }
-    } else {
-        for (int u = tid; u < arows * UPR * 2; u += NT) {
-            const int which = u >= arows * UPR, rem = u - which * arows * UPR;
-            const int j = j0 + rem / UPR, unit = rem % UPR;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
-            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
-        }
-    }
-    for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
-    // the key sum after this step, for step_post and for the next step
-    if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
-
-    // ---- output
+    // ---- output: stored first, so that the write latency runs under the score flush and the append
     if (active && p.psplits > 1) {
         // Partials leave in the accumulator's own layout, as whole 512-byte slabs with no detour
         // through LDS: slab (db, jj) of a 32-row block holds, for lane (h, l32), the four values
@@ -1003,6 +985,25 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             if (mbase + row < Mtot) *reinterpret_cast<u32x4 *>(gbase + (size_t)row * ROWB + unit * 16) = val;
         }
     }
+
+    if (small) {
+        if (tid < arows * UPR * 2) {
+            const int which = tid >= arows * UPR, rem = tid - which * arows * UPR;
+            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j0 + rem / UPR) * D + (rem % UPR) * 8) = aval;
+        }
+    } else {
+        for (int u = tid; u < arows * UPR * 2; u += NT) {
+            const int which = u >= arows * UPR, rem = u - which * arows * UPR;
+            const int j = j0 + rem / UPR, unit = rem % UPR;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>((which ? vnew : knew) + (size_t)j * D + unit * 8);
+            *reinterpret_cast<u32x4 *>((which ? p.v : p.k) + ((size_t)bh * p.cap + p.len + j) * D + unit * 8) = val;
+        }
+    }
+    for (int j = j0 + tid; j < j1; j += NT) p.pos[(size_t)bh * p.cap + p.len + j] = p.pos0 + j;
+    // the key sum after this step, for step_post and for the next step
+    if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
+
+    if (scoring) flush_scores();   // last: the square roots and divisions run while the stores above complete
 }
 
 template <int D, int NW, int NQ, bool HELP, bool ALT>
