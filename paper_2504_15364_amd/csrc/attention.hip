@@ -144,7 +144,12 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     __shared__ double st_dot[NW][64], st_k2[NW][64];
     __shared__ int st_row[NW][64];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: what follows from it (buffer pieces, roles, branches) is then
+    // scalar arithmetic and scalar branches instead of per-lane values and execution masks
+    // (not in the alternating mode, whose two roles the compiler then turns into two copies of the
+    // loop body and spills)
+    const int wave = ALT ? tid >> 6 : __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
     const int BH = p.batch * p.hkv;
     int id = block_id;
