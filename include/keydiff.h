@@ -26,6 +26,10 @@
  *   - Every call enqueues its kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = default stream) and returns without synchronising.  Calls on
  *     one handle must be issued in order on one stream.
+ *   - Every call reads and updates host-side state of the handle (the row count, which half of
+ *     the key-sum double buffer is current, a pending eviction) and bakes it into the launches:
+ *     replaying such launches from a captured HIP graph would run them with stale parameters and
+ *     is not supported.
  *   - Return value: KEYDIFF_OK (0) or a negative error.  Argument, shape and
  *     state errors are found before anything is enqueued and leave the cache
  *     unchanged; KEYDIFF_EHIP (a failed launch) may leave part of the step
