@@ -183,10 +183,16 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
 
 // The merge as a kernel of its own (a step whose eviction is deferred has nothing else to run
 // here): small workgroups, so that the rows spread over every compute unit.
+// Workgroup i takes head i % BH, like the workgroups of step_main: on a chip whose workgroups go
+// round-robin over the XCDs the partials of a head are then read on the XCD that wrote them.
 template <int D>
 __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(StepParams p)
 {
-    merge_rows<D>(p, (size_t)blockIdx.x * MERGE_THREADS + threadIdx.x);
+    const int BH = p.batch * p.hkv;
+    const size_t per_head = (size_t)((p.G * p.Bt + 31) / 32) * (D / 8) * 64;
+    const int bh = blockIdx.x % BH;
+    const size_t local = (size_t)(blockIdx.x / BH) * MERGE_THREADS + threadIdx.x;
+    if (local < per_head) merge_rows<D>(p, (size_t)bh * per_head + local);
 }
 
 // step_score: every workgroup scores SCORE_ROWS rows of one head.  The launch boundary after it
@@ -415,8 +421,8 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
     const int grid = (p.do_evict ? p.batch * p.hkv : 0) + p.merge_wgs;
     if (grid == 0) return hipSuccess;
     if (!p.do_evict) {   // merge only
-        const size_t threads = (size_t)p.batch * p.hkv * ((p.G * p.Bt + 31) / 32) * (p.D / 8) * 64;
-        const int mgrid = (int)((threads + MERGE_THREADS - 1) / MERGE_THREADS);
+        const size_t per_head = (size_t)((p.G * p.Bt + 31) / 32) * (p.D / 8) * 64;
+        const int mgrid = p.batch * p.hkv * (int)((per_head + MERGE_THREADS - 1) / MERGE_THREADS);
         if (p.D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);
         else if (p.D == 64) hipLaunchKernelGGL((merge_kernel<64>), dim3(mgrid), dim3(MERGE_THREADS), 0, s, p);
         else return hipErrorInvalidValue;
