@@ -97,7 +97,8 @@ def test_decode_8b_shape_batch16():
     assert cache.status() == 0
 
 
-def test_llama31_8b_shape_deferred_eviction_across_layers():
+@pytest.mark.parametrize("layout", [kd.LAYOUT_FILL, kd.LAYOUT_ORDERED], ids=["fill", "ordered"])
+def test_llama31_8b_shape_deferred_eviction_across_layers(layout):
     # the headline workload the way bench.py runs it by default: caches loaded at the budget, then
     # steady-state block steps through several layers, every layer's eviction carried by the next
     # layer's attention launch.  Attention is checked on sampled calls, the caches at the end.
@@ -107,7 +108,7 @@ def test_llama31_8b_shape_deferred_eviction_across_layers():
     layers = []
     for l in range(L):
         data = make_layer(w, seed=91, layer=l, t1=T)
-        cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=kd.LAYOUT_FILL))
+        cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=layout))
         oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B)
         K0 = data["k"][:N].transpose(1, 0, 2)[None].copy()
         V0 = data["v"][:N].transpose(1, 0, 2)[None].copy()
@@ -132,6 +133,8 @@ def test_llama31_8b_shape_deferred_eviction_across_layers():
         pos, K, V = rows_by_position(cache)   # finishes what is still pending (the last layer's last eviction)
         assert np.array_equal(pos, oc.positions()), f"retained set of layer {l} differs"
         assert np.array_equal(K, oc.keys()) and np.array_equal(V, oc.values())
+        if layout == kd.LAYOUT_ORDERED:
+            assert np.all(np.diff(cache.positions().cpu().numpy(), axis=-1) > 0), "rows not in position order"
         assert cache.status() == 0
         cnt = cache.profile_read()
         alone += cnt["select_alone"][1]
