@@ -43,9 +43,9 @@ SMALL = get_config("toy").small(n_q_heads=6, n_kv_heads=2, head_dim=16, prompt_T
 
 @pytest.mark.parametrize("B", [45, 16, 7, 1])
 def test_blockwise_attention_without_eviction_is_one_shot_causal_attention(B):
-    # "applying block prompt processing with B = T yields the same result as processing
-    # all of X at once"; with N >= T nothing is evicted, so this holds for every B,
-    # and B = 1 is the generation phase (Eq. 2).
+    # Background, block prompt processing: one block of the whole prompt (B = T) is one-shot
+    # processing; with N >= T nothing is evicted, so the same holds for every B, and B = 1 is
+    # the generation phase (Eq. 2).
     data = make_layer(SMALL, seed=3)
     ref = full_causal_reference(data["q"], data["k"], data["v"], SMALL.group)
     got, trace, _ = run_blocks(SMALL, data, B, N=64)
@@ -142,26 +142,85 @@ def test_each_step_keeps_the_brute_force_lowest_scores():
         assert np.array_equal(np.sort(rows_pos[order]), oc.positions()[0, 0])
 
 
-def test_budget_at_least_prompt_never_evicts_and_b1_equals_decode():
+def test_budget_at_least_prompt_never_evicts():
     w = get_config("toy").small(prompt_T=40, head_dim=16)
     data = make_layer(w, seed=31)
     _, trace, oc = run_blocks(w, data, 8, N=40)
     assert oc.len == 40 and all(ev == 0 for _, ev, _ in trace)
-    a = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, 4)
-    b = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, 4)
+    assert np.array_equal(oc.positions()[0, 0], np.arange(40))
+
+
+def test_decode_step_is_eq2_for_one_token_and_evicts_the_most_anchor_similar_key():
+    # B = 1 is the generation phase.  Every step is replayed by hand on a cache tracked in numpy:
+    # the new token attends to [K || k_new], [V || v_new] (Eq. 2) written with library calls, and
+    # once the budget is exceeded the one key with the highest cosine to the mean key leaves
+    # (full argsort by (score, position), last element).
+    w = get_config("toy").small(n_q_heads=4, n_kv_heads=2, head_dim=16, prompt_T=40)
+    G, N, d = 2, 12, 16
+    data = make_layer(w, seed=31)
+    oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, d, N, 1)
+    held = [np.zeros(0, np.int64) for _ in range(w.n_kv_heads)]     # positions cached per KV head
     for t in range(40):
-        args = (block_of(data["q"], t, 1)[None], block_of(data["k"], t, 1)[None], block_of(data["v"], t, 1)[None], t)
-        oa, _, _ = a.prefill_block(*args)
-        ob, _, _ = b.decode_step(*args)
-        assert np.array_equal(oa, ob)
-    assert np.array_equal(a.positions(), b.positions())
+        q, k, v = (block_of(data[x], t, 1)[None] for x in ("q", "k", "v"))
+        out, _, ev = oc.decode_step(q, k, v, t)
+        assert ev == (1 if t >= N else 0)
+        for g in range(w.n_kv_heads):
+            rows = np.concatenate([held[g], [t]])
+            Kd = torch.from_numpy(bf16_bits_to_f64(data["k"][rows, g]))
+            Vd = torch.from_numpy(bf16_bits_to_f64(data["v"][rows, g]))
+            for h in range(g * G, (g + 1) * G):
+                qd = torch.from_numpy(bf16_bits_to_f64(data["q"][t, h]))
+                ref = torch.softmax(Kd @ qd / np.sqrt(d), dim=0) @ Vd
+                assert np.allclose(out[0, h, 0], ref.numpy(), rtol=1e-6, atol=1e-7)
+            if len(rows) > N:
+                cos = torch.nn.functional.cosine_similarity(Kd.mean(0)[None], Kd, dim=1).numpy().astype(np.float32)
+                gone = np.lexsort((rows, cos))[-1]
+                rows = np.delete(rows, gone)
+            held[g] = rows
+            assert np.array_equal(oc.positions()[0, g], held[g])
 
 
-def test_teacher_forced_load_round_trip():
-    w = get_config("toy").small(prompt_T=96, head_dim=16)
+def test_scores_of_the_cache_are_the_cosine_to_the_mean_cached_key():
+    # several KV heads and a cache shorter than its capacity: a wrong head stride, or the capacity
+    # taken for the length, would move the rows the anchor and the scores are taken over
+    w = get_config("toy").small(n_q_heads=6, n_kv_heads=3, head_dim=16, prompt_T=96)
     data = make_layer(w, seed=41)
-    _, _, oc = run_blocks(w, data, 32, N=48)
+    _, _, oc = run_blocks(w, data, 32, N=48, with_q=False)
+    assert oc.len == 48 and oc.cap == 80
+    got = oc.scores()
+    assert got.shape == (1, 3, 48)
+    for g in range(3):
+        rows = oc.keys()[0, g]
+        assert np.array_equal(rows, data["k"][oc.positions()[0, g], g])
+        x = torch.from_numpy(bf16_bits_to_f64(rows))
+        cos = torch.nn.functional.cosine_similarity(x.mean(0)[None], x, dim=1).numpy()
+        assert np.allclose(got[0, g], cos, rtol=1e-6, atol=1e-7)
+        _, s32 = oracle.scores(rows)          # the free function, pinned on its own in test_oracle_scores
+        assert np.array_equal(got[0, g], s32)
+    # a cache still filling (len < N) scores exactly the rows it holds
+    oc_part = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, 48, 32)
+    oc_part.prefill_block(None, block_of(data["k"], 0, 20)[None], block_of(data["v"], 0, 20)[None], 0)
+    x = torch.from_numpy(bf16_bits_to_f64(data["k"][:20, 1]))
+    cos = torch.nn.functional.cosine_similarity(x.mean(0)[None], x, dim=1).numpy()
+    assert np.allclose(oc_part.scores()[0, 1], cos, rtol=1e-6, atol=1e-7)
+
+
+def test_teacher_forced_load_restores_rows_positions_and_the_next_step():
+    w = get_config("toy").small(prompt_T=128, head_dim=16)
+    data = make_layer(w, seed=41)
+    oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, 48, 32)
+    for t in range(0, 96, 32):
+        oc.prefill_block(None, block_of(data["k"], t, 32)[None], block_of(data["v"], t, 32)[None], t)
     oc2 = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, 48, 32)
     oc2.load(oc.keys(), oc.values(), oc.positions())
-    assert np.array_equal(oc2.keys(), oc.keys()) and np.array_equal(oc2.positions(), oc.positions())
-    assert np.array_equal(oc2.scores(), oc.scores())
+    pos = oc.positions()[0, 0]
+    assert oc2.len == 48 and np.array_equal(oc2.positions()[0, 0], pos)
+    assert np.array_equal(oc2.keys()[0, 0], data["k"][pos, 0]) and np.array_equal(oc2.values()[0, 0], data["v"][pos, 0])
+    # the step after the load, replayed by hand from the loaded rows
+    k, v = block_of(data["k"], 96, 32)[None], block_of(data["v"], 96, 32)[None]
+    oc2.prefill_block(None, k, v, 96)
+    rows = np.concatenate([pos, np.arange(96, 128)])
+    x = torch.from_numpy(bf16_bits_to_f64(data["k"][rows, 0]))
+    cos = torch.nn.functional.cosine_similarity(x.mean(0)[None], x, dim=1).numpy().astype(np.float32)
+    keep = np.sort(rows[np.lexsort((rows, cos))[:48]])
+    assert np.array_equal(oc2.positions()[0, 0], keep)
