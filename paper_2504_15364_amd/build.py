@@ -17,12 +17,19 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+TIMELINE_LIB = os.path.join(HERE, "libkeydiff_timeline.so")
+
+
+def build(verbose: bool = False, timeline: bool = False) -> str:
+    """timeline=True builds the profiling variant (libkeydiff_timeline.so, -DKD_TIMELINE: wall-clock stamps
+    inside step_main and the carried selection, read by `python -m paper_2504_15364_amd.timeline`)."""
     objs = []
     procs = []
+    extra = ["-DKD_TIMELINE"] if timeline else []
+    suffix = ".timeline.o" if timeline else ".o"
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(CSRC, src.replace(".hip", suffix))
+        cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -34,10 +41,11 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    lib = TIMELINE_LIB if timeline else LIB
+    link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(link, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, timeline="--timeline" in sys.argv))

@@ -143,6 +143,8 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // division that finish a score are long instruction sequences, run once per 64 rows this way
     __shared__ double st_dot[NW][64], st_k2[NW][64];
     __shared__ int st_row[NW][64];
+    KD_TL_DECL
+    KD_TL(0);
 
     const int tid = threadIdx.x, lane = tid & 63;
     // the wave index as a scalar: what follows from it (buffer pieces, roles, branches) is then
@@ -294,6 +296,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         }
     }
     if (ntl > 1) issue_tile(t0 + 1);
+    KD_TL(1);   // first two tiles and the queries requested
 
     // ---- anchor (Method, "Efficient Variant"): key sum after this step = key sum before it + the
     // block's keys.  Every workgroup that scores forms it by itself (the block is 32 KB in L2); one
@@ -339,10 +342,12 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         }
     };
     if (need_sum) block_rows(0);   // the first BPASS * BROWS rows: their loads fly with the queries
+    KD_TL(2);   // block rows summed (their loads have landed)
 
     // everything issued so far has landed: the queries go from LDS to registers (a wave reads only
     // what its own copies wrote)
     wait_copies<0>();
+    KD_TL(3);   // every copy of this wave has landed
 #pragma unroll
     for (int a = 0; a < NQ; ++a)
 #pragma unroll
@@ -366,6 +371,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         // (the per-wave sums are published by the barrier of the prologue below and added up after it)
     }
 
+    KD_TL(4);   // queries in registers, block sum folded
     f32x16 oacc[NQ][NDB];
     float mref[NQ], lrun[NQ][2];  // the row sum runs in two independent chains
 #pragma unroll
@@ -668,6 +674,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         // LDS; the staging buffers are free for tile t0 + 2, which flies while S^T of tile t0 is formed
         __syncthreads();
         static_assert(STAGES == 4, "the prologue fills three of the four ring buffers");
+        KD_TL(5);   // first barrier passed
         if (ntl > 2) issue_tile(t0 + 2);
         if (need_sum) {
             // the anchor: waves 0 .. D/64 - 1 form it while the others already work on tile t0
@@ -684,6 +691,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             sq = row_allreduce_f64<16>(sq);
             if ((lane & 15) == 0) red[wave][lane >> 4] = sq;
         }
+        KD_TL(6);   // anchor formed
         if (active && !(alt && wave == 1)) {   // (ALT: tile t0 is wave 0's; wave 1 starts with t0 + 1 inside the loop)
             qk_tile(smem + (size_t)(t0 % STAGES) * 2 * TILE_B, s);
             if (t0 >= tint) mask_tile(s, t0 * TILE_KEYS);
@@ -696,6 +704,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         // The anchor is complete before any row is scored: the barrier that opens the first step of
         // the loop publishes it; a range of a single tile has no such step.
         if (need_sum && ntl == 1) __syncthreads();
+        KD_TL(7);   // logits of the first tile ready: the loop starts
     }
     // ---- the tile loop, software pipelined by hand (at most two waves share a SIMD: little else
     // hides a latency).  Iteration t:
@@ -747,6 +756,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             else wait_copies<0>();
             __syncthreads();
         }
+#ifdef KD_TIMELINE
+        if (t == t0 + 2) KD_TL(16);   // step t0 + 2: barrier passed
+        if (t == t0 + 3) KD_TL(20);
+#endif
         if (HELP && !active) {
             if (NEXT) {
 #pragma unroll
@@ -836,6 +849,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 if (slot_of(g) == i) beat(g, arg, ex, pk);
             __builtin_amdgcn_sched_barrier(0);
         }
+#ifdef KD_TIMELINE
+        if (t == t0 + 2) KD_TL(17);   // stage A done
+        if (t == t0 + 3) KD_TL(21);
+#endif
         if (NEXT && MASKED) mask_tile(sn, (t + 1) * TILE_KEYS);
         float mch[NQ][2];  // max scan of tile t + 1 in two chains per block
 #pragma unroll
@@ -862,8 +879,16 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+#ifdef KD_TIMELINE
+        if (t == t0 + 2) KD_TL(18);   // stage B done
+        if (t == t0 + 3) KD_TL(22);
+#endif
         // tile t is still in its buffer (recycled in the next iteration): score its rows
         if (scoring && t % p.mtiles == mt) score_tile(t);
+#ifdef KD_TIMELINE
+        if (t == t0 + 2) KD_TL(19);   // tile scored (if this workgroup owns it)
+        if (t == t0 + 3) KD_TL(23);
+#endif
         float mloc[NQ];
 #pragma unroll
         for (int a = 0; a < NQ; ++a) mloc[a] = NEXT ? max3_raw(mch[a][0], mch[a][1], mch[a][0]) : 0.f;
@@ -902,6 +927,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         for (; t + 1 < tint; ++t) step1(t, T_{}, F_{}, std::integral_constant<int, 0>{});
     for (; t + 1 < t1; ++t) step1(t, T_{}, T_{}, std::integral_constant<int, 2>{});
 
+    KD_TL(8);   // all steps but the last done
     // ---- append (Eq. 5): this workgroup's slice of the block's rows.  The attention reads the
     // block straight from k_new / v_new, so nothing waits for the append: when the slice is small
     // its loads are issued here, fly during the last tile, and are stored after it.
@@ -916,6 +942,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     }
 
     if (ntl > 0) step1(t, F_{}, F_{}, std::integral_constant<int, 0>{});
+    KD_TL(9);   // last tile done
 
     // ---- output: stored first, so that the write latency runs under the score flush and the append
     if (active && p.psplits > 1) {
@@ -991,6 +1018,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         }
     }
 
+    KD_TL(10);  // output stores issued
     if (small) {
         if (tid < arows * UPR * 2) {
             const int which = tid >= arows * UPR, rem = tid - which * arows * UPR;
@@ -1009,6 +1037,16 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
 
     if (scoring) flush_scores();   // last: the square roots and divisions run while the stores above complete
+    KD_TL(11);  // append stored, scores flushed
+#ifdef KD_TIMELINE
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores of this wave have been acknowledged
+    KD_TL(12);
+    if (threadIdx.x == 0) {
+        kd_tl[30] = (unsigned long long)ntl;
+        kd_tl[31] = 1;   // record kind: attention workgroup
+    }
+    KD_TL_DUMP(p.timeline, blockIdx.x);
+#endif
 }
 
 template <int D, int NW, int NQ, bool HELP, bool ALT>
@@ -1098,11 +1136,15 @@ hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hip
     if (!can_carry(p, cy)) return hipErrorInvalidValue;
     const int ncarry = cy.batch * cy.hkv;
     const int grid = ncarry + p.batch * p.hkv * p.mtiles * p.splits;
+    StepParams cyl = cy;
+#ifdef KD_TIMELINE
+    cyl.timeline = p.timeline;   // one record per workgroup of the launch, passengers first
+#endif
     const size_t lds = main_lds_bytes(p.D);
     const bool help = main_runs_help(p);
 #define KD_GO(DD)                                                                                                   \
-    if (help) hipLaunchKernelGGL((step_main_carry_kernel<DD, true>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry); \
-    else hipLaunchKernelGGL((step_main_carry_kernel<DD, false>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cy, ncarry);
+    if (help) hipLaunchKernelGGL((step_main_carry_kernel<DD, true>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry); \
+    else hipLaunchKernelGGL((step_main_carry_kernel<DD, false>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry);
     if (p.D == 128) { KD_GO(128) }
     else if (p.D == 64) { KD_GO(64) }
 #undef KD_GO

@@ -3,6 +3,30 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Phase timeline (profiling build, -DKD_TIMELINE): thread 0 of a workgroup stamps the constant
+// 100 MHz wall clock into LDS at named points and the workgroup stores its 32 stamps at the end.
+// The product build compiles all of it away.
+#ifdef KD_TIMELINE
+#define KD_TL_DECL                                                  \
+    __shared__ unsigned long long kd_tl[32];                        \
+    if (threadIdx.x == 0) {                                         \
+        for (int i_ = 0; i_ < 32; ++i_) kd_tl[i_] = 0;              \
+    }
+#define KD_TL(i)                                                    \
+    do {                                                            \
+        if (threadIdx.x == 0) kd_tl[(i)] = wall_clock64();          \
+    } while (0)
+#define KD_TL_DUMP(dst, wg)                                                                      \
+    do {                                                                                         \
+        __syncthreads();                                                                         \
+        if ((dst) && threadIdx.x < 32) (dst)[(size_t)(wg) * 32 + threadIdx.x] = kd_tl[threadIdx.x]; \
+    } while (0)
+#else
+#define KD_TL_DECL
+#define KD_TL(i) do { } while (0)
+#define KD_TL_DUMP(dst, wg) do { } while (0)
+#endif
+
 namespace kd {
 
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }

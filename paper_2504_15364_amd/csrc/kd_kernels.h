@@ -65,6 +65,9 @@ struct StepParams {
     int32_t pos0, window_pos_min;
     float scale_log2e;
     double eps;
+#ifdef KD_TIMELINE
+    unsigned long long *timeline;    // [workgroup][32] wall-clock stamps of this launch (profiling build only)
+#endif
 };
 
 hipError_t configure_kernels();      // one-time function attributes (dynamic LDS sizes)

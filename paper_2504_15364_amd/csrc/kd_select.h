@@ -214,6 +214,14 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     int32_t *pos = p.pos + (size_t)bh * p.cap;
     uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     uint16_t *vb = p.v + (size_t)bh * p.cap * D;
+    KD_TL_DECL
+    KD_TL(0);
+#ifdef KD_TIMELINE
+    if (threadIdx.x == 0) kd_tl[31] = 2;   // record kind: selection workgroup
+#define KD_SEL_RETURN do { KD_TL(12); KD_TL_DUMP(p.timeline, blockIdx.x); return; } while (0)
+#else
+#define KD_SEL_RETURN return
+#endif
 
     // ---- 0. every load that does not depend on the selection is issued here, so that the chain
     // below costs one memory round trip now and one for the evicted rows later: the scores and
@@ -257,6 +265,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
     }
 
+    KD_TL(1);   // loads issued
     const int nwords = (p.n + 31) / 32;
     if (E == 1) {
         // ---- 1'. a single row to evict (the generation phase): the arg-max by (score bits, position)
@@ -332,10 +341,11 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             }
             __syncthreads();
             if (tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_old - sh.colsum[0][tid];
-            return;
+            KD_SEL_RETURN;
         }
     } else {
     // ---- 1. histogram of the non-exempt scores in LDS
+    KD_TL(2);
     for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
     for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
     if (tid == 0) {
@@ -353,6 +363,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     }
     __syncthreads();
 
+    KD_TL(3);   // scores arrived and binned
     // ---- 2. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
     uint32_t cnt[HIST_BINS / THREADS];
     uint32_t mine = 0;
@@ -380,6 +391,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     const int tb = sh.tb;
     const uint32_t need = sh.need;
 
+    KD_TL(4);   // threshold bin known
     // above the bin -> evicted, inside it -> candidate for the exact ranking
 #pragma unroll
     for (int k = 0; k < SPT; ++k) {
@@ -400,6 +412,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     __syncthreads();
     const uint32_t ncand = sh.ncand;
 
+    KD_TL(5);   // candidates collected
     // ---- 3. exact ranking inside the bin by (score bits, position), largest first: a wave takes a
     // candidate, its lanes compare it with 64 others at a time and count by ballot
     if (ncand <= CAND_MAX) {
@@ -427,6 +440,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     }
     }   // E > 1
 
+    KD_TL(6);   // ranking done: the eviction bitmap is final
     // ---- 4. ordered lists: thread t owns bitmap word t = rows [32 t, 32 t + 32)
     const int own0 = min(p.n, 32 * tid), own1 = min(p.n, own0 + 32);
     const uint32_t valid = own1 - own0 == 32 ? 0xFFFFFFFFu : ((1u << (own1 - own0)) - 1u);
@@ -446,7 +460,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     const bool sane = tot_ev == (uint32_t)E && nholes == nmov;
     if (!sane) {
         if (tid == 0) atomicOr(p.status, STATUS_SELECT_COUNT);
-        return;
+        KD_SEL_RETURN;
     }
     // evicted rows | holes (evicted rows below N) | movers (kept rows from N on) | rank of tail row N + r
     // among the movers (-1: evicted)
@@ -488,6 +502,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     }
     // (the ranks are first read after the barrier inside step 5)
 
+    KD_TL(7);   // lists written
     // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
     // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
     {
@@ -547,6 +562,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
     }
 
+    KD_TL(8);   // evicted rows read, key sum stored
     // ---- 6. compaction
     if (p.layout == 1) {
         // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N).  Rows from N
@@ -598,6 +614,12 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             }
         }
     }
+    KD_TL(9);   // moves issued
+#ifdef KD_TIMELINE
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    KD_SEL_RETURN;
+#endif
+#undef KD_SEL_RETURN
 }
 
 }  // namespace kd

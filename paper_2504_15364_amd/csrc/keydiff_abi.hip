@@ -31,9 +31,29 @@ struct Layout {
     size_t off_pos, off_ksum, off_status, off_oflags;                                 // in meta
     size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part;  // in scratch
     int cap, max_part_rows;
+    int target_wgs;   // bound used to size the partial buffers: twice the compute units of the chip
 };
 
-constexpr int kTargetWorkgroups = 512;   // bound used to size the partial buffers: twice the compute units of the chip
+// Compute units of the current device (one 8-wave attention workgroup runs per unit); 256, the
+// MI355X's count, where no device can be asked (sizing calls on a host without a GPU).
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
 int check_config(const keydiff_config_t *c)
 {
@@ -69,6 +89,8 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_oflags = off;  off += align256(BH * ((L.cap + kd::ORD_ROWS - 1) / kd::ORD_ROWS) * 4);  // ordered compaction
     L.meta_bytes = off;
     // split-KV partial rows: splits * BH * (G * Bt rounded up to 32) never exceeds this (see plan_attention)
+    const int kTargetWorkgroups = 2 * compute_units();
+    L.target_wgs = kTargetWorkgroups;
     const int max_mtiles = (G * c->block_B + 127) / 128;
     const size_t by_tiles = (kTargetWorkgroups + BH * max_mtiles + BH) * 256;
     const size_t Mpad_max = (size_t)((G * c->block_B + 31) / 32 * 32);                               // blocks of 32 rows
@@ -98,6 +120,7 @@ struct keydiff_cache {
     Layout L;
     uint16_t *k, *v;
     unsigned char *meta, *scratch;
+    int device;           // the device that was current when the handle was created
     int len;
     double eps;
     float scale_log2e;
@@ -155,7 +178,8 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 // Pointers and sizes every kernel of a step shares; the attention plan is filled in by plan_attention.
-kd::StepParams base_params(const keydiff_cache *c, int n)
+// `scratch`: the buffer the step's temporaries live in (the handle's own, or the static array)
+kd::StepParams base_params(const keydiff_cache *c, int n, unsigned char *scratch)
 {
     kd::StepParams p{};
     const keydiff_config_t &cf = c->cfg;
@@ -169,11 +193,11 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
         p.ksum_next = both + (size_t)(c->kpar ^ 1) * half;
     }
     p.status = reinterpret_cast<int32_t *>(c->meta + c->L.off_status);
-    p.part_o = reinterpret_cast<_Float16 *>(c->scratch + c->L.off_part_o);
-    p.part_ml = reinterpret_cast<float2 *>(c->scratch + c->L.off_part_ml);
-    p.scores = reinterpret_cast<float *>(c->scratch + c->L.off_scores);
-    p.dstmap = reinterpret_cast<int32_t *>(c->scratch + c->L.off_dstmap);
-    p.lists = reinterpret_cast<int32_t *>(c->scratch + c->L.off_lists);
+    p.part_o = reinterpret_cast<_Float16 *>(scratch + c->L.off_part_o);
+    p.part_ml = reinterpret_cast<float2 *>(scratch + c->L.off_part_ml);
+    p.scores = reinterpret_cast<float *>(scratch + c->L.off_scores);
+    p.dstmap = reinterpret_cast<int32_t *>(scratch + c->L.off_dstmap);
+    p.lists = reinterpret_cast<int32_t *>(scratch + c->L.off_lists);
     p.batch = cf.batch;
     p.hq = cf.n_q_heads;
     p.hkv = cf.n_kv_heads;
@@ -197,6 +221,19 @@ kd::StepParams base_params(const keydiff_cache *c, int n)
     return p;
 }
 
+#ifdef KD_TIMELINE
+// Profiling build: the caller lends a device buffer for the in-kernel wall-clock stamps; launch i of
+// step_main writes the records of its workgroups into slot i % slots (kTimelineWgs records of 32 words).
+constexpr int kTimelineWgs = 512;
+unsigned long long *g_tl_buf = nullptr;
+long g_tl_slots = 0, g_tl_count = 0;
+unsigned long long *timeline_slot()
+{
+    if (!g_tl_buf || g_tl_slots < 1) return nullptr;
+    return g_tl_buf + (size_t)(g_tl_count++ % g_tl_slots) * kTimelineWgs * 32;
+}
+#endif
+
 // M tiling (GQA-packed rows per KV head) and the number of key splits that fills the chip
 // `reserved`: compute units to leave to the workgroups of a carried selection
 void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
@@ -212,7 +249,7 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     const int TM = 32 * p.NW;
     p.mtiles = (Mtot + TM - 1) / TM;
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
-    const int target = kTargetWorkgroups / 2;   // the compute units of the chip
+    const int target = c->L.target_wgs / 2;   // the compute units of the chip
     // 8-wave workgroups run one per compute unit: rounding the split count up would push the last
     // workgroups into a second round that doubles the kernel's duration
     int splits = target / (BH * p.mtiles);
@@ -260,6 +297,9 @@ int finish_pending(keydiff_cache *c, hipStream_t s)
     if (!c->pending) return KEYDIFF_OK;
     kd::StepParams p = c->pend;
     p.merge_wgs = 0;
+#ifdef KD_TIMELINE
+    p.timeline = nullptr;   // only launches of step_main are recorded
+#endif
     {
         ProfScope ps(c, KEYDIFF_K_SELECT, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel (deferred selection)");
@@ -269,8 +309,11 @@ int finish_pending(keydiff_cache *c, hipStream_t s)
     return KEYDIFF_OK;
 }
 
+// `work`: the buffer for the step's temporaries -- the handle's scratch buffer, or the static array.
+// Every check and every planning decision comes before the first launch, so an argument, shape or
+// state error leaves nothing enqueued.
 int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v_new, int32_t Bt, int64_t pos0,
-               void *out, float *scores_out, bool defer, keydiff_cache *carry, hipStream_t s)
+               void *out, float *scores_out, bool defer, keydiff_cache *carry, unsigned char *work, hipStream_t s)
 {
     if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
     if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
@@ -283,10 +326,9 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     const bool contiguous = c->contiguous && (c->next_pos < 0 || c->next_pos == pos0);
     if (cf.window_W > 0 && n > N && !contiguous)
         return fail(KEYDIFF_ESTATE, "the sliding window needs consecutive token positions across calls");
-    if (int rc = finish_pending(c, s)) return rc;   // this step reads the compacted cache
 
     const bool evict = n > N;
-    kd::StepParams p = base_params(c, n);
+    kd::StepParams p = base_params(c, n, work);
     p.q = static_cast<const uint16_t *>(q);
     p.k_new = static_cast<const uint16_t *>(k_new);
     p.v_new = static_cast<const uint16_t *>(v_new);
@@ -301,17 +343,21 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
 
     // a passenger rides only if the attention still fits the chip in one round beside it
     bool riding = false;
-    if (carry && carry->pending) {
-        if (carry->pend_stream == s) {
-            const int seats = carry->cfg.batch * carry->cfg.n_kv_heads;
-            plan_attention(c, p, seats);
-            riding = kd::can_carry(p, carry->pend) &&
-                     p.batch * p.hkv * p.mtiles * p.splits + seats <= kTargetWorkgroups / 2;
-        }
-        if (!riding)
-            if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
+    if (carry && carry->pending && carry->pend_stream == s) {
+        const int seats = carry->cfg.batch * carry->cfg.n_kv_heads;
+        plan_attention(c, p, seats);
+        riding = kd::can_carry(p, carry->pend) &&
+                 p.batch * p.hkv * p.mtiles * p.splits + seats <= c->L.target_wgs / 2;
     }
     if (!riding) plan_attention(c, p);
+
+    // ---- launches from here on
+    if (int rc = finish_pending(c, s)) return rc;   // this step reads the compacted cache
+    if (carry && carry->pending && !riding)
+        if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
+#ifdef KD_TIMELINE
+    p.timeline = timeline_slot();
+#endif
     {
         ProfScope ps(c, KEYDIFF_K_MAIN, s);
         if (riding) {
@@ -386,6 +432,11 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->v = static_cast<uint16_t *>(v_cache);
     c->meta = static_cast<unsigned char *>(meta);
     c->scratch = static_cast<unsigned char *>(scratch);
+    c->device = -1;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return fail(KEYDIFF_EHIP, "no current device");
+    }
     c->len = 0;  // C_0 is empty
     c->eps = cfg->eps > 0.f ? (double)cfg->eps : 1e-8;
     const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
@@ -432,13 +483,17 @@ int keydiff_cache_len(const keydiff_cache_t *c, int32_t *len)
 int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
                           int64_t pos0, void *out, float *scores_out, void *stream)
 {
-    return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, static_cast<hipStream_t>(stream));
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, c->scratch,
+                      static_cast<hipStream_t>(stream));
 }
 
 int keydiff_prefill_block_deferred(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
                                    int64_t pos0, void *out, keydiff_cache_t *carry, void *stream)
 {
-    return block_step(c, q, k_new, v_new, Bt, pos0, out, nullptr, true, carry, static_cast<hipStream_t>(stream));
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, nullptr, true, carry, c->scratch,
+                      static_cast<hipStream_t>(stream));
 }
 
 int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q,
@@ -457,7 +512,9 @@ int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layer
     for (int l = 0; l < n_layers; ++l) {
         // layer 0 takes along what the last layer left pending at the previous block
         keydiff_cache *carry = n_layers > 1 ? caches[(l + n_layers - 1) % n_layers] : nullptr;
-        if (int rc = block_step(caches[l], q[l], k_new[l], v_new[l], Bt, pos0, out[l], nullptr, true, carry, s)) return rc;
+        if (int rc = block_step(caches[l], q[l], k_new[l], v_new[l], Bt, pos0, out[l], nullptr, true, carry,
+                                caches[l]->scratch, s))
+            return rc;
     }
     return KEYDIFF_OK;
 }
@@ -482,7 +539,7 @@ int keydiff_scores(const keydiff_cache_t *cc, float *scores_out, void *stream)
     keydiff_cache *c = const_cast<keydiff_cache *>(cc);  // scratch, profiling events, a pending eviction
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (int rc = finish_pending(c, s)) return rc;
-    kd::StepParams p = base_params(c, c->len);
+    kd::StepParams p = base_params(c, c->len, c->scratch);
     p.scores_out = scores_out;
     p.do_score = 1;
     p.do_evict = 0;
@@ -518,7 +575,7 @@ int keydiff_cache_load(keydiff_cache_t *c, const void *k, const void *v, const i
     KD_LAUNCH(kd::launch_load_pos(pos, reinterpret_cast<int32_t *>(c->meta + c->L.off_pos), BH, c->L.cap, len, 1, s),
               "cache load");
     {
-        kd::StepParams p = base_params(c, len);
+        kd::StepParams p = base_params(c, len, c->scratch);
         ProfScope ps(c, KEYDIFF_K_AUX, s);
         KD_LAUNCH(kd::launch_ksum_rebuild(p, reinterpret_cast<double *>(c->scratch + c->L.off_ksum_part), s),
                   "key sum rebuild");
@@ -569,5 +626,18 @@ int keydiff_profile_read(keydiff_cache_t *c, float *ms_out, int32_t *launches_ou
     c->events.clear();
     return KEYDIFF_OK;
 }
+
+#ifdef KD_TIMELINE
+// Profiling build only (not part of include/keydiff.h): buf is device memory of `bytes` bytes, zeroed by
+// the caller; returns the number of launch slots it holds.  Pass NULL to stop recording.
+KEYDIFF_API long keydiff_timeline_buffer(void *buf, size_t bytes)
+{
+    g_tl_buf = static_cast<unsigned long long *>(buf);
+    g_tl_slots = buf ? (long)(bytes / ((size_t)kTimelineWgs * 32 * 8)) : 0;
+    g_tl_count = 0;
+    return g_tl_slots;
+}
+KEYDIFF_API long keydiff_timeline_launches(void) { return g_tl_count; }
+#endif
 
 }  // extern "C"

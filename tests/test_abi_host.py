@@ -58,3 +58,4 @@ def test_null_handles_are_rejected_before_anything_is_enqueued():
     assert lib.keydiff_prefill_block_layers(none4, 0, none4, none4, none4, 1, 0, none4, None) == kd.ESHAPE
     assert lib.keydiff_prefill_block_layers(none4, 4, none4, none4, none4, 1, 0, none4, None) == kd.EINVAL
     assert b"layer 0" in lib.keydiff_last_error()
+

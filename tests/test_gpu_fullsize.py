@@ -23,14 +23,16 @@ def dev_blocks(bits, B):
     return t.view(T // B, B, H, d).permute(0, 2, 1, 3).contiguous().unsqueeze(1)
 
 
-def run_full(name, layout, T=None, attn_steps=(), seed=77, layer=0):
+def run_full(name, layout, T=None, attn_steps=(), seed=77, layer=0, **kw):
+    """The whole prompt of one layer through keydiff_prefill_block: retained sets against the oracle
+    after every step, attention on the steps named, K/V rows at the end.  kw: anchor_mode, window_W."""
     w = get_config(name)
     T = T or w.prompt_T
     B, N = w.block_B, w.budget_N
     data = make_layer(w, seed=seed, layer=layer, t1=T)
     dq, dk, dv = (dev_blocks(data[x], B) for x in ("q", "k", "v"))
-    cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=layout))
-    oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B)
+    cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=layout, **kw))
+    oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, **kw)
     nsteps = T // B
     attn_steps = {s % nsteps for s in attn_steps}
     evicting = 0
@@ -50,6 +52,8 @@ def run_full(name, layout, T=None, attn_steps=(), seed=77, layer=0):
     assert np.array_equal(K, oc.keys()) and np.array_equal(V, oc.values())
     assert cache.status() == 0
     assert evicting == nsteps - N // B
+    if layout == kd.LAYOUT_ORDERED:
+        assert np.all(np.diff(cache.positions().cpu().numpy(), axis=-1) > 0), "rows not in position order"
     cache.close()
 
 
@@ -58,43 +62,131 @@ def test_llama31_8b_shape_whole_prompt_fill_layout():
     run_full("llama31_8b", kd.LAYOUT_FILL, attn_steps=(3, 64, 255))
 
 
-def test_llama31_8b_shape_ordered_layout():
-    run_full("llama31_8b", kd.LAYOUT_ORDERED, T=8192 + 24 * 128, attn_steps=(-1,), layer=5)
+def test_llama31_8b_shape_whole_prompt_ordered_layout():
+    # the stable in-place layout over all 256 steps (192 of them shift rows)
+    run_full("llama31_8b", kd.LAYOUT_ORDERED, attn_steps=(100, -1), layer=5)
+
+
+def test_llama31_8b_shape_whole_prompt_sliding_window():
+    # Method, "KeyDiff with Sliding Window": 10 % of the budget reserved for the most recent tokens
+    run_full("llama31_8b", kd.LAYOUT_FILL, attn_steps=(200,), layer=2, window_W=819)
+
+
+def test_llama31_8b_shape_whole_prompt_unit_key_anchor():
+    # Eq. 7 as printed: the anchor is the mean of the unit keys
+    run_full("llama31_8b", kd.LAYOUT_FILL, attn_steps=(130,), layer=3, anchor_mode=kd.ANCHOR_MEAN_UNIT_KEY)
 
 
 def test_llama32_3b_shape_whole_prompt():
     run_full("llama32_3b", kd.LAYOUT_FILL, attn_steps=(40, 127))
 
 
-def test_qwen25_7b_shape():
-    # G = 7, B = 256, heavy channel outliers
-    run_full("qwen25_7b", kd.LAYOUT_FILL, T=8192 + 24 * 256, attn_steps=(31, -1))
+def test_qwen25_7b_shape_whole_prompt():
+    # G = 7, B = 256, heavy channel outliers: all 128 steps (96 evicting)
+    run_full("qwen25_7b", kd.LAYOUT_FILL, attn_steps=(31, 77, -1))
 
 
-def test_decode_8b_shape_batch16():
-    # full budget, batch of 16 sequences, one token and one eviction per step
+def test_decode_8b_shape_batch16_all_steps():
+    # full budget, batch of 16 sequences, one token and one eviction per sequence, head and step, for
+    # all 1024 steps.  The retained sets are compared after every step (the oracle runs the eviction
+    # trace without attention, one host thread per sequence: the sequences are independent); attention
+    # on sampled steps, where the oracle is in the bit-identical cache state.
+    from concurrent.futures import ThreadPoolExecutor
     w = get_config("decode_8b")
-    N, steps = w.budget_N, 32
-    seqs = [make_layer(w, seed=55, seq=s, t1=N + steps) for s in range(w.batch)]
-    cfg = kd.KeyDiffConfig(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, 1, layout=kd.LAYOUT_FILL)
-    cache = kd.KeyDiffCache(cfg)
-    oc = oracle.OracleCache(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, 1)
-    K0 = np.stack([s["k"][:N].transpose(1, 0, 2) for s in seqs])          # [batch][Hkv][N][d]
-    V0 = np.stack([s["v"][:N].transpose(1, 0, 2) for s in seqs])
-    P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (w.batch, w.n_kv_heads, N)).copy()
-    cache.load(to_dev(K0), to_dev(V0), torch.from_numpy(P0).cuda())
-    oc.load(K0, V0, P0)
-    for t in range(N, N + steps):
-        q, k, v = (np.stack([s[x][t][:, None, :] for s in seqs]) for x in ("q", "k", "v"))
-        out = cache.decode_step(to_dev(q), to_dev(k), to_dev(v), t)
-        ref, _, ev = oc.decode_step(q, k, v, t)
-        assert ev == 1
-        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
-        assert np.array_equal(np.sort(cache.positions().cpu().numpy(), axis=-1), oc.positions()), t
+    N, steps = w.budget_N, w.decode_steps
+    assert steps == 1024
+    sampled = {0, 1, 63, 200, 511, 777, 1000, 1023}
+    with ThreadPoolExecutor(16) as ex:
+        seqs = list(ex.map(lambda s: make_layer(w, seed=55, seq=s, t1=N + steps), range(w.batch)))
+        cfg = kd.KeyDiffConfig(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, 1, layout=kd.LAYOUT_FILL)
+        cache = kd.KeyDiffCache(cfg)
+        ocs = [oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, 1) for _ in range(w.batch)]
+        K0 = np.stack([s["k"][:N].transpose(1, 0, 2) for s in seqs])          # [batch][Hkv][N][d]
+        V0 = np.stack([s["v"][:N].transpose(1, 0, 2) for s in seqs])
+        P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (w.batch, w.n_kv_heads, N)).copy()
+        cache.load(to_dev(K0), to_dev(V0), torch.from_numpy(P0).cuda())
+        for b, oc in enumerate(ocs):
+            oc.load(K0[b:b + 1], V0[b:b + 1], P0[b:b + 1])
+        toks = {x: to_dev(np.stack([s[x][N:] for s in seqs]).transpose(1, 0, 2, 3)[:, :, :, None, :])
+                for x in ("q", "k", "v")}                                     # [step][batch][heads][1][d]
+        for i in range(steps):
+            t = N + i
+            out = cache.decode_step(toks["q"][i], toks["k"][i], toks["v"][i], t)
+            want = i in sampled
+
+            def one(b):
+                q, k, v = (seqs[b][x][t][None, :, None, :] for x in ("q", "k", "v"))
+                ref, _, ev = ocs[b].decode_step(q if want else None, k, v, t)
+                assert ev == 1
+                return ref, ocs[b].positions()[0]
+            res = list(ex.map(one, range(w.batch)))
+            got_pos = np.sort(cache.positions().cpu().numpy(), axis=-1)
+            assert np.array_equal(got_pos, np.stack([r[1] for r in res])), f"retained set differs after step {i}"
+            if want:
+                ref = np.concatenate([r[0] for r in res])
+                err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+                assert err <= ATTN_ATOL, f"attention error {err} at step {i}"
     got = cache.scores().cpu().numpy()
     order = np.argsort(cache.positions().cpu().numpy(), axis=-1, kind="stable")
-    assert np.allclose(np.take_along_axis(got, order, -1), oc.scores(), rtol=SCORE_RTOL, atol=SCORE_ATOL)
+    want_sc = np.concatenate([oc.scores() for oc in ocs])
+    assert np.allclose(np.take_along_axis(got, order, -1), want_sc, rtol=SCORE_RTOL, atol=SCORE_ATOL)
+    pos, K, V = rows_by_position(cache)
+    assert np.array_equal(K, np.concatenate([oc.keys() for oc in ocs]))
+    assert np.array_equal(V, np.concatenate([oc.values() for oc in ocs]))
     assert cache.status() == 0
+    cache.close()
+
+
+BENCH_SEED = 20250415 + 100 * 3     # bench.py: --seed + 100 * (config number) + layer
+
+
+def test_llama31_8b_shape_whole_prompt_through_the_layers_call_with_the_bench_seeds():
+    # What bench.py times, from empty caches over the whole prompt: keydiff_prefill_block_layers on
+    # the first four layers with the benchmark's own seeds, every layer's eviction carried by the
+    # next layer's attention launch.  Retained sets of layers 0-2 are compared with the oracle after
+    # every block (reading them forces nothing: their evictions have ridden already); the last
+    # layer's eviction is still pending after a call, and reading its positions would run it in a
+    # launch of its own, so it is read every 16th block and at the end -- both ways of finishing an
+    # eviction then occur.  Attention on sampled (block, layer) pairs.
+    from concurrent.futures import ThreadPoolExecutor
+    w = get_config("llama31_8b")
+    B, N, T, L = w.block_B, w.budget_N, w.prompt_T, 4
+    nb = T // B
+    with ThreadPoolExecutor(L) as ex:
+        layers = list(ex.map(lambda l: make_layer(w, seed=BENCH_SEED + l, layer=l, t1=T), range(L)))
+        caches = [kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=kd.LAYOUT_FILL))
+                  for _ in range(L)]
+        ocs = [oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B) for _ in range(L)]
+        dq, dk, dv = ([dev_blocks(d[x], B) for d in layers] for x in ("q", "k", "v"))
+        for c in caches:
+            c.profile_enable(True)
+        sampled = {(5, 0), (64, 1), (65, 3), (150, 2), (255, 0), (255, 3)}
+        for i in range(nb):
+            outs = kd.prefill_block_layers(caches, [t[i] for t in dq], [t[i] for t in dk], [t[i] for t in dv], i * B)
+
+            def one(l):
+                q = block_of(layers[l]["q"], i * B, B)[None] if (i, l) in sampled else None
+                ref, _, _ = ocs[l].prefill_block(q, block_of(layers[l]["k"], i * B, B)[None],
+                                                 block_of(layers[l]["v"], i * B, B)[None], i * B)
+                return ref
+            refs = list(ex.map(one, range(L)))
+            for l in range(L):
+                if refs[l] is not None:
+                    err = float(np.abs(bf16_out_to_f32(outs[l]) - refs[l]).max())
+                    assert err <= ATTN_ATOL, f"attention error {err}, block {i}, layer {l}"
+                if l < L - 1 or i % 16 == 15 or i == nb - 1:
+                    pos = np.sort(caches[l].positions().cpu().numpy(), axis=-1)
+                    assert np.array_equal(pos, ocs[l].positions()), f"retained set differs: block {i}, layer {l}"
+    rode = alone = 0
+    for l in range(L):
+        pos, K, V = rows_by_position(caches[l])
+        assert np.array_equal(pos, ocs[l].positions())
+        assert np.array_equal(K, ocs[l].keys()) and np.array_equal(V, ocs[l].values()), f"rows of layer {l} differ"
+        assert caches[l].status() == 0
+        alone += caches[l].profile_read()["select_alone"][1]
+        caches[l].close()
+    evicting = nb - N // B
+    assert alone == evicting // 16, f"{alone} evictions ran alone; expected the {evicting // 16} the test forced"
 
 
 @pytest.mark.parametrize("layout", [kd.LAYOUT_FILL, kd.LAYOUT_ORDERED], ids=["fill", "ordered"])

@@ -78,8 +78,8 @@ def test_ragged_shapes(layout, hq, hkv, d, N, B, T):
     run_prompt(w, data, N, B, layout=layout)
 
 
-def test_two_query_sets_per_wave_and_split_merge():
-    # G * B = 512 rows per KV head takes the 64-rows-per-wave kernel and several key splits
+def test_two_row_tiles_per_head_and_split_merge():
+    # G * B = 512 rows per KV head: two 256-row workgroup tiles per head and several key splits
     w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1536)
     data = make_layer(w, seed=5)
     run_prompt(w, data, 768, 128, layout=kd.LAYOUT_FILL)
