@@ -120,6 +120,25 @@ KEYDIFF_API int keydiff_prefill_block(keydiff_cache_t *cache, const void *q, con
                           const void *v_new, int32_t Bt, int64_t pos0, void *out,
                           float *scores_out, void *stream);
 
+/* keydiff_prefill_block for callers that must not allocate device memory and hold no scratch
+ * buffer of their own to lend (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the step's temporaries (attention partials, scores, selection lists,
+ * destination map) live in a static device array of KEYDIFF_STATIC_SCRATCH_BYTES inside the
+ * library instead of the handle's scratch buffer, which this call does not touch.  Each GPU holds
+ * its own copy of the array from library load until the process ends; its address on a GPU is
+ * looked up once, in the keydiff_init_cache that creates the first handle on that GPU.  Same
+ * arguments, results and errors as keydiff_prefill_block, plus KEYDIFF_ESHAPE when the handle's
+ * configuration needs more scratch than the array holds (every shape with
+ * keydiff_workspace_bytes' scratch_bytes <= KEYDIFF_STATIC_SCRATCH_BYTES fits).  The call makes no
+ * hipMalloc / hipFree and calls no allocating routine.  Nothing in the array has to start at
+ * zero: every word a step reads it has written before.  All handles on one GPU share the array,
+ * and it keeps the last call's contents: calls that overlap on one GPU (different streams or
+ * threads) race, so issue them in order on one stream.                                      */
+#define KEYDIFF_STATIC_SCRATCH_BYTES (40u << 20)
+KEYDIFF_API int keydiff_prefill_block_static(keydiff_cache_t *cache, const void *q, const void *k_new,
+                                 const void *v_new, int32_t Bt, int64_t pos0, void *out,
+                                 float *scores_out, void *stream);
+
 /* The block step of one layer of a model whose layers run one after the other, with its
  * eviction left pending.  Attention of layer l + 1 does not depend on the eviction of layer l
  * (Fig. 1: the eviction follows the attention; only the same layer's next block reads the

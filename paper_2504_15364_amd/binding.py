@@ -18,7 +18,8 @@ LAYOUT_ORDERED, LAYOUT_FILL = 0, 1
 KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux", "event_pair", "select_alone")
 
 EXPORTS = (
-    "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_deferred",
+    "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_static",
+    "keydiff_prefill_block_deferred",
     "keydiff_prefill_block_layers", "keydiff_finish", "keydiff_decode_step",
     "keydiff_scores", "keydiff_cache_len", "keydiff_cache_positions", "keydiff_cache_load",
     "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
@@ -74,6 +75,7 @@ def load_library() -> C.CDLL:
     L.keydiff_workspace_bytes.argtypes = [C.POINTER(_Config), szp, szp, szp, szp]
     L.keydiff_init_cache.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, C.POINTER(vp)]
     L.keydiff_prefill_block.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    L.keydiff_prefill_block_static.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     L.keydiff_prefill_block_deferred.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     pp = C.POINTER(vp)
     L.keydiff_prefill_block_layers.argtypes = [pp, i32, pp, pp, pp, i32, i64, pp, vp]
@@ -181,6 +183,19 @@ class KeyDiffCache:
                                              int(pos0), out.data_ptr(),
                                              scores_out.data_ptr() if scores_out is not None else None,
                                              _stream_ptr(stream)))
+        return out
+
+    def prefill_block_static(self, q, k_new, v_new, pos0: int, out, scores_out=None, stream=None):
+        """prefill_block with the step's temporaries in the library's static device array; `out` is
+        the caller's (this wrapper allocates nothing either)."""
+        import torch
+        Bt = k_new.shape[-2]
+        for t in (q, k_new, v_new, out):
+            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
+        _check(self._L.keydiff_prefill_block_static(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
+                                                    int(pos0), out.data_ptr(),
+                                                    scores_out.data_ptr() if scores_out is not None else None,
+                                                    _stream_ptr(stream)))
         return out
 
     def prefill_block_deferred(self, q, k_new, v_new, pos0: int, out=None, carry=None, stream=None):

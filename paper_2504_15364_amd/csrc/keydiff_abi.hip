@@ -55,6 +55,37 @@ int compute_units()
     return cached[dev];
 }
 
+// Scratch of keydiff_prefill_block_static: one array per GPU the library runs on, held until the process ends.
+// On the host the array's name only stands for the symbol; the memory is reached through the device
+// address hipGetSymbolAddress returns, looked up once per device (static_scratch_of).
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+
+// (No `used` attribute: the compiler gives the variable a symbol the runtime can look up because
+// host code below names it; emitted before that use is seen it stays local to the code object, and
+// hipGetSymbolAddress then aborts the process instead of returning an error.)
+static __device__ __align__(256) unsigned char scratch[KEYDIFF_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+unsigned char *g_static_scratch[kMaxDevices] = {};   // device address of `scratch` on each GPU, once known
+
+// device address of the static scratch array on `device`, which must be the current device
+int static_scratch_of(int device, unsigned char **out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(KEYDIFF_ESHAPE, "device index %d out of range", device);
+    if (!g_static_scratch[device]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(KEYDIFF_EHIP, "hipGetSymbolAddress(static scratch): %s", hipGetErrorString(e));
+        g_static_scratch[device] = static_cast<unsigned char *>(ptr);
+    }
+    *out = g_static_scratch[device];
+    return KEYDIFF_OK;
+}
+
 int check_config(const keydiff_config_t *c)
 {
     if (!c) return fail(KEYDIFF_EINVAL, "config is null");
@@ -437,6 +468,11 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
         delete c;
         return fail(KEYDIFF_EHIP, "no current device");
     }
+    {   // once per device, with that device current: where this GPU holds the static scratch array.
+        // A failed lookup only disables keydiff_prefill_block_static, which then reports it.
+        unsigned char *unused = nullptr;
+        (void)static_scratch_of(c->device, &unused);
+    }
     c->len = 0;  // C_0 is empty
     c->eps = cfg->eps > 0.f ? (double)cfg->eps : 1e-8;
     const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
@@ -485,6 +521,20 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
 {
     if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
     return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, c->scratch,
+                      static_cast<hipStream_t>(stream));
+}
+
+int keydiff_prefill_block_static(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
+                                 int64_t pos0, void *out, float *scores_out, void *stream)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    if (c->L.scratch_bytes > (size_t)KEYDIFF_STATIC_SCRATCH_BYTES)
+        return fail(KEYDIFF_ESHAPE, "this configuration needs %zu bytes of scratch; the static array holds %zu",
+                    c->L.scratch_bytes, (size_t)KEYDIFF_STATIC_SCRATCH_BYTES);
+    // the address was looked up when the handle was created, with its device current
+    unsigned char *work = c->device >= 0 && c->device < kMaxDevices ? g_static_scratch[c->device] : nullptr;
+    if (!work) return fail(KEYDIFF_ESTATE, "the static scratch array of device %d was not found at init", c->device);
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, work,
                       static_cast<hipStream_t>(stream));
 }
 

@@ -59,3 +59,22 @@ def test_null_handles_are_rejected_before_anything_is_enqueued():
     assert lib.keydiff_prefill_block_layers(none4, 4, none4, none4, none4, 1, 0, none4, None) == kd.EINVAL
     assert b"layer 0" in lib.keydiff_last_error()
 
+
+def test_static_scratch_array_is_visible_to_the_runtime(tmp_path):
+    # keydiff_prefill_block_static reaches its device array through hipGetSymbolAddress, which aborts
+    # the process when the code object holds the array as a local symbol: check the built object
+    import shutil
+    import subprocess
+    tools = "/opt/rocm/lib/llvm/bin"
+    obj = os.path.join(os.path.dirname(kd.LIB_PATH), "csrc", "keydiff_abi.o")
+    if not (os.path.exists(obj) and os.path.exists(f"{tools}/llvm-objdump") and os.path.exists(f"{tools}/llvm-readelf")):
+        pytest.skip("needs the built object and the LLVM binary tools")
+    work = tmp_path / "keydiff_abi.o"
+    shutil.copy(obj, work)
+    subprocess.run([f"{tools}/llvm-objdump", "--offloading", str(work)], check=True, capture_output=True, cwd=tmp_path)
+    device = [p for p in tmp_path.iterdir() if "gfx950" in p.name]
+    assert device, "no gfx950 code object in keydiff_abi.o"
+    syms = subprocess.run([f"{tools}/llvm-readelf", "--dyn-syms", "-W", str(device[0])], check=True,
+                          capture_output=True, text=True).stdout
+    rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch")]
+    assert rows and all(r[4] == "GLOBAL" and int(r[2]) == 40 << 20 for r in rows), syms
