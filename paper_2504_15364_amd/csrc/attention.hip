@@ -1062,23 +1062,30 @@ __global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
 // busy per head for about half as long as the attention keeps the others busy: launched this way
 // it costs no time of its own.  The two caches share nothing, so no ordering between the two
 // kinds of workgroup is needed.
+// cy_res: the passengers work on LDS copies of their head's scores and positions (the launch then
+// asks for the dynamic LDS that takes)
 template <int D, bool HELP>
-__global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepParams p, StepParams cy, int ncarry)
+__global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepParams p, StepParams cy, int ncarry, int cy_res)
 {
     if ((int)blockIdx.x < ncarry) {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
         PostShared &sh = *reinterpret_cast<PostShared *>(smem);
-        uint32_t *evbits = reinterpret_cast<uint32_t *>(smem + carry_shared_bytes());
-        const int bh = (int)blockIdx.x;
-        int32_t *lists = cy.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (cy.n + 31) / 32)
-                                         : cy.lists + (size_t)bh * 4 * cy.B;
-        select_and_compact<D, SPT_CARRY, CARRY_THREADS>(cy, sh, evbits, lists, bh);
+        unsigned char *dyn = smem + carry_shared_bytes();
+        if (cy_res) select_and_compact<D, true, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
+        else select_and_compact<D, false, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
         return;
     }
     step_main_body<D, 8, 1, HELP, false>(p, (int)blockIdx.x - ncarry);
 }
 
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
+// dynamic LDS the carrying kernel may ask for: what 160 KB per compute unit leaves next to the
+// static tables of the attention body (below 20 KB)
+constexpr size_t CARRY_DYN_MAX = 140 * 1024;
+static size_t carry_need(const StepParams &cy, bool resident)
+{
+    return carry_shared_bytes() + select_dyn_bytes(cy.n, cy.N, cy.cap, cy.lists_in_lds != 0, resident);
+}
 
 hipError_t configure_main_kernels()
 {
@@ -1093,10 +1100,15 @@ hipError_t configure_main_kernels()
     KD_SET((step_main_kernel<64, 8, 1, false, false>), 64)
     KD_SET((step_main_kernel<64, 8, 1, true, false>), 64)
     KD_SET((step_main_kernel<64, 8, 1, true, true>), 64)
-    KD_SET((step_main_carry_kernel<128, false>), 128)
-    KD_SET((step_main_carry_kernel<128, true>), 128)
-    KD_SET((step_main_carry_kernel<64, false>), 64)
-    KD_SET((step_main_carry_kernel<64, true>), 64)
+#undef KD_SET
+#define KD_SET(fn)                                                                                  \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                            (int)CARRY_DYN_MAX);                                                    \
+    if (e != hipSuccess) return e;
+    KD_SET((step_main_carry_kernel<128, false>))
+    KD_SET((step_main_carry_kernel<128, true>))
+    KD_SET((step_main_carry_kernel<64, false>))
+    KD_SET((step_main_carry_kernel<64, true>))
 #undef KD_SET
     return hipSuccess;
 }
@@ -1126,9 +1138,8 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
 bool can_carry(const StepParams &p, const StepParams &cy)
 {
     const int ncarry = cy.batch * cy.hkv;
-    return p.NW == 8 && p.psplits == p.splits && p.D == cy.D && cy.do_evict &&
-           cy.n <= SPT_CARRY * CARRY_THREADS && cy.n <= 32 * CARRY_THREADS &&
-           carry_shared_bytes() + post_lds_bytes(cy.n, cy.N) <= main_lds_bytes(p.D) && ncarry > 0;
+    return p.NW == 8 && p.psplits == p.splits && p.D == cy.D && cy.do_evict && cy.n <= 32 * CARRY_THREADS &&
+           carry_need(cy, false) <= CARRY_DYN_MAX && ncarry > 0;
 }
 
 hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hipStream_t s)
@@ -1140,11 +1151,13 @@ hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hip
 #ifdef KD_TIMELINE
     cyl.timeline = p.timeline;   // one record per workgroup of the launch, passengers first
 #endif
-    const size_t lds = main_lds_bytes(p.D);
+    const int res = carry_need(cy, true) <= CARRY_DYN_MAX ? 1 : 0;
+    const size_t need = carry_need(cy, res != 0);
+    const size_t lds = need > main_lds_bytes(p.D) ? need : main_lds_bytes(p.D);
     const bool help = main_runs_help(p);
 #define KD_GO(DD)                                                                                                   \
-    if (help) hipLaunchKernelGGL((step_main_carry_kernel<DD, true>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry); \
-    else hipLaunchKernelGGL((step_main_carry_kernel<DD, false>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry);
+    if (help) hipLaunchKernelGGL((step_main_carry_kernel<DD, true>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res); \
+    else hipLaunchKernelGGL((step_main_carry_kernel<DD, false>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res);
     if (p.D == 128) { KD_GO(128) }
     else if (p.D == 64) { KD_GO(64) }
 #undef KD_GO

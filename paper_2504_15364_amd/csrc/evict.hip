@@ -208,8 +208,9 @@ __global__ __launch_bounds__(SCORE_THREADS) void step_score_kernel(StepParams p)
 }
 
 // step_post: workgroups [0, BH) select and compact one head each (when this step evicts); the
-// rest merge the attention partials.
-template <int D, int SPT>
+// rest merge the attention partials.  RES: the selection works on LDS copies of the head's scores
+// and positions (they fit next to its other tables).
+template <int D, bool RES>
 __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -219,11 +220,7 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
         merge_rows<D>(p, (size_t)(blockIdx.x - n_select) * POST_THREADS + threadIdx.x);
         return;
     }
-    const int bh = blockIdx.x;
-    uint32_t *evbits = reinterpret_cast<uint32_t *>(smem_raw);
-    int32_t *lists = p.lists_in_lds ? reinterpret_cast<int32_t *>(evbits + (p.n + 31) / 32)
-                                    : p.lists + (size_t)bh * 4 * p.B;
-    select_and_compact<D, SPT, POST_THREADS>(p, sh, evbits, lists, bh);
+    select_and_compact<D, RES, POST_THREADS>(p, sh, smem_raw, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------- ordered compaction
@@ -381,11 +378,12 @@ constexpr size_t LISTS_LDS_MAX = 48 * 1024;
 
 bool lists_fit_lds(int n, int N) { return n > N && (size_t)(n - N) * 16 <= LISTS_LDS_MAX; }
 
-size_t post_lds_bytes(int n, int N)
+// dynamic LDS a step_post launch may ask for next to its static tables (160 KB per compute unit)
+constexpr size_t POST_DYN_MAX = 160 * 1024 - sizeof(PostShared) - 1024;
+
+static bool post_resident(const StepParams &p)
 {
-    size_t b = (size_t)((n + 31) / 32) * 4;
-    if (lists_fit_lds(n, N)) b += (size_t)(n - N) * 16;
-    return b + 16;
+    return select_dyn_bytes(p.n, p.N, p.cap, p.lists_in_lds != 0, true) <= POST_DYN_MAX;
 }
 
 
@@ -395,13 +393,13 @@ hipError_t configure_kernels()
 {
     hipError_t e = configure_main_kernels();
     if (e != hipSuccess) return e;
-    const int post_max = (int)(MAX_CAP / 8 + LISTS_LDS_MAX + 16);
-    const void *post_fns[] = {reinterpret_cast<const void *>(step_post_kernel<128, SPT_SMALL>),
-                              reinterpret_cast<const void *>(step_post_kernel<128, SPT_LARGE>),
-                              reinterpret_cast<const void *>(step_post_kernel<64, SPT_SMALL>),
-                              reinterpret_cast<const void *>(step_post_kernel<64, SPT_LARGE>)};
+    static_assert(MAX_CAP / 8 + LISTS_LDS_MAX + 16 <= POST_DYN_MAX, "the non-resident selection always fits");
+    const void *post_fns[] = {reinterpret_cast<const void *>(step_post_kernel<128, true>),
+                              reinterpret_cast<const void *>(step_post_kernel<128, false>),
+                              reinterpret_cast<const void *>(step_post_kernel<64, true>),
+                              reinterpret_cast<const void *>(step_post_kernel<64, false>)};
     for (const void *fn : post_fns) {
-        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, post_max);
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)POST_DYN_MAX);
         if (e != hipSuccess) return e;
     }
     return e;
@@ -428,12 +426,13 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
-    const size_t lds = post_lds_bytes(p.n, p.N);
-    const bool small = p.n <= SPT_SMALL * POST_THREADS;
-    if (p.D == 128 && small) hipLaunchKernelGGL((step_post_kernel<128, SPT_SMALL>), dim3(grid), dim3(POST_THREADS), lds, s, p);
-    else if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128, SPT_LARGE>), dim3(grid), dim3(POST_THREADS), lds, s, p);
-    else if (p.D == 64 && small) hipLaunchKernelGGL((step_post_kernel<64, SPT_SMALL>), dim3(grid), dim3(POST_THREADS), lds, s, p);
-    else if (p.D == 64) hipLaunchKernelGGL((step_post_kernel<64, SPT_LARGE>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    if (p.n > 32 * POST_THREADS) return hipErrorInvalidValue;   // a thread owns one word of the eviction bitmap
+    const bool res = post_resident(p);
+    const size_t lds = select_dyn_bytes(p.n, p.N, p.cap, p.lists_in_lds != 0, res);
+    if (p.D == 128 && res) hipLaunchKernelGGL((step_post_kernel<128, true>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128, false>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 64 && res) hipLaunchKernelGGL((step_post_kernel<64, true>), dim3(grid), dim3(POST_THREADS), lds, s, p);
+    else if (p.D == 64) hipLaunchKernelGGL((step_post_kernel<64, false>), dim3(grid), dim3(POST_THREADS), lds, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

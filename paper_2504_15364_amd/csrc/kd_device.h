@@ -29,6 +29,16 @@
 
 namespace kd {
 
+// Asynchronous 16-byte-per-lane copy global -> LDS (no registers).  `lds_base` is uniform over the
+// active lanes; lane i writes bytes [16 i, 16 i + 16) above it.  Issued through asm, so the compiler
+// does not count it: completion is awaited with an explicit s_waitcnt vmcnt (copies complete in
+// issue order, together with the wave's other loads).
+__device__ __forceinline__ void lds_copy16(uint32_t lds_base, const void *gaddr)
+{
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(gaddr) : "memory");
+}
+
 __device__ __forceinline__ double bf16_lo(uint32_t w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
 

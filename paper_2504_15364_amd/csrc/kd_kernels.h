@@ -88,7 +88,6 @@ hipError_t launch_load_rows(const uint16_t *src, uint16_t *dst, int BH, int cap,
 hipError_t launch_load_pos(const int32_t *src, int32_t *dst, int BH, int cap, int len, int to_cache,
                            hipStream_t s);
 
-size_t post_lds_bytes(int n, int N);
 bool lists_fit_lds(int n, int N);
 
 }  // namespace kd

@@ -2,10 +2,16 @@
 // the kernels that can run it: step_post (one workgroup of 1024 threads per head) and the variant of
 // step_main that carries another cache's pending eviction (workgroups of 512 threads).
 //
-// One workgroup loads the head's scores once, bins them into a 4096-bin LDS histogram (a monotone
-// map of the float), scans it for the bin that holds the E-th largest score, evicts everything
-// above that bin and ranks the few rows inside it exactly by (score bits, position): equal scores
-// keep the lower position.  It then compacts the cache and takes the evicted keys out of ksum.
+// One workgroup copies the head's scores and positions into LDS once (asynchronously, no registers),
+// bins the scores into a 4096-bin LDS histogram (a monotone map of the float), scans it for the bin
+// that holds the E-th largest score, evicts everything above that bin and ranks the few rows inside
+// it exactly by (score bits, position): equal scores keep the lower position.  It then compacts the
+// cache and takes the evicted keys out of ksum.
+//
+// The passes over the rows are short rolled loops over the LDS copy.  As a passenger the selection
+// runs on one compute unit per head, whose instruction cache nothing has warmed, while the
+// attention saturates the memory system: with the rows in registers and every pass unrolled
+// (25 KB of straight-line code) it spent most of its time waiting for its own instructions.
 #pragma once
 #include "kd_kernels.h"
 #include "kd_device.h"
@@ -18,13 +24,11 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int CAND_MAX = 2048;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
+constexpr int CAND_MAX = 1024;  // rows of the threshold bin ranked in LDS; more fall back to a radix select
 constexpr int MAX_SELECT_WAVES = POST_THREADS / 64;   // PostShared is laid out for the largest workgroup
 constexpr int TAIL_WORDS = 72;                      // bitmap words the tail rows [N, n) may span on the fast path
-constexpr int SPT_SMALL = 12;                       // scores per thread: caches of up to 12288 rows
-constexpr int SPT_LARGE = MAX_CAP / POST_THREADS;   // ... and up to the limit
 constexpr int CARRY_THREADS = 512;                  // workgroup size of the step_main variant that carries a selection
-constexpr int SPT_CARRY = 24;                       // ... which covers caches of up to 12288 rows as well
+constexpr int SELECT_TAILU = 8;                     // 16-byte units of the tail rows [N, n) a thread keeps in registers
 
 // float -> unsigned key with the same order
 __device__ __forceinline__ uint32_t orderable(float s)
@@ -117,7 +121,7 @@ __device__ __forceinline__ T block_exclusive_scan_t(T v, T *wave_tot, T *total)
 // ---------------------------------------------------- slow path: radix select in a bin
 // More than CAND_MAX rows share the threshold bin (near-identical keys).  MSB-first
 // 8-bit radix select over the 64-bit key (orderable score : position) restricted to
-// that bin; reads scores and positions from memory on every pass.  Marks the
+// that bin; reads scores and positions again on every pass.  Marks the
 // `need` largest in the evict bitmap.
 template <int THREADS>
 __device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const float *sc, const int32_t *pos,
@@ -196,24 +200,59 @@ __device__ void radix_select_in_bin(const StepParams &p, PostShared &sh, const f
     __syncthreads();
 }
 
+// bytes of dynamic LDS the selection of a step uses behind PostShared: the eviction bitmap, the
+// lists (when they fit) and, for the resident variant, the copies of the scores and positions
+__host__ __device__ inline size_t select_dyn_bytes(int n, int N, int cap, bool lists_in_lds, bool resident)
+{
+    size_t b = ((size_t)((n + 31) / 32) * 4 + 15) & ~(size_t)15;
+    if (lists_in_lds) b += (size_t)(n - N) * 16;
+    if (resident) b += (size_t)cap * 8;
+    return b;
+}
+
 // ------------------------------------------------------------- select + compaction
-// `lists` holds three arrays of E row indices (evicted | holes | movers): in LDS when
-// they fit, else in the scratch buffer.
-// SPT: scores per thread the instantiation can hold (n <= SPT * THREADS); the caller also keeps
-// n <= 32 * THREADS (a thread owns one word of the eviction bitmap)
-template <int D, int SPT, int THREADS>
-__device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t *evbits, int32_t *lists, int bh)
+// `dyn`: dynamic LDS of select_dyn_bytes(...) bytes, 16-byte aligned.  The lists are three arrays of
+// E row indices (evicted | holes | movers) and the mover rank of every tail row: in LDS when they
+// fit, else in the scratch buffer.
+// RES: the head's scores and positions are copied into LDS once and every pass reads the copy;
+// otherwise (caches too large for that) the passes read them from memory.
+// The caller keeps n <= 32 * THREADS (a thread owns one word of the eviction bitmap).
+template <int D, bool RES, int THREADS>
+__device__ void select_and_compact(const StepParams &p, PostShared &sh, unsigned char *dyn, int bh)
 {
     constexpr int UPR = D / 8;
-    // 16-byte units of the tail rows a thread keeps in registers (the large instantiation has none to spare)
-    constexpr int TAILU = SPT * THREADS < MAX_CAP ? 8 : 0;
+    constexpr int TAILU = SELECT_TAILU;
     constexpr int NWAVES = THREADS / 64;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = p.n - p.N;
-    const float *sc = p.scores + (size_t)bh * p.cap;
+    const float *sc_g = p.scores + (size_t)bh * p.cap;
     int32_t *pos = p.pos + (size_t)bh * p.cap;
     uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     uint16_t *vb = p.v + (size_t)bh * p.cap * D;
+    const int nwords = (p.n + 31) / 32;
+    uint32_t *evbits = reinterpret_cast<uint32_t *>(dyn);
+    size_t dyn_off = ((size_t)nwords * 4 + 15) & ~(size_t)15;
+    int32_t *lists = p.lists + (size_t)bh * 4 * p.B;
+    if (p.lists_in_lds) {
+        lists = reinterpret_cast<int32_t *>(dyn + dyn_off);
+        dyn_off += (size_t)E * 16;
+    }
+    float *sc_l = reinterpret_cast<float *>(dyn + dyn_off);
+    int32_t *pos_l = reinterpret_cast<int32_t *>(dyn + dyn_off + (size_t)p.cap * 4);
+    // what the passes read: the LDS copies (as LDS pointers, so that the loops use ds_read) or memory
+    typedef __attribute__((address_space(3))) const float lds_cf32;
+    typedef __attribute__((address_space(3))) const int32_t lds_ci32;
+    lds_cf32 *sc_s = (lds_cf32 *)sc_l;
+    lds_ci32 *pos_s = (lds_ci32 *)pos_l;
+    auto SC = [&](int i) -> float {
+        if constexpr (RES) return sc_s[i];
+        else return sc_g[i];
+    };
+    auto PS = [&](int i) -> int32_t {
+        if constexpr (RES) return pos_s[i];
+        else return pos[i];
+    };
     KD_TL_DECL
     KD_TL(0);
 #ifdef KD_TIMELINE
@@ -225,34 +264,21 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
 
     // ---- 0. every load that does not depend on the selection is issued here, so that the chain
     // below costs one memory round trip now and one for the evicted rows later: the scores and
-    // positions of all rows, the running key sum, and (FILL layout) the K/V rows [N, n), the only
-    // ones that can move.
-    // A thread takes groups of four consecutive rows (one 16-byte load each for scores and positions:
-    // the memory pipeline spends the same time on a wave's load whatever its width): slot k of a
-    // thread is row 4 ((k / 4) THREADS + tid) + k % 4.  The buffers hold a multiple of four rows.
-    static_assert(SPT % 4 == 0, "slots come in groups of four");
-    auto row_of = [&](int k) { return 4 * ((k >> 2) * THREADS + tid) + (k & 3); };
-    auto group_live = [&](int k) { return 4 * (k >> 2) * THREADS < p.n; };   // uniform: some thread has rows there
-    float sv[SPT];
-    int32_t sp[SPT];
-#pragma unroll
-    for (int g = 0; g < SPT / 4; ++g) {
-        const int r0 = 4 * (g * THREADS + tid);
-        f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
-        i32x4 p4 = {0, 0, 0, 0};
-        if (4 * g * THREADS < p.n && r0 < p.n) {
-            s4 = *reinterpret_cast<const f32x4 *>(sc + r0);
-            p4 = *reinterpret_cast<const i32x4 *>(pos + r0);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            sv[4 * g + j] = s4[j];
-            sp[4 * g + j] = p4[j];
+    // positions of all rows (asynchronous copies into LDS, 1 KB per wave and instruction; the buffers
+    // hold a multiple of four rows), the running key sum, and (FILL layout) the K/V rows [N, n), the
+    // only ones that can move, into registers.
+    if (RES) {
+        const int nchunks = (p.cap * 4 + 1023) / 1024;
+        for (int c = wave; c < 2 * nchunks; c += NWAVES) {      // wave uniform
+            const bool second = c >= nchunks;
+            const int w0 = (second ? c - nchunks : c) * 256 + 4 * lane;   // first of this lane's four words
+            const uint32_t dst = (uint32_t)(uintptr_t)(second ? (void *)pos_l : (void *)sc_l) + (uint32_t)(w0 - 4 * lane) * 4u;
+            if (w0 < p.cap) lds_copy16(dst, second ? (const void *)(pos + w0) : (const void *)(sc_g + w0));
         }
     }
     const double ksum_old = tid < D ? p.ksum_next[(size_t)bh * D + tid] : 0.0;  // the sum step_main just wrote
-    const bool tail_regs = TAILU > 0 && p.layout == 1 && 2 * E * UPR <= TAILU * THREADS;
-    u32x4 tailv[TAILU > 0 ? TAILU : 1];
+    const bool tail_regs = p.layout == 1 && 2 * E * UPR <= TAILU * THREADS;
+    u32x4 tailv[TAILU];
     if (tail_regs) {
 #pragma unroll
         for (int q = 0; q < TAILU; ++q) {
@@ -264,21 +290,29 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             }
         }
     }
-
+    for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
+    for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
+    if (tid == 0) {
+        sh.ncand = 0;
+        sh.nev = 0;
+        sh.tb = 0;
+        sh.need = 0;
+    }
     KD_TL(1);   // loads issued
-    const int nwords = (p.n + 31) / 32;
+    if (RES) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies have landed
+    __syncthreads();   // every wave's part of the copies; the cleared histogram and bitmap
+    KD_TL(2);   // scores and positions in LDS
+
     if (E == 1) {
         // ---- 1'. a single row to evict (the generation phase): the arg-max by (score bits, position)
         // replaces histogram, threshold and ranking
-        for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
         uint64_t best = 0;   // 0: no row (every real key is larger: orderable() of a finite score is > 0)
         int besti = -1;
-#pragma unroll
-        for (int k = 0; k < SPT; ++k) {
-            const int i = row_of(k);
-            if (!group_live(k)) break;
-            if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) {
-                const uint64_t key = ((uint64_t)orderable(sv[k]) << 32) | (uint32_t)sp[k];
+#pragma unroll 2
+        for (int i = tid; i < p.n; i += THREADS) {
+            const int32_t pi = PS(i);
+            if (!(p.window_W > 0 && pi >= p.window_pos_min)) {
+                const uint64_t key = ((uint64_t)orderable(SC(i)) << 32) | (uint32_t)pi;
                 if (key > best) {
                     best = key;
                     besti = i;
@@ -293,7 +327,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             wbest = o > wbest ? o : wbest;
         }
         if (lane == 0) sh.wave_tot64[wave] = wbest;
-        __syncthreads();   // also: the bitmap is clear
+        __syncthreads();
         uint64_t gbest = 0;
 #pragma unroll
         for (int w = 0; w < NWAVES; ++w) gbest = sh.wave_tot64[w] > gbest ? sh.wave_tot64[w] : gbest;
@@ -345,26 +379,13 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
     } else {
     // ---- 1. histogram of the non-exempt scores in LDS
-    KD_TL(2);
-    for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
-    for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
-    if (tid == 0) {
-        sh.ncand = 0;
-        sh.nev = 0;
-        sh.tb = 0;
-        sh.need = 0;
-    }
+#pragma unroll 2
+    for (int i = tid; i < p.n; i += THREADS)
+        if (!(p.window_W > 0 && PS(i) >= p.window_pos_min)) atomicAdd(&sh.hist[score_bin(SC(i))], 1u);
     __syncthreads();
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = row_of(k);
-        if (!group_live(k)) break;
-        if (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) atomicAdd(&sh.hist[score_bin(sv[k])], 1u);
-    }
-    __syncthreads();
+    KD_TL(3);   // scores binned
 
-    KD_TL(3);   // scores arrived and binned
-    // ---- 2. threshold bin: thread t owns the 4 bins below 4*(1023-t)+3, highest first
+    // ---- 2. threshold bin: thread t owns the HIST_BINS / THREADS bins below its top one, highest first
     uint32_t cnt[HIST_BINS / THREADS];
     uint32_t mine = 0;
     const int top = HIST_BINS - 1 - (HIST_BINS / THREADS) * tid;
@@ -390,42 +411,42 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
     __syncthreads();
     const int tb = sh.tb;
     const uint32_t need = sh.need;
-
     KD_TL(4);   // threshold bin known
+
     // above the bin -> evicted, inside it -> candidate for the exact ranking
-#pragma unroll
-    for (int k = 0; k < SPT; ++k) {
-        const int i = row_of(k);
-        if (!group_live(k)) break;
-        // bin of the row, -1 if it cannot be evicted (exempt or past the end)
-        const int sb = (i < p.n && !(p.window_W > 0 && sp[k] >= p.window_pos_min)) ? score_bin(sv[k]) : -1;
+#pragma unroll 2
+    for (int i = tid; i < p.n; i += THREADS) {
+        const int32_t pi = PS(i);
+        const float s = SC(i);
+        // bin of the row, -1 if it cannot be evicted (exempt)
+        const int sb = !(p.window_W > 0 && pi >= p.window_pos_min) ? score_bin(s) : -1;
         if (sb > tb) atomicOr(&evbits[i >> 5], 1u << (i & 31));
         else if (sb == tb) {
             const uint32_t c = atomicAdd(&sh.ncand, 1u);
             if (c < CAND_MAX) {
                 sh.cand_slot[c] = (uint32_t)i;
-                sh.cand_key[c] = orderable(sv[k]);
-                sh.cand_pos[c] = sp[k];
+                sh.cand_key[c] = orderable(s);
+                sh.cand_pos[c] = pi;
             }
         }
     }
     __syncthreads();
     const uint32_t ncand = sh.ncand;
-
     KD_TL(5);   // candidates collected
+
     // ---- 3. exact ranking inside the bin by (score bits, position), largest first: a wave takes a
     // candidate, its lanes compare it with 64 others at a time and count by ballot
     if (ncand <= CAND_MAX) {
         for (uint32_t c = wave; c < ncand; c += NWAVES) {   // uniform per wave
             const uint32_t key = sh.cand_key[c];
-            const int32_t ps = sh.cand_pos[c];
+            const int32_t cp = sh.cand_pos[c];
             uint32_t rank = 0;
             for (uint32_t o0 = 0; o0 < ncand; o0 += 64) {
                 const uint32_t o = o0 + lane;
                 bool gt = false;
                 if (o < ncand) {
                     const uint32_t ok = sh.cand_key[o];
-                    gt = (ok > key) || (ok == key && sh.cand_pos[o] > ps);
+                    gt = (ok > key) || (ok == key && sh.cand_pos[o] > cp);
                 }
                 rank += (uint32_t)__popcll(__ballot(gt));
             }
@@ -436,11 +457,11 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
         __syncthreads();
     } else {
-        radix_select_in_bin<THREADS>(p, sh, sc, pos, evbits, tb, need);
+        radix_select_in_bin<THREADS>(p, sh, RES ? sc_l : sc_g, RES ? pos_l : pos, evbits, tb, need);
     }
     }   // E > 1
-
     KD_TL(6);   // ranking done: the eviction bitmap is final
+
     // ---- 4. ordered lists: thread t owns bitmap word t = rows [32 t, 32 t + 32)
     const int own0 = min(p.n, 32 * tid), own1 = min(p.n, own0 + 32);
     const uint32_t valid = own1 - own0 == 32 ? 0xFFFFFFFFu : ((1u << (own1 - own0)) - 1u);
@@ -501,8 +522,8 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }   // an evicted tail row got its -1 above
     }
     // (the ranks are first read after the barrier inside step 5)
-
     KD_TL(7);   // lists written
+
     // ---- 5. take the evicted keys out of the running key sum (before rows are overwritten).
     // UPR lanes share an evicted row (16 bytes each); a wave holds 64/UPR rows at a time.
     {
@@ -561,8 +582,8 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
             p.ksum_next[(size_t)bh * D + tid] = ksum_old - s;
         }
     }
-
     KD_TL(8);   // evicted rows read, key sum stored
+
     // ---- 6. compaction
     if (p.layout == 1) {
         // FILL: k-th surviving row of [N, n) moves into the k-th evicted slot of [0, N).  Rows from N
@@ -590,26 +611,27 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, uint32_t
         }
         for (int r = tid; r < (int)nholes; r += THREADS) pos[holes[r]] = p.pos0 + (movers[r] - p.len);
     } else {
-        // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here
-        // (they were all read into registers at the start), the K/V rows by compact_ordered_kernel.
-        // Every thread handles the rows it loaded (groups of four consecutive rows: coalesced), with
-        // the evicted count before a row taken from the bitmap and the per-word counts of the scan.
-        uint32_t *word_base = sh.cand_slot;   // the candidate arrays are free by now; nwords <= CAND_MAX
+        // ORDERED: kept row i moves to i - (evicted rows before i); positions are compacted here, the
+        // K/V rows by compact_ordered_kernel.  The evicted count before a row comes from the bitmap
+        // and the per-word counts of the scan.  A position lands at or below the row it came from,
+        // and the rows are taken in ascending chunks: reading from the LDS copy nothing can be
+        // overwritten before it is read; reading from memory, a chunk is read, then (barrier) written.
+        uint32_t *word_base = sh.cand_slot;   // the candidate arrays are free by now
         static_assert(MAX_CAP / 32 <= CAND_MAX, "one count per bitmap word");
         if (tid < nwords) word_base[tid] = eb;
         __syncthreads();
         int32_t *dst = p.dstmap + (size_t)bh * p.cap;
-#pragma unroll
-        for (int k = 0; k < SPT; ++k) {
-            const int i = row_of(k);
-            if (!group_live(k)) break;
+        for (int i0 = 0; i0 < p.n; i0 += THREADS) {   // uniform
+            const int i = i0 + tid;
+            const int32_t pi = i < p.n ? PS(i) : 0;
+            if (!RES) __syncthreads();
             if (i < p.n) {
                 const uint32_t word = evbits[i >> 5], bit = (uint32_t)i & 31u;
                 if ((word >> bit) & 1u) dst[i] = -1;
                 else {
                     const int to = i - (int)(word_base[i >> 5] + (uint32_t)__popc(word & ((1u << bit) - 1u)));
                     dst[i] = to;
-                    pos[to] = sp[k];
+                    pos[to] = pi;
                 }
             }
         }
