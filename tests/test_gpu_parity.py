@@ -286,13 +286,13 @@ def test_largest_capacity():
 
 
 # ---- deferred eviction: the selection of one layer rides in the attention launch of the next ----
-def run_layers_deferred(w, N, B, nlayers, seeds, check_every, expect_ride, **kw):
+def run_layers_deferred(w, N, B, nlayers, seeds, check_every, expect_ride, datas=None, **kw):
     """Layers run in turn on every block, each carrying the pending eviction of the one before it
     (the first carries the last one's from the previous block).  Attention is checked on every
     call; the cache states every `check_every` blocks (reading a state finishes its pending
     eviction in a launch of its own) and at the end."""
     layers = [make_pair(w, N, B, **kw) for _ in range(nlayers)]
-    datas = [make_layer(w, seed=s) for s in seeds]
+    datas = datas or [make_layer(w, seed=s) for s in seeds]
     for c, _ in layers:
         c.profile_enable(True)
     evicting = 0
@@ -329,6 +329,30 @@ def test_deferred_eviction_rides_the_next_layers_attention():
     # G * B = 512 rows per KV head: 8-wave workgroups, several key splits, the carrying kernel
     w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1536)
     run_layers_deferred(w, 768, 128, 3, seeds=(41, 42, 43), check_every=0, expect_ride=True, layout=kd.LAYOUT_FILL)
+
+
+@pytest.mark.parametrize("N,B", [(448, 64), (1536, 64)], ids=["ranked-in-lds", "radix-select"])
+@pytest.mark.parametrize("layout", [kd.LAYOUT_FILL, kd.LAYOUT_ORDERED], ids=["fill", "ordered"])
+def test_deferred_eviction_of_nearly_identical_keys(N, B, layout):
+    # Keys that differ from one common vector in a single component by one bf16 step have scores
+    # 1e-8 .. 1e-6 apart, many of them equal once rounded to float (the position then decides): the
+    # threshold bin of the selection holds every row.  With 512 rows they fit its candidate table, with
+    # 1600 they take the radix select; the evictions ride in the next layer's attention launch.
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=N + 4 * B)
+    rng = np.random.default_rng(N)
+    datas = []
+    for seed in (71, 72):
+        data = make_layer(w, seed=seed)
+        base = np.linspace(-1.0, 2.0, w.head_dim, dtype=np.float32)
+        k = np.tile(base, (w.prompt_T, w.n_kv_heads, 1))
+        cols = rng.integers(0, w.head_dim, size=(w.prompt_T, w.n_kv_heads))
+        bits = f32_to_bf16_bits(k)
+        step = rng.integers(-1, 2, size=(w.prompt_T, w.n_kv_heads)).astype(np.int32)   # -1, 0 or +1 bf16 steps
+        tt, hh = np.meshgrid(np.arange(w.prompt_T), np.arange(w.n_kv_heads), indexing="ij")
+        bits[tt, hh, cols] = (bits[tt, hh, cols].astype(np.int32) + step).astype(np.uint16)
+        datas.append(dict(data, k=bits))
+    run_layers_deferred(w, N, B, 2, seeds=None, check_every=1, expect_ride=None, datas=datas, layout=layout)
+    run_layers_deferred(w, N, B, 2, seeds=None, check_every=0, expect_ride=True, datas=datas, layout=layout)
 
 
 def test_deferred_eviction_with_states_read_in_between():
