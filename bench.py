@@ -168,6 +168,53 @@ def bench_decode(args, w):
     }))
 
 
+def decode_record(args, steps=24, warmup=6):
+    """A short run of the generation phase (decode_8b: batch 16, N = 8192, B = 1) for the default line."""
+    import torch
+
+    import paper_2504_15364_amd as kd
+    w = get_config("decode_8b")
+    N, D, Hq, Hkv, batch = w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch
+    total = warmup + steps + 8
+    with ThreadPoolExecutor(min(16, os.cpu_count() or 1)) as ex:
+        seqs = list(ex.map(lambda s_: make_layer(w, seed=args.seed + 1000 * 5, seq=s_, t1=N + total), range(batch)))
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+    cache = kd.KeyDiffCache(kd.KeyDiffConfig(batch, Hq, Hkv, D, N, 1, layout=kd.LAYOUT_FILL))
+    K0 = np.stack([s_["k"][:N].transpose(1, 0, 2) for s_ in seqs])
+    V0 = np.stack([s_["v"][:N].transpose(1, 0, 2) for s_ in seqs])
+    P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (batch, Hkv, N)).copy()
+    cache.load(dev(K0), dev(V0), torch.from_numpy(P0).cuda())
+    toks = [tuple(dev(np.stack([s_[x][N + i][:, None, :] for s_ in seqs])) for x in ("q", "k", "v")) for i in range(total)]
+    out = torch.empty((batch, Hq, 1, D), dtype=torch.bfloat16, device="cuda")
+    i = 0
+    for _ in range(warmup):
+        cache.decode_step(*toks[i], N + i, out=out)
+        i += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        cache.decode_step(*toks[i], N + i, out=out)
+        i += 1
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    cache.profile_enable(True)
+    for _ in range(8):
+        cache.decode_step(*toks[i], N + i, out=out)
+        i += 1
+    torch.cuda.synchronize()
+    prof = {k: v[0] / v[1] * 1e3 for k, v in cache.profile_read().items() if v[1] and k != "event_pair"}
+    assert cache.status() == 0
+    cache.close()
+    kv_bytes = 2.0 * batch * Hkv * (N + 1) * D * 2
+    t_min_us = (kv_bytes + 2 * batch * Hq * D * 2 + batch * Hkv * (N + 1) * 4) / (PEAK_HBM_GBPS * 1e9) * 1e6
+    return {"workload": "decode_8b", "batch": batch, "budget_N": N, "steps": steps, "us_per_step": us,
+            "tokens_per_s_per_layer": batch / (us * 1e-6), "kv_bytes_per_step": kv_bytes,
+            "step_GBps": kv_bytes / us / 1e3, "frac_of_hbm_roofline": t_min_us / us,
+            "event_bracket_us": prof}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,9 +232,14 @@ def main():
     ap.add_argument("--seed", type=int, default=20250415)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
-    ap.add_argument("--whole-prompt", action="store_true",
-                    help="also time the whole prompt through every layer from empty caches (fill steps + evicting "
-                         "steps); off by default so that every launch of the default run is a steady-state one")
+    ap.add_argument("--no-whole-prompt", action="store_true",
+                    help="skip the whole-prompt run (every block of the prompt through every layer from empty "
+                         "caches: the fill steps and every evicting step)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the secondary measurements (the other eviction mode and row layout, the keydiff_scores "
+                         "pass, the decode step): with it, and --no-whole-prompt, every launch of the process is a "
+                         "steady-state block step of the headline mode -- what the rocprofv3 summaries are taken from")
+    ap.add_argument("--mode-steps", type=int, default=12, help="timed steps of each secondary mode")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain device copies of a known size (untimed), so that a rocprofv3 "
                          "--pmc run of this command holds the counter's reading for a known byte count")
@@ -206,7 +258,7 @@ def main():
     B, N, D, Hq, Hkv = w.block_B, w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads
     fill_blocks = N // B
     n_steps = args.warmup + args.steps + args.profile_steps
-    T_need = (fill_blocks + n_steps) * B
+    T_need = (fill_blocks + max(n_steps, 0 if args.no_extras else 7 + args.mode_steps)) * B
     if T_need > w.prompt_T:
         sys.exit(f"--warmup + --steps + --profile-steps = {n_steps} exceeds the {w.prompt_T // B - fill_blocks} "
                  f"evicting steps of a {w.prompt_T}-token prompt")
@@ -320,6 +372,82 @@ def main():
                    for k, v in tot.items() if v[1]}
     assert all(c.status() == 0 for c in caches)
 
+    # ---- secondary: the same steady-state steps with the eviction inside the step (keydiff_prefill_block,
+    # two launches per layer) and in the stable row layout, on fresh caches with the same data; the
+    # keydiff_scores pass over a full cache
+    plan = caches[0].plan()
+    modes, scores_pass, ordered_kernels = None, None, None
+    if not args.no_extras:
+        first = fill_blocks + args.warmup
+        def run_mode(lay, defer):
+            cs = [kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=lay)) for _ in range(L)]
+            for l in range(L):
+                load_first_N(cs[l], l)
+            def blk(i):
+                if defer and L > 1:
+                    kd.prefill_block_layers(cs, [t[i] for t in dq], [t[i] for t in dk], [t[i] for t in dv], i * B, out=outs)
+                else:
+                    for l in range(L):
+                        cs[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
+            for i in range(fill_blocks, fill_blocks + 3):
+                blk(i)
+            cs[L - 1].finish()
+            torch.cuda.synchronize()
+            t0_ = time.perf_counter()
+            for i in range(fill_blocks + 3, fill_blocks + 3 + args.mode_steps):
+                blk(i)
+            cs[L - 1].finish()
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0_) / (args.mode_steps * L) * 1e6
+            prof = None
+            if lay == kd.LAYOUT_ORDERED and defer:      # per-kernel times of the stable layout (HIP events)
+                for c in cs:
+                    c.profile_enable(True)
+                for i in range(fill_blocks + 3 + args.mode_steps, fill_blocks + 7 + args.mode_steps):
+                    blk(i)
+                cs[L - 1].finish()
+                torch.cuda.synchronize()
+                tot = {}
+                for c in cs:
+                    for name, (ms, cnt) in c.profile_read().items():
+                        a = tot.setdefault(name, [0.0, 0])
+                        a[0] += ms
+                        a[1] += cnt
+                pair = tot.pop("event_pair", [0.0, 0])
+                prof = {k: {"event_bracket_us": v[0] / v[1] * 1e3, "launches": v[1]} for k, v in tot.items() if v[1]}
+            assert all(c.status() == 0 for c in cs)
+            for c in cs:
+                c.close()
+            return us, prof
+        modes = {"deferred_fill": us_per_layer_step if deferred and args.layout == "fill" else None}
+        for key, lay, defer in (("deferred_fill", kd.LAYOUT_FILL, True), ("immediate_fill", kd.LAYOUT_FILL, False),
+                                ("deferred_ordered", kd.LAYOUT_ORDERED, True), ("immediate_ordered", kd.LAYOUT_ORDERED, False)):
+            if modes.get(key) is None:
+                modes[key], prof = run_mode(lay, defer)
+                if prof is not None:
+                    ordered_kernels = prof
+        modes = {k: {"us_per_layer_step": v, "tokens_per_s_per_layer": B / (v * 1e-6),
+                     "frac_of_step_roofline": None} for k, v in modes.items()}
+        # keydiff_scores on the caches of all layers in turn, back to back (each cache is at the budget:
+        # N rows of d bf16 per head in, a float per row out; 32 caches of 17 MB each, so the keys of a
+        # launch come from HBM, not from a cache that still holds them)
+        for c in caches:
+            c.scores()
+        torch.cuda.synchronize()
+        reps = 4
+        sc_out = torch.empty((w.batch, Hkv, N), dtype=torch.float32, device="cuda")
+        lib, stream_ptr = kd.load_library(), torch.cuda.current_stream().cuda_stream
+        calls = [(c._h, sc_out.data_ptr(), stream_ptr) for c in caches] * reps   # the bare C calls: the host must keep ahead
+        t0_ = time.perf_counter()
+        for a in calls:
+            lib.keydiff_scores(*a)
+        torch.cuda.synchronize()
+        sc_us = (time.perf_counter() - t0_) / (reps * L) * 1e6
+        sc_bytes = w.batch * Hkv * N * (D * 2 + 4)
+        scores_pass = {"kernel": "step_score_kernel", "bytes": sc_bytes, "us": sc_us,
+                       "GBps": sc_bytes / (sc_us * 1e-6) / 1e9, "frac_of_hbm_peak": sc_bytes / (sc_us * 1e-6) / 1e9 / PEAK_HBM_GBPS,
+                       "note": f"wall clock over {reps * L} back-to-back launches on {L} different caches (launch gaps included)"}
+
     # algorithmic work of one steady-state block step of one layer
     n = N + B
     flops_attn = 4.0 * Hq * B * D * (N + B / 2.0)
@@ -371,7 +499,7 @@ def main():
     # back to back from empty caches, through every layer with that layer's own data -- the order a
     # model runs them in (block by block, layer after layer)
     whole = None
-    if args.whole_prompt:
+    if not args.no_whole_prompt:
         for c in caches:
             c.close()
         del caches[:], dq[:], dk[:], dv[:]
@@ -410,6 +538,30 @@ def main():
         for wc in wcs:
             wc.close()
 
+    # the bandwidth-bound kernels of a step against the HBM peak (live HIP-event times; bytes per launch
+    # from the launch plan: `splits` partial outputs of Hq x B rows in fp16 + their (max, sum) pairs in,
+    # the merged rows out; the stable shift reads and writes the rows behind the first evicted one,
+    # here priced as every row of K and V)
+    hbm_kernels = {}
+    if plan[0] > 1 and "step_post" in kernels and deferred:
+        mb = plan[0] * Hq * B * (D * 2 + 8) + Hq * B * D * 2
+        us = kernels["step_post"]["avg_us"]
+        hbm_kernels["merge_kernel"] = {"bytes": mb, "us": us, "GBps": mb / us / 1e3,
+                                       "frac_of_hbm_peak": mb / us / 1e3 / PEAK_HBM_GBPS, "key_ranges": plan[0]}
+    if ordered_kernels and "compact_ordered" in ordered_kernels:
+        cb = 2 * 2 * Hkv * N * D * 2
+        us = ordered_kernels["compact_ordered"]["event_bracket_us"]
+        hbm_kernels["compact_ordered_kernel"] = {"bytes_upper_bound": cb, "event_bracket_us": us, "GBps": cb / us / 1e3,
+                                                 "frac_of_hbm_peak": cb / us / 1e3 / PEAK_HBM_GBPS}
+    if scores_pass:
+        hbm_kernels["step_score_kernel"] = scores_pass
+    if modes:
+        for v in modes.values():
+            v["frac_of_step_roofline"] = t_min / (v["us_per_layer_step"] * 1e-6)
+    decode = None
+    if not args.no_extras and w.name == "llama31_8b":
+        decode = decode_record(args)
+
     print(json.dumps({
         "metric": "prompt tokens/sec per layer (KeyDiff block prefill) at N=8K"
                   if N == 8192 else f"prompt tokens/sec per layer (KeyDiff block prefill) at N={N}",
@@ -423,7 +575,8 @@ def main():
         "us_per_layer_step": us_per_layer_step,
         "step_roofline": {"binding": "mfma" if flops_attn / 2.5e15 > bytes_step / 8e12 else "hbm",
                           "t_min_us": t_min * 1e6, "frac": step_frac, "flops": flops_attn, "bytes": bytes_step},
-        "roofline": roofline, "kernels": kernels, "whole_prompt": whole, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "modes": modes, "hbm_kernels": hbm_kernels,
+        "whole_prompt": whole, "decode": decode, "cpu_baseline": cpu,
     }))
 
 

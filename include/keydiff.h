@@ -35,7 +35,12 @@
  *     unchanged; KEYDIFF_EHIP (a failed launch) may leave part of the step
  *     enqueued and the handle must then be discarded.  keydiff_last_error()
  *     gives a thread-local message.  No exception crosses this boundary.
- *   - Inputs must be finite.  Scores are IEEE double arithmetic on the bf16
+ *   - Inputs must be finite, and values (v_new, and what keydiff_cache_load brings in) must not exceed
+ *     65504 in magnitude: where the keys of a step are cut into several ranges, the attention output
+ *     of each range travels as fp16, normalised by its own weight sum (so it is bounded by the largest
+ *     |v| it covers), before the ranges are merged; a larger value would become infinite there.  The
+ *     library does not check this.  Queries and keys have no such limit.
+ *   - Scores are IEEE double arithmetic on the bf16
  *     data rounded once to float; the eviction decision is taken on that float
  *     and ties keep the lower token position.
  */
@@ -193,6 +198,12 @@ KEYDIFF_API int keydiff_scores(const keydiff_cache_t *cache, float *scores_out, 
 
 /* Rows currently cached per (sequence, KV head); host value, no sync. */
 KEYDIFF_API int keydiff_cache_len(const keydiff_cache_t *cache, int32_t *len);
+
+/* How the last block step on `cache` was cut up for the chip (host values, no sync): plan_out[0] the
+ * number of key ranges (split-KV partials per output row the merge adds up; 1 = no merge launch),
+ * [1] workgroups of 256 query rows per KV head, [2] 64-key tiles of the step, [3] 1 if the step's
+ * launch carried another cache's pending eviction.  For byte and launch accounting by a benchmark.  */
+KEYDIFF_API int keydiff_cache_plan(const keydiff_cache_t *cache, int32_t plan_out[4]);
 
 /* Token position of every cached row: pos_out int32 [batch][n_kv_heads][len] (device). */
 KEYDIFF_API int keydiff_cache_positions(const keydiff_cache_t *cache, int32_t *pos_out, void *stream);

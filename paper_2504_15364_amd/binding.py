@@ -21,7 +21,7 @@ EXPORTS = (
     "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_static",
     "keydiff_prefill_block_deferred",
     "keydiff_prefill_block_layers", "keydiff_finish", "keydiff_decode_step",
-    "keydiff_scores", "keydiff_cache_len", "keydiff_cache_positions", "keydiff_cache_load",
+    "keydiff_scores", "keydiff_cache_len", "keydiff_cache_plan", "keydiff_cache_positions", "keydiff_cache_load",
     "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
     "keydiff_last_error", "keydiff_version",
 )
@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
     L.keydiff_decode_step.argtypes = [vp, vp, vp, vp, i64, vp, vp]
     L.keydiff_scores.argtypes = [vp, vp, vp]
     L.keydiff_cache_len.argtypes = [vp, C.POINTER(i32)]
+    L.keydiff_cache_plan.argtypes = [vp, C.POINTER(i32)]
     L.keydiff_cache_positions.argtypes = [vp, vp, vp]
     L.keydiff_cache_load.argtypes = [vp, vp, vp, vp, i32, vp]
     L.keydiff_cache_status.argtypes = [vp, C.POINTER(i32), vp]
@@ -234,6 +235,12 @@ class KeyDiffCache:
         n = C.c_int32()
         _check(self._L.keydiff_cache_len(self._h, C.byref(n)))
         return n.value
+
+    def plan(self):
+        """(key ranges, row tiles per head, key tiles, carried a passenger) of the last block step."""
+        out = (C.c_int32 * 4)()
+        _check(self._L.keydiff_cache_plan(self._h, out))
+        return tuple(out)
 
     def positions(self, stream=None):
         import torch

@@ -115,12 +115,16 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// NQ: 32-row query blocks per wave; every K / V fragment read from LDS feeds one MFMA per block.
+// A workgroup is NW = 8 waves of NQ = 1 block of 32 query rows each (two waves per SIMD: with one wave
+// of 64 rows per SIMD every vector, LDS and copy-issue latency lay open and the kernel was slower).
 // HELP: some waves of a workgroup may have no query row at all (few query rows: decode); such a
 // wave takes no part in the attention, it copies its share of every tile and scores rows.
-template <int D, int NW, int NQ, bool HELP, bool ALT>
+constexpr int MAIN_WAVES = 8;
+template <int D, bool HELP, bool ALT>
 __device__ __forceinline__ void step_main_body(const StepParams &p, const int block_id)
 {
+    constexpr int NW = MAIN_WAVES;   // waves per workgroup
+    constexpr int NQ = 1;            // 32-row query blocks per wave
     constexpr int NT = 64 * NW;   // threads
     constexpr int TM = 32 * NQ * NW;          // query rows per workgroup
     constexpr int UPR = D / 8;    // 16-byte units per K/V row
@@ -1049,10 +1053,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #endif
 }
 
-template <int D, int NW, int NQ, bool HELP, bool ALT>
-__global__ __launch_bounds__(64 * NW) void step_main_kernel(StepParams p)
+template <int D, bool HELP, bool ALT>
+__global__ __launch_bounds__(64 * MAIN_WAVES) void step_main_kernel(StepParams p)
 {
-    step_main_body<D, NW, NQ, HELP, ALT>(p, (int)blockIdx.x);
+    step_main_body<D, HELP, ALT>(p, (int)blockIdx.x);
 }
 
 // step_main with passengers (8-wave workgroups, with or without helper waves, not the alternating
@@ -1075,7 +1079,7 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepPara
         else select_and_compact<D, false, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
         return;
     }
-    step_main_body<D, 8, 1, HELP, false>(p, (int)blockIdx.x - ncarry);
+    step_main_body<D, HELP, false>(p, (int)blockIdx.x - ncarry);
 }
 
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
@@ -1094,12 +1098,12 @@ hipError_t configure_main_kernels()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             (int)main_lds_bytes(D));                                               \
     if (e != hipSuccess) return e;
-    KD_SET((step_main_kernel<128, 8, 1, false, false>), 128)
-    KD_SET((step_main_kernel<128, 8, 1, true, false>), 128)
-    KD_SET((step_main_kernel<128, 8, 1, true, true>), 128)
-    KD_SET((step_main_kernel<64, 8, 1, false, false>), 64)
-    KD_SET((step_main_kernel<64, 8, 1, true, false>), 64)
-    KD_SET((step_main_kernel<64, 8, 1, true, true>), 64)
+    KD_SET((step_main_kernel<128, false, false>), 128)
+    KD_SET((step_main_kernel<128, true, false>), 128)
+    KD_SET((step_main_kernel<128, true, true>), 128)
+    KD_SET((step_main_kernel<64, false, false>), 64)
+    KD_SET((step_main_kernel<64, true, false>), 64)
+    KD_SET((step_main_kernel<64, true, true>), 64)
 #undef KD_SET
 #define KD_SET(fn)                                                                                  \
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -1123,13 +1127,13 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s)
     const bool help = main_runs_help(p);
     const bool alt = p.psplits != p.splits;   // two waves share the key tiles: planned only for 8-wave helper launches
     if (alt && !(help && p.NW == 8 && p.psplits == 2 * p.splits)) return hipErrorInvalidValue;
-#define KD_GO(DD, WW)                                                                                          \
-    if (help) hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, true, false>), dim3(grid), dim3(64 * WW), lds, s, p);  \
-    else hipLaunchKernelGGL((step_main_kernel<DD, WW, 1, false, false>), dim3(grid), dim3(64 * WW), lds, s, p);
-    if (alt && p.D == 128) hipLaunchKernelGGL((step_main_kernel<128, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
-    else if (alt && p.D == 64) hipLaunchKernelGGL((step_main_kernel<64, 8, 1, true, true>), dim3(grid), dim3(512), lds, s, p);
-    else if (p.D == 128 && p.NW == 8) { KD_GO(128, 8) }
-    else if (p.D == 64 && p.NW == 8) { KD_GO(64, 8) }
+#define KD_GO(DD)                                                                                          \
+    if (help) hipLaunchKernelGGL((step_main_kernel<DD, true, false>), dim3(grid), dim3(64 * MAIN_WAVES), lds, s, p);  \
+    else hipLaunchKernelGGL((step_main_kernel<DD, false, false>), dim3(grid), dim3(64 * MAIN_WAVES), lds, s, p);
+    if (alt && p.D == 128) hipLaunchKernelGGL((step_main_kernel<128, true, true>), dim3(grid), dim3(512), lds, s, p);
+    else if (alt && p.D == 64) hipLaunchKernelGGL((step_main_kernel<64, true, true>), dim3(grid), dim3(512), lds, s, p);
+    else if (p.D == 128 && p.NW == MAIN_WAVES) { KD_GO(128) }
+    else if (p.D == 64 && p.NW == MAIN_WAVES) { KD_GO(64) }
 #undef KD_GO
     else return hipErrorInvalidValue;
     return hipGetLastError();

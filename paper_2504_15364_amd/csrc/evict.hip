@@ -29,31 +29,32 @@ struct ScoreShared {
     double k2[SCORE_WAVES][64];
 };
 
-// Rows [row0, row1) of head bh.  D/8 lanes share a row (one 16-byte unit each); a wave takes 64
-// consecutive rows per round, stages (mu.k, |k|^2) of each row in LDS and then lane i finishes
-// row i of the round.
+// Rows [row0, row1) of head bh (at most SCORE_ROWS), scored against the anchor ksum / n.  D/8 lanes
+// share a row (one 16-byte unit each); a wave takes SCORE_ROWS / SCORE_WAVES consecutive rows, stages
+// (mu.k, |k|^2) of each row in LDS and then lane i finishes row i of them.  Small row counts per wave
+// and two waves per SIMD: the pass is one memory round trip plus a chain of double-precision
+// arithmetic, and what hides either is other waves.
 template <int D>
 __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh, int bh, int row0, int row1)
 {
     constexpr int UPR = D / 8;
-    constexpr int RPW = 64 / UPR;  // rows per wave per pass
+    constexpr int RPW = 64 / UPR;                   // rows per wave per pass
+    constexpr int WROWS = SCORE_ROWS / SCORE_WAVES; // rows per wave
+    constexpr int NP = WROWS / RPW;                 // passes per wave
+    static_assert(NP >= 2 && NP % 2 == 0 && WROWS <= 64, "a wave takes an even number of passes and at most 64 rows");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int u = lane % UPR, rl = lane / UPR;
     const uint16_t *kb = p.k + (size_t)bh * p.cap * D;
-    // the rows of the first round are requested before the anchor is formed: the two memory
-    // round trips (key sum, rows) then overlap
-    auto load_round = [&](int base, u32x4 (&w)[UPR]) {
+    // the rows are requested before the anchor is formed: the two memory round trips (key sum, rows) overlap
+    const int base = row0 + wave * WROWS;
+    u32x4 w[NP];
 #pragma unroll
-        for (int ps = 0; ps < UPR; ++ps) {
-            const int row = base + ps * RPW + rl;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (row < row1) z = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
-            w[ps] = z;
-        }
-    };
-    const int base0 = row0 + wave * 64;
-    u32x4 w[UPR];
-    load_round(base0, w);
+    for (int ps = 0; ps < NP; ++ps) {
+        const int row = base + ps * RPW + rl;
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (row < row1) z = *reinterpret_cast<const u32x4 *>(kb + (size_t)row * D + u * 8);
+        w[ps] = z;
+    }
     // anchor = ksum / n (Method, "Efficient Variant"); |mu| by a fixed-shape reduction
     double m = 0.0;
     if (tid < D) {
@@ -67,26 +68,47 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
     __syncthreads();
     double mu2 = 0.0;
 #pragma unroll
-    for (int w = 0; w < SCORE_WAVES; ++w) mu2 += sh.red[w];
+    for (int wv = 0; wv < SCORE_WAVES; ++wv) mu2 += sh.red[wv];
     const double nmu = sqrt(mu2);
 
     double mreg[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) mreg[i] = sh.mu[u * 8 + i];
-    // a round = 64 rows per wave; rounds are spread over the waves
-    for (int base = base0; base < row1; base += SCORE_WAVES * 64) {
-        if (base != base0) load_round(base, w);  // the round's loads are issued together
+    // products of two bf16 values are exact in double, so fma(a, a, .) is the plain sum of squares;
+    // mu.k takes one rounding per term either way
+    auto partial = [&](const u32x4 &wv, double &dot, double &k2) {
+        dot = 0.0;
+        k2 = 0.0;
 #pragma unroll
-        for (int ps = 0; ps < UPR; ++ps) {
-            double dot = 0.0, k2 = 0.0;
+        for (int i = 0; i < 4; ++i) {
+            const double a = bf16_lo(wv[i]), b = bf16_hi(wv[i]);
+            dot = __builtin_fma(mreg[2 * i], a, dot);
+            k2 = __builtin_fma(a, a, k2);
+            dot = __builtin_fma(mreg[2 * i + 1], b, dot);
+            k2 = __builtin_fma(b, b, k2);
+        }
+    };
+    if constexpr (UPR == 16) {
+        // two passes at a time: the four quantities are summed over the 16 lanes of a row with 5
+        // additions per lane; lanes 0-3 of a row end with mu.k of the first pass, 4-7 with its
+        // |k|^2, 8-11 and 12-15 with those of the second
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const double a = bf16_lo(w[ps][i]), b = bf16_hi(w[ps][i]);
-                dot += mreg[2 * i] * a;
-                k2 += a * a;
-                dot += mreg[2 * i + 1] * b;
-                k2 += b * b;
+        for (int ps = 0; ps < NP; ps += 2) {
+            double d0, q0, d1, q1;
+            partial(w[ps], d0, q0);
+            partial(w[ps + 1], d1, q1);
+            const double v = row_reduce_scatter4_f64(d0, q0, d1, q1, u);
+            if ((u & 3) == 0) {
+                const int slot = (ps + (u >> 3)) * RPW + rl;
+                if (u & 4) sh.k2[wave][slot] = v;
+                else sh.dot[wave][slot] = v;
             }
+        }
+    } else {
+#pragma unroll
+        for (int ps = 0; ps < NP; ++ps) {
+            double dot, k2;
+            partial(w[ps], dot, k2);
             dot = row_allreduce_f64<UPR>(dot);
             k2 = row_allreduce_f64<UPR>(k2);
             if (u == 0) {
@@ -94,17 +116,16 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
                 sh.k2[wave][ps * RPW + rl] = k2;
             }
         }
-        // same wave wrote and reads: the LDS accesses of one wave complete in order; the fence only
-        // keeps the compiler from moving the reads above the writes
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const int row = base + lane;
-        if (row < row1) {
-            const double dot = sh.dot[wave][lane], k2 = sh.k2[wave][lane];
-            const float s = finish_score(dot, k2, nmu, p.eps);
-            p.scores[(size_t)bh * p.cap + row] = s;
-            if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = s;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    // same wave wrote and reads: the LDS accesses of one wave complete in order; the fence only
+    // keeps the compiler from moving the reads above the writes
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const int row = base + lane;
+    if (lane < WROWS && row < row1) {
+        const double dot = sh.dot[wave][lane], k2 = sh.k2[wave][lane];
+        const float sc = finish_score(dot, k2, nmu, p.eps);
+        p.scores[(size_t)bh * p.cap + row] = sc;
+        if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = sc;
     }
 }
 

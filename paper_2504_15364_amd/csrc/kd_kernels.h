@@ -19,7 +19,7 @@ namespace kd {
 constexpr int TILE_KEYS = 64;       // keys per attention K/V tile
 constexpr int POST_THREADS = 1024;  // workgroup size of step_post
 constexpr int SCORE_THREADS = 256;  // workgroup size of step_score
-constexpr int SCORE_ROWS = 256;     // rows per step_score workgroup: 64 per wave
+constexpr int SCORE_ROWS = 128;     // rows per step_score workgroup: 32 per wave
 constexpr int HIST_BINS = 4096;     // score histogram resolution in step_post (bins over [-1, 1])
 constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
 constexpr int ORD_ROWS = 128;       // rows per workgroup of the ordered compaction

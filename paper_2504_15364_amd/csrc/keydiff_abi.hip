@@ -162,6 +162,7 @@ struct keydiff_cache {
     bool pending;         // a deferred eviction (selection + compaction) has not been enqueued yet
     kd::StepParams pend;  // ... the parameters of the step it belongs to
     hipStream_t pend_stream;
+    int32_t plan[4];      // of the last block step: key ranges, row tiles per head, key tiles, carried a passenger
     bool profiling;
     std::vector<ProfEvent> events;
     std::vector<hipEvent_t> pool;
@@ -420,6 +421,10 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     if (riding && carry->cfg.layout == KEYDIFF_LAYOUT_ORDERED)
         if (int rc = compact_ordered(carry, carry->pend, s)) return rc;
     if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
+    c->plan[0] = p.psplits;
+    c->plan[1] = p.mtiles;
+    c->plan[2] = p.ntiles;
+    c->plan[3] = riding ? 1 : 0;
     c->kpar ^= 1;   // step_main wrote the new key sum into the other half
     c->len = evict ? N : n;
     c->contiguous = contiguous;
@@ -484,6 +489,7 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->epoch = 0;
     c->pending = false;
     c->pend_stream = nullptr;
+    for (int32_t &x : c->plan) x = 0;
     static hipError_t configured = kd::configure_kernels();  // once per process
     hipError_t e = configured;
     if (e == hipSuccess)
@@ -513,6 +519,13 @@ int keydiff_cache_len(const keydiff_cache_t *c, int32_t *len)
 {
     if (!c || !len) return fail(KEYDIFF_EINVAL, "null pointer");
     *len = c->len;
+    return KEYDIFF_OK;
+}
+
+int keydiff_cache_plan(const keydiff_cache_t *c, int32_t plan_out[4])
+{
+    if (!c || !plan_out) return fail(KEYDIFF_EINVAL, "null pointer");
+    for (int i = 0; i < 4; ++i) plan_out[i] = c->plan[i];
     return KEYDIFF_OK;
 }
 

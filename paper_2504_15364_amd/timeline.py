@@ -159,6 +159,29 @@ def main():
     print("# stamps: thread 0 of every workgroup, constant 100 MHz clock (0.01 us resolution)")
     summarise(1, ATTN_PHASES, "attention workgroups")
     summarise(2, SEL_PHASES, "carried selection workgroups")
+    # when the attention workgroups end, by position in the grid: key split (workgroups of a split take
+    # consecutive key tiles; the last split holds the block's own rows) and KV head
+    BH = w.batch * Hkv
+    mtiles = (w.group * B + 255) // 256
+    by_split, by_head, by_start = {}, {}, []
+    for s in range(slots):
+        r = rec[s]
+        idx = np.nonzero(r[:, 31] == 1)[0]
+        if idx.size == 0:
+            continue
+        t_launch = r[r[:, 31] != 0][:, 0].min()
+        first = idx.min()
+        for i in idx:
+            wg = i - first
+            end = (r[i, 12] - t_launch) * TICK_US
+            by_split.setdefault(wg // (BH * mtiles), []).append((end, r[i, 30], (r[i, 0] - t_launch) * TICK_US))
+            by_head.setdefault(wg % BH, []).append(end)
+    if by_split:
+        print("\nattention workgroups by key split: tiles, start, end (us, mean over launches, heads and row tiles)")
+        for sp in sorted(by_split):
+            v = np.array(by_split[sp])
+            print(f"  split {sp:2d}: tiles {v[:, 1].mean():5.2f}  start {v[:, 2].mean():5.2f}  end {v[:, 0].mean():6.2f}  (max {v[:, 0].max():6.2f})")
+        print("  by KV head (end, mean): " + "  ".join(f"{np.mean(by_head[h]):.2f}" for h in sorted(by_head)))
     ends = []
     for s in range(slots):
         live = rec[s][rec[s][:, 31] != 0]

@@ -514,6 +514,31 @@ def test_very_large_logits_stay_finite():
     assert cache.status() == 0
 
 
+def test_values_up_to_the_documented_magnitude_limit():
+    # Split-KV partial outputs are stored as fp16 (normalised by their own row sum, so bounded by the
+    # largest |v| of the rows they cover): keydiff.h limits |v| to 65504.  Values scaled by 2^13 (exact in
+    # bf16; the largest is then about 3.7e4, just inside the limit) must give 2^13 times the outputs of
+    # the unscaled run: every rounding on the way (bf16 weights, fp16 partials, bf16 output) is scale
+    # free as long as nothing overflows -- up to one bf16 step where a partial of the unscaled run was
+    # an fp16 subnormal.  Through the split path, several key splits.
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1024)
+    data = make_layer(w, seed=64)
+    e = (data["v"] >> 7) & 0xFF
+    big = data["v"].copy()
+    nz = e != 0
+    big[nz] = (data["v"][nz] & 0x807F) | ((e[nz].astype(np.int32) + 13).astype(np.uint16) << 7)
+    vmax = float(np.abs(bf16_out_to_f32(to_dev(big))).max())
+    assert 3.0e4 < vmax < 65504.0
+    a, _ = make_pair(w, 512, 128, layout=kd.LAYOUT_FILL)
+    b, _ = make_pair(w, 512, 128, layout=kd.LAYOUT_FILL)
+    for (t, Bt, q, k, v), (_, _, _, _, vb) in zip(blocks(data, 128), blocks(dict(data, v=big), 128)):
+        out_a = bf16_out_to_f32(a.prefill_block(to_dev(q), to_dev(k), to_dev(v), t))
+        out_b = bf16_out_to_f32(b.prefill_block(to_dev(q), to_dev(k), to_dev(vb), t))
+        assert np.isfinite(out_b).all(), t
+        assert np.allclose(out_b / 8192.0, out_a, rtol=2.0 ** -7, atol=1e-4), f"outputs do not scale at token {t}"
+    assert a.status() == 0 and b.status() == 0
+
+
 def test_zero_key_and_tiny_keys_hit_the_eps_clamp():
     hq, hkv, d, N, B = 2, 1, 64, 40, 16
     w = get_config("toy").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=64)
