@@ -89,6 +89,12 @@ def bench_decode(args, w):
     for _ in range(args.warmup):
         cache.decode_step(*toks[i], N + i, out=out)
         i += 1
+    if args.pmc_calibration:
+        src = torch.empty(CALIBRATION_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads and writes CALIBRATION_COPY_BYTES each
+        del src, dst
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):

@@ -165,14 +165,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     const int sp = id / p.mtiles;
     const int b = bh / p.hkv, kvh = bh % p.hkv;
     const int Mtot = p.G * p.Bt;
-    // Key range of this split.  The tiles that take rows of the block (causal mask, a second source,
-    // decisions per copy) cost more than a plain tile of cached keys: the ranges are balanced with
-    // such a tile counted as edge_cost plain ones.
-    const int tplain = min(p.ntiles, p.len / TILE_KEYS);
-    const int ctotal = tplain + (p.ntiles - tplain) * p.edge_cost;
+    // Key range of this split: the 64-key tiles are dealt out evenly (in-kernel stamps: a tile that
+    // holds rows of the block -- causal mask, a second source -- takes as long as a tile of cached keys).
     auto tile_at = [&](int i) {   // first tile of split i
-        const int c = (int)(((unsigned)i * (unsigned)ctotal) / (unsigned)p.splits);   // < 2^31: at most 512 splits x 1536 cost units
-        return c <= tplain ? c : tplain + (c - tplain) / p.edge_cost;
+        return (int)(((unsigned)i * (unsigned)p.ntiles) / (unsigned)p.splits);   // < 2^31: at most 512 splits x 512 tiles
     };
     const int t0 = tile_at(sp);
     const int t1 = sp + 1 == p.splits ? p.ntiles : tile_at(sp + 1);

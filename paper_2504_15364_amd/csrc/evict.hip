@@ -270,14 +270,15 @@ __global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p, int
         const int w = q * 1024 + tid;
         const int which = w >= ORD_ROWS * UPR, rem = w - which * ORD_ROWS * UPR;
         const int row = r0 + rem / UPR, u = rem % UPR;
+        // the row is requested together with its destination, not after it: one memory round trip
+        // (rows that turn out to stay, or to be evicted, are the few ahead of the first eviction and
+        // the evicted ones themselves)
         drow[q] = -1;
         val[q] = u32x4{0u, 0u, 0u, 0u};
         if (row < p.n) {
+            val[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)row * D + u * 8);
             const int d = dst[row];
-            if (d >= 0 && d != row) {
-                drow[q] = d;
-                val[q] = *reinterpret_cast<const u32x4 *>((which ? vb : kb) + (size_t)row * D + u * 8);
-            }
+            if (d >= 0 && d != row) drow[q] = d;
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // every row of this chunk is in registers

@@ -241,7 +241,6 @@ kd::StepParams base_params(const keydiff_cache *c, int n, unsigned char *scratch
     p.cap = c->L.cap;
     p.splits = 1;
     p.psplits = 1;
-    p.edge_cost = 1;
     p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
     if (p.score_chunks < 1) p.score_chunks = 1;
     p.lists_in_lds = kd::lists_fit_lds(n, cf.budget_N) ? 1 : 0;
@@ -297,16 +296,6 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     while (splits > 1 && (long)per * splits * BH * Mpad > c->L.max_part_rows) --splits;
     p.splits = splits;
     p.psplits = per * splits;
-    // a tile with rows of the block counts as up to three plain ones when the tiles are dealt out
-    // (measured: the steps around such tiles take about that much longer); every split must still
-    // span at least one tile, which a span of 2 * edge_cost cost units guarantees
-    const int tplain = p.len / kd::TILE_KEYS < p.ntiles ? p.len / kd::TILE_KEYS : p.ntiles;
-    p.edge_cost = 1;
-    for (int e = 3; e > 1; --e)
-        if ((tplain + e * (p.ntiles - tplain)) / splits >= 2 * e) {
-            p.edge_cost = e;
-            break;
-        }
     const size_t merge_threads = (size_t)BH * (Mpad / 32) * (p.D / 8) * 64;
     p.merge_wgs = p.psplits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
@@ -411,6 +400,9 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
         c->pend = p;
         c->pend_stream = s;
     } else if (evict || p.merge_wgs > 0) {
+#ifdef KD_TIMELINE
+        p.timeline = timeline_slot();   // the selection inside step_post records into the next slot
+#endif
         ProfScope ps(c, KEYDIFF_K_POST, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");
     }

@@ -1,10 +1,12 @@
 """Condense rocprofv3 CSV output into the few figures a roofline needs.
 
-    python -m paper_2504_15364_amd.rocprof_summary stats   <dir>            # --kernel-trace --stats run
+    python -m paper_2504_15364_amd.rocprof_summary stats   <dir> [--first K]  # --kernel-trace --stats run
     python -m paper_2504_15364_amd.rocprof_summary counter <dir> <COUNTER> [--copy-bytes N]
 
 `stats` prints, per kernel, launches / average / median / min / max duration from the
-kernel trace.  `counter` prints the per-dispatch mean of one hardware counter for each
+kernel trace; with --first K also the average over the first K launches of each kernel in
+time order (bench.py runs its timed steady-state steps first, the secondary measurements
+after them).  `counter` prints the per-dispatch mean of one hardware counter for each
 kernel of this library and, when --copy-bytes is given, the same counter for the plain
 copy kernel of that size the benchmark ran for calibration (bench.py --pmc-calibration),
 with the resulting bytes-per-count factor and the calibrated per-launch byte count.
@@ -31,19 +33,22 @@ def short(name):
     return name.replace("void ", "").replace("kd::", "")[-64:]
 
 
-def stats(root):
+def stats(root, first=0):
     rows = []
     for f in _find(root, "kernel_trace.csv"):
         rows += list(csv.DictReader(open(f)))
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
     agg = collections.defaultdict(list)
     for r in rows:
         agg[short(r["Kernel_Name"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
     total = sum(sum(v) for v in agg.values())
-    print(f"{'kernel':64s} {'calls':>7s} {'avg_us':>9s} {'med_us':>9s} {'min_us':>9s} {'max_us':>9s} {'%time':>6s}")
+    head = f"{'avg_first_' + str(first):>16s}" if first else ""
+    print(f"{'kernel':64s} {'calls':>7s} {'avg_us':>9s} {'med_us':>9s} {'min_us':>9s} {'max_us':>9s} {'%time':>6s}{head}")
     for k, v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
         s = sorted(v)
+        extra = f"{sum(v[:first]) / len(v[:first]):16.2f}" if first else ""
         print(f"{k:64s} {len(v):7d} {sum(v) / len(v):9.2f} {s[len(v) // 2]:9.2f} {s[0]:9.2f} {s[-1]:9.2f} "
-              f"{100 * sum(v) / total:6.1f}")
+              f"{100 * sum(v) / total:6.1f}{extra}")
 
 
 def counter(root, name, copy_bytes):
@@ -69,7 +74,7 @@ def counter(root, name, copy_bytes):
                   f"-> {factor:.2f} bytes per count")
     print(f"{'kernel':64s} {'n':>6s} {'mean ' + name:>20s} {'calibrated bytes':>18s}")
     for k, v in sorted(agg.items()):
-        if "step_" not in k and "compact" not in k and "merge" not in k:
+        if "step_" not in k and "compact" not in k and "merge" not in k and "ksum" not in k:
             continue
         m = sum(v) / len(v)
         cal = f"{m * factor:18.0f}" if factor else f"{'-':>18s}"
@@ -78,7 +83,7 @@ def counter(root, name, copy_bytes):
 
 def main(argv):
     if len(argv) >= 2 and argv[0] == "stats":
-        stats(argv[1])
+        stats(argv[1], int(argv[argv.index("--first") + 1]) if "--first" in argv else 0)
     elif len(argv) >= 3 and argv[0] == "counter":
         cb = int(argv[argv.index("--copy-bytes") + 1]) if "--copy-bytes" in argv else 0
         counter(argv[1], argv[2], cb)

@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--steps", type=int, default=6)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seed", type=int, default=20250415)
+    ap.add_argument("--eviction", choices=["deferred", "immediate"], default="deferred",
+                    help="immediate: keydiff_prefill_block per layer; the selection then runs in step_post, after the attention")
     args = ap.parse_args()
 
     import torch
@@ -102,12 +104,16 @@ def main():
         caches[l].load(k0, v0, p0)
 
     def run_block(i):
-        kd.prefill_block_layers(caches, [t[i] for t in dq], [t[i] for t in dk], [t[i] for t in dv], i * B, out=outs)
+        if args.eviction == "deferred":
+            kd.prefill_block_layers(caches, [t[i] for t in dq], [t[i] for t in dk], [t[i] for t in dv], i * B, out=outs)
+        else:
+            for l in range(L):
+                caches[l].prefill_block(dq[l][i], dk[l][i], dv[l][i], i * B, out=outs[l])
 
     for i in range(fill, fill + args.warmup):
         run_block(i)
     torch.cuda.synchronize()
-    slots = L * args.steps
+    slots = L * args.steps * (1 if args.eviction == "deferred" else 2)   # immediate: step_main, then step_post
     WGS = 512
     buf = torch.zeros(slots * WGS * 32, dtype=torch.int64, device="cuda")
     got = lib.keydiff_timeline_buffer(buf.data_ptr(), buf.numel() * 8)
@@ -155,10 +161,12 @@ def main():
             if not name.startswith("  "):
                 prev = m
 
-    print(f"# workload {w.name}: {L} layers, {args.steps} recorded block steps, eviction deferred (step_main_carry_kernel)")
+    print(f"# workload {w.name}: {L} layers, {args.steps} recorded block steps, eviction {args.eviction} "
+          f"({'step_main_carry_kernel' if args.eviction == 'deferred' else 'step_main_kernel, then step_post_kernel'})")
     print("# stamps: thread 0 of every workgroup, constant 100 MHz clock (0.01 us resolution)")
     summarise(1, ATTN_PHASES, "attention workgroups")
-    summarise(2, SEL_PHASES, "carried selection workgroups")
+    summarise(2, SEL_PHASES, "carried selection workgroups" if args.eviction == "deferred"
+              else "selection workgroups of step_post (a launch of its own after the attention)")
     # when the attention workgroups end, by position in the grid: key split (workgroups of a split take
     # consecutive key tiles; the last split holds the block's own rows) and KV head
     BH = w.batch * Hkv
