@@ -183,6 +183,28 @@ KEYDIFF_API int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int
                                  const void *const *q, const void *const *k_new, const void *const *v_new,
                                  int32_t Bt, int64_t pos0, void *const *out, void *stream);
 
+/* The block step with the rotary position embedding applied inside the call (Background, Fig. 1:
+ * step (1) of a layer forms the block's queries and keys, of which the rotation is the part that
+ * can live behind this boundary; the paper's method takes the keys as the cache holds them, i.e.
+ * rotated).  q and k_new arrive as the projections produced them; they are rotated at the positions
+ * pos0 + j (row j of the block) into buffers inside the scratch buffer, by one more launch ahead of
+ * the step's own, and everything after that is keydiff_prefill_block / _layers on the rotated block.
+ *   cos_table, sin_table  device, float [table_rows][head_dim / 2], 16-byte aligned: cosine and sine of
+ *                         the angle of position p (row p) and frequency i (column i)
+ *   pairing               element i of a row is rotated with element i + head_dim / 2:
+ *                         y_i = x_i cos - x_(i+h) sin,  y_(i+h) = x_(i+h) cos + x_i sin,  every product and
+ *                         sum rounded to float on its own, the result rounded once to bf16
+ * KEYDIFF_ESHAPE if pos0 + Bt exceeds table_rows.  The inputs are not modified.                      */
+KEYDIFF_API int keydiff_prefill_block_rope(keydiff_cache_t *cache, const void *q, const void *k_new,
+                               const void *v_new, int32_t Bt, int64_t pos0, const float *cos_table,
+                               const float *sin_table, int64_t table_rows, void *out, float *scores_out,
+                               void *stream);
+KEYDIFF_API int keydiff_prefill_block_layers_rope(keydiff_cache_t *const *caches, int32_t n_layers,
+                                      const void *const *q, const void *const *k_new,
+                                      const void *const *v_new, int32_t Bt, int64_t pos0,
+                                      const float *cos_table, const float *sin_table, int64_t table_rows,
+                                      void *const *out, void *stream);
+
 /* Enqueue the pending eviction of `cache` on `stream`, if it has one (else a no-op). */
 KEYDIFF_API int keydiff_finish(keydiff_cache_t *cache, void *stream);
 

@@ -20,7 +20,7 @@ KERNEL_NAMES = ("step_main", "step_score", "step_post", "compact_ordered", "aux"
 EXPORTS = (
     "keydiff_workspace_bytes", "keydiff_init_cache", "keydiff_prefill_block", "keydiff_prefill_block_static",
     "keydiff_prefill_block_deferred",
-    "keydiff_prefill_block_layers", "keydiff_finish", "keydiff_decode_step",
+    "keydiff_prefill_block_layers", "keydiff_prefill_block_rope", "keydiff_prefill_block_layers_rope", "keydiff_finish", "keydiff_decode_step",
     "keydiff_scores", "keydiff_cache_len", "keydiff_cache_plan", "keydiff_cache_positions", "keydiff_cache_load",
     "keydiff_cache_status", "keydiff_profile_enable", "keydiff_profile_read", "keydiff_destroy_cache",
     "keydiff_last_error", "keydiff_version",
@@ -79,6 +79,8 @@ def load_library() -> C.CDLL:
     L.keydiff_prefill_block_deferred.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp]
     pp = C.POINTER(vp)
     L.keydiff_prefill_block_layers.argtypes = [pp, i32, pp, pp, pp, i32, i64, pp, vp]
+    L.keydiff_prefill_block_rope.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, i64, vp, vp, vp]
+    L.keydiff_prefill_block_layers_rope.argtypes = [pp, i32, pp, pp, pp, i32, i64, vp, vp, i64, pp, vp]
     L.keydiff_finish.argtypes = [vp, vp]
     L.keydiff_decode_step.argtypes = [vp, vp, vp, vp, i64, vp, vp]
     L.keydiff_scores.argtypes = [vp, vp, vp]
@@ -120,9 +122,11 @@ def _stream_ptr(stream):
     return getattr(stream, "cuda_stream", stream)
 
 
-def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=None):
+def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=None, rope=None):
     """One block through the layers of a model: `caches`, `q`, `k_new`, `v_new` (and `out`) are
-    sequences with one entry per layer; every layer's eviction rides in the next layer's launch."""
+    sequences with one entry per layer; every layer's eviction rides in the next layer's launch.
+    rope = (cos, sin): float32 device tables [positions][head_dim / 2]; q and k_new are then rotated
+    inside the call (keydiff_prefill_block_layers_rope)."""
     import torch
     n = len(caches)
     assert n >= 1 and len(q) == len(k_new) == len(v_new) == n
@@ -135,6 +139,15 @@ def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=No
         out = [torch.empty_like(t) for t in q]
     arr = lambda ptrs: (C.c_void_p * n)(*ptrs)
     L = caches[0]._L
+    if rope is not None:
+        cos, sin = rope
+        assert cos.dtype == torch.float32 and sin.dtype == torch.float32 and cos.is_contiguous() and sin.is_contiguous()
+        _check(L.keydiff_prefill_block_layers_rope(arr([c._h.value for c in caches]), n,
+                                                   arr([t.data_ptr() for t in q]), arr([t.data_ptr() for t in k_new]),
+                                                   arr([t.data_ptr() for t in v_new]), Bt, int(pos0), cos.data_ptr(),
+                                                   sin.data_ptr(), cos.shape[0], arr([t.data_ptr() for t in out]),
+                                                   _stream_ptr(stream)))
+        return out
     _check(L.keydiff_prefill_block_layers(arr([c._h.value for c in caches]), n,
                                           arr([t.data_ptr() for t in q]), arr([t.data_ptr() for t in k_new]),
                                           arr([t.data_ptr() for t in v_new]), Bt, int(pos0),
@@ -184,6 +197,22 @@ class KeyDiffCache:
                                              int(pos0), out.data_ptr(),
                                              scores_out.data_ptr() if scores_out is not None else None,
                                              _stream_ptr(stream)))
+        return out
+
+    def prefill_block_rope(self, q, k_new, v_new, pos0: int, cos, sin, out=None, scores_out=None, stream=None):
+        """prefill_block on a block whose q and k_new are not rotated yet: cos, sin float32 device
+        tables [positions][head_dim / 2]."""
+        import torch
+        Bt = k_new.shape[-2]
+        for t in (q, k_new, v_new):
+            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
+        assert cos.dtype == torch.float32 and sin.dtype == torch.float32 and cos.is_contiguous() and sin.is_contiguous()
+        if out is None:
+            out = torch.empty_like(q)
+        _check(self._L.keydiff_prefill_block_rope(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
+                                                  int(pos0), cos.data_ptr(), sin.data_ptr(), cos.shape[0], out.data_ptr(),
+                                                  scores_out.data_ptr() if scores_out is not None else None,
+                                                  _stream_ptr(stream)))
         return out
 
     def prefill_block_static(self, q, k_new, v_new, pos0: int, out, scores_out=None, stream=None):

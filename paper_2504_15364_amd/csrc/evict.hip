@@ -366,6 +366,56 @@ __global__ void ksum_final_kernel(const double *partials, double *ksum, int nchu
     ksum[(size_t)bh * D + c] = s;
 }
 
+// ------------------------------------------------------------------ rotary embedding
+// Fig. 1 step (1), the part of it that can live inside this boundary: the block's queries and keys
+// arrive as the projections produced them and are rotated here, at the positions pos0 + j, into
+// buffers the block step then reads.  Half-split pairing (i, i + D/2); cos and sin come from the
+// caller's float tables [position][D/2]; x1 cos - x2 sin and x2 cos + x1 sin with every product and
+// sum rounded to float on its own, then one rounding to bf16.
+// rows: all (sequence, head) rows of q followed by those of k_new, Bt tokens each; a thread takes the
+// 8 + 8 paired elements of one 16-byte unit of the first half.
+template <int D>
+__global__ __launch_bounds__(256) void rope_kernel(const uint16_t *q, const uint16_t *k, uint16_t *q_rot, uint16_t *k_rot,
+                                                   const float *cos_t, const float *sin_t, int q_rows, int k_rows, int Bt,
+                                                   int32_t pos0)
+{
+    constexpr int UPH = D / 16;   // 16-byte units per half row
+    const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t row = gid / UPH;
+    const int unit = (int)(gid % UPH);
+    if (row >= (size_t)q_rows + k_rows) return;
+    const bool isk = row >= (size_t)q_rows;
+    const size_t r = isk ? row - q_rows : row;
+    const uint16_t *src = (isk ? k : q) + r * D;
+    uint16_t *dst = (isk ? k_rot : q_rot) + r * D;
+    const int j = (int)(r % Bt);
+    const float *cs = cos_t + ((size_t)pos0 + j) * (D / 2) + unit * 8;
+    const float *sn = sin_t + ((size_t)pos0 + j) * (D / 2) + unit * 8;
+    const u32x4 a = *reinterpret_cast<const u32x4 *>(src + unit * 8);           // x1: elements 8 unit .. + 7
+    const u32x4 b = *reinterpret_cast<const u32x4 *>(src + D / 2 + unit * 8);   // x2: the paired elements
+    const f32x4 c0 = *reinterpret_cast<const f32x4 *>(cs), c1 = *reinterpret_cast<const f32x4 *>(cs + 4);
+    const f32x4 s0 = *reinterpret_cast<const f32x4 *>(sn), s1 = *reinterpret_cast<const f32x4 *>(sn + 4);
+    u32x4 o1, o2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float y1[2], y2[2];
+#pragma unroll
+        for (int hw = 0; hw < 2; ++hw) {
+            const float x1 = __uint_as_float(hw ? (a[i] & 0xFFFF0000u) : (a[i] << 16));
+            const float x2 = __uint_as_float(hw ? (b[i] & 0xFFFF0000u) : (b[i] << 16));
+            const int e = 2 * i + hw;
+            const float c = e < 4 ? c0[e] : c1[e - 4], sgn = e < 4 ? s0[e] : s1[e - 4];
+            y1[hw] = __fsub_rn(__fmul_rn(x1, c), __fmul_rn(x2, sgn));
+            y2[hw] = __fadd_rn(__fmul_rn(x2, c), __fmul_rn(x1, sgn));
+        }
+        const __bf16 l1 = (__bf16)y1[0], h1 = (__bf16)y1[1], l2 = (__bf16)y2[0], h2 = (__bf16)y2[1];
+        o1[i] = (uint32_t)__builtin_bit_cast(uint16_t, l1) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+        o2[i] = (uint32_t)__builtin_bit_cast(uint16_t, l2) | ((uint32_t)__builtin_bit_cast(uint16_t, h2) << 16);
+    }
+    *reinterpret_cast<u32x4 *>(dst + unit * 8) = o1;
+    *reinterpret_cast<u32x4 *>(dst + D / 2 + unit * 8) = o2;
+}
+
 // ------------------------------------------------------------------ small helpers
 __global__ void zero_words_kernel(int32_t *p, size_t n)
 {
@@ -482,6 +532,17 @@ hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(ksum_final_kernel, dim3(BH), dim3(128), 0, s, partials, const_cast<double *>(p.ksum), nchunks, p.D);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope(const uint16_t *q, const uint16_t *k, uint16_t *q_rot, uint16_t *k_rot, const float *cos_t,
+                       const float *sin_t, int q_rows, int k_rows, int Bt, int D, int32_t pos0, hipStream_t s)
+{
+    const size_t threads = ((size_t)q_rows + k_rows) * (D / 16);
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    if (D == 128) hipLaunchKernelGGL((rope_kernel<128>), dim3(grid), dim3(256), 0, s, q, k, q_rot, k_rot, cos_t, sin_t, q_rows, k_rows, Bt, pos0);
+    else if (D == 64) hipLaunchKernelGGL((rope_kernel<64>), dim3(grid), dim3(256), 0, s, q, k, q_rot, k_rot, cos_t, sin_t, q_rows, k_rows, Bt, pos0);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

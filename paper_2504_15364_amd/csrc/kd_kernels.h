@@ -80,6 +80,10 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s);
 // flags: [BH][ceil(cap / ORD_ROWS)] int32 in zero-initialised device memory; epoch: a value no earlier launch used
 hipError_t launch_compact_ordered(const StepParams &p, int32_t *flags, int32_t epoch, hipStream_t s);
 hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s);
+// rotary embedding of the block's queries (q_rows rows) and keys (k_rows rows), Bt tokens per (sequence,
+// head) at positions pos0 + j, by the caller's float tables [position][D / 2]
+hipError_t launch_rope(const uint16_t *q, const uint16_t *k, uint16_t *q_rot, uint16_t *k_rot, const float *cos_t,
+                       const float *sin_t, int q_rows, int k_rows, int Bt, int D, int32_t pos0, hipStream_t s);
 hipError_t launch_zero_words(int32_t *p, size_t nwords, hipStream_t s);
 hipError_t launch_load_rows(const uint16_t *src, uint16_t *dst, int BH, int cap, int D, int len,
                             hipStream_t s);

@@ -29,7 +29,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct Layout {
     size_t k_bytes, meta_bytes, scratch_bytes;
     size_t off_pos, off_ksum, off_status, off_oflags;                                 // in meta
-    size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part;  // in scratch
+    size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part, off_q_rot, off_k_rot;  // in scratch
     int cap, max_part_rows;
     int target_wgs;   // bound used to size the partial buffers: twice the compute units of the chip
 };
@@ -135,6 +135,8 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_dstmap = off;     off += align256(BH * L.cap * 4);
     L.off_lists = off;      off += align256(BH * 4 * (size_t)c->block_B * 4);
     L.off_ksum_part = off;  off += align256(BH * chunks * D * 8);
+    L.off_q_rot = off;      off += align256((size_t)c->batch * c->n_q_heads * c->block_B * D * 2);   // rotated block (rope entry points)
+    L.off_k_rot = off;      off += align256(BH * c->block_B * D * 2);
     L.scratch_bytes = off;
     return L;
 }
@@ -333,8 +335,15 @@ int finish_pending(keydiff_cache *c, hipStream_t s)
 // `work`: the buffer for the step's temporaries -- the handle's scratch buffer, or the static array.
 // Every check and every planning decision comes before the first launch, so an argument, shape or
 // state error leaves nothing enqueued.
+// The caller's rotary tables: float [rows][head_dim / 2] each; both null = q and k_new arrive rotated.
+struct Rope {
+    const float *cos_t, *sin_t;
+    int64_t rows;
+};
+
 int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v_new, int32_t Bt, int64_t pos0,
-               void *out, float *scores_out, bool defer, keydiff_cache *carry, unsigned char *work, hipStream_t s)
+               void *out, float *scores_out, bool defer, keydiff_cache *carry, unsigned char *work, hipStream_t s,
+               const Rope *rope = nullptr)
 {
     if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
     if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
@@ -342,6 +351,12 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     if (Bt < 1 || Bt > c->cfg.block_B) return fail(KEYDIFF_ESHAPE, "Bt must lie in [1, block_B], got %d", Bt);
     if (pos0 < 0 || pos0 + Bt > 0x7fffffffLL) return fail(KEYDIFF_ESHAPE, "positions must fit in int32");
     if (carry == c) return fail(KEYDIFF_EINVAL, "a cache cannot carry its own eviction");
+    if (rope) {
+        if (!rope->cos_t || !rope->sin_t) return fail(KEYDIFF_EINVAL, "null rotary table");
+        if (misaligned(rope->cos_t) || misaligned(rope->sin_t)) return fail(KEYDIFF_EINVAL, "rotary tables must be 16-byte aligned");
+        if (pos0 + Bt > rope->rows) return fail(KEYDIFF_ESHAPE, "the rotary tables hold %lld positions; the block ends at %lld",
+                                                (long long)rope->rows, (long long)(pos0 + Bt));
+    }
     const keydiff_config_t &cf = c->cfg;
     const int len = c->len, n = len + Bt, N = cf.budget_N;
     const bool contiguous = c->contiguous && (c->next_pos < 0 || c->next_pos == pos0);
@@ -373,6 +388,17 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     if (!riding) plan_attention(c, p);
 
     // ---- launches from here on
+    if (rope) {
+        // Fig. 1 step (1), as far as it lies inside this boundary: rotate the block's queries and keys
+        uint16_t *q_rot = reinterpret_cast<uint16_t *>(work + c->L.off_q_rot);
+        uint16_t *k_rot = reinterpret_cast<uint16_t *>(work + c->L.off_k_rot);
+        ProfScope ps(c, KEYDIFF_K_AUX, s);
+        KD_LAUNCH(kd::launch_rope(p.q, p.k_new, q_rot, k_rot, rope->cos_t, rope->sin_t, cf.batch * cf.n_q_heads * Bt,
+                                  cf.batch * cf.n_kv_heads * Bt, Bt, cf.head_dim, (int32_t)pos0, s),
+                  "rotary embedding kernel");
+        p.q = q_rot;
+        p.k_new = k_rot;
+    }
     if (int rc = finish_pending(c, s)) return rc;   // this step reads the compacted cache
     if (carry && carry->pending && !riding)
         if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
@@ -529,6 +555,16 @@ int keydiff_prefill_block(keydiff_cache_t *c, const void *q, const void *k_new, 
                       static_cast<hipStream_t>(stream));
 }
 
+int keydiff_prefill_block_rope(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
+                               int64_t pos0, const float *cos_table, const float *sin_table, int64_t table_rows, void *out,
+                               float *scores_out, void *stream)
+{
+    if (!c) return fail(KEYDIFF_EINVAL, "null pointer");
+    const Rope rope{cos_table, sin_table, table_rows};
+    return block_step(c, q, k_new, v_new, Bt, pos0, out, scores_out, false, nullptr, c->scratch,
+                      static_cast<hipStream_t>(stream), &rope);
+}
+
 int keydiff_prefill_block_static(keydiff_cache_t *c, const void *q, const void *k_new, const void *v_new, int32_t Bt,
                                  int64_t pos0, void *out, float *scores_out, void *stream)
 {
@@ -551,9 +587,8 @@ int keydiff_prefill_block_deferred(keydiff_cache_t *c, const void *q, const void
                       static_cast<hipStream_t>(stream));
 }
 
-int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q,
-                                 const void *const *k_new, const void *const *v_new, int32_t Bt, int64_t pos0,
-                                 void *const *out, void *stream)
+static int block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q, const void *const *k_new,
+                        const void *const *v_new, int32_t Bt, int64_t pos0, void *const *out, void *stream, const Rope *rope)
 {
     if (!caches || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
     if (n_layers < 1) return fail(KEYDIFF_ESHAPE, "n_layers must be positive, got %d", n_layers);
@@ -568,10 +603,26 @@ int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layer
         // layer 0 takes along what the last layer left pending at the previous block
         keydiff_cache *carry = n_layers > 1 ? caches[(l + n_layers - 1) % n_layers] : nullptr;
         if (int rc = block_step(caches[l], q[l], k_new[l], v_new[l], Bt, pos0, out[l], nullptr, true, carry,
-                                caches[l]->scratch, s))
+                                caches[l]->scratch, s, rope))
             return rc;
     }
     return KEYDIFF_OK;
+}
+
+int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q,
+                                 const void *const *k_new, const void *const *v_new, int32_t Bt, int64_t pos0,
+                                 void *const *out, void *stream)
+{
+    return block_layers(caches, n_layers, q, k_new, v_new, Bt, pos0, out, stream, nullptr);
+}
+
+int keydiff_prefill_block_layers_rope(keydiff_cache_t *const *caches, int32_t n_layers, const void *const *q,
+                                      const void *const *k_new, const void *const *v_new, int32_t Bt, int64_t pos0,
+                                      const float *cos_table, const float *sin_table, int64_t table_rows,
+                                      void *const *out, void *stream)
+{
+    const Rope rope{cos_table, sin_table, table_rows};
+    return block_layers(caches, n_layers, q, k_new, v_new, Bt, pos0, out, stream, &rope);
 }
 
 int keydiff_finish(keydiff_cache_t *c, void *stream)

@@ -12,11 +12,13 @@ reach both sides.
 """
 from .configs import CONFIGS, Workload, get_config
 from .generate import (
+    apply_rope,
     bf16_bits_to_f32,
     bf16_bits_to_f64,
     block_of,
     f32_to_bf16_bits,
     make_layer,
+    rope_tables,
 )
 
 __all__ = [
@@ -24,6 +26,8 @@ __all__ = [
     "Workload",
     "get_config",
     "make_layer",
+    "rope_tables",
+    "apply_rope",
     "block_of",
     "f32_to_bf16_bits",
     "bf16_bits_to_f32",

@@ -72,24 +72,37 @@ def _uniforms(seed, layer, seq, kind, t0, t1, inner_shape) -> np.ndarray:
     return out
 
 
-def _rope(x: np.ndarray, t0: int, theta: float) -> np.ndarray:
-    """Rotate x[(t, head, d)] at positions t0 + t, half-split pairing."""
-    T, _, d = x.shape
+def rope_tables(t0: int, T: int, d: int, theta: float):
+    """cos and sin of the rotary angles of positions t0 .. t0 + T - 1: float32 [T][d/2]
+    (inv_freq_i = theta^(-2i/d), angles in fp64, tables cast to fp32)."""
     half = d // 2
     inv_freq = theta ** (-2.0 * np.arange(half, dtype=np.float64) / d)
     ang = (t0 + np.arange(T, dtype=np.float64))[:, None] * inv_freq[None, :]
-    cos = np.cos(ang).astype(np.float32)[:, None, :]
-    sin = np.sin(ang).astype(np.float32)[:, None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def apply_rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotate float32 x[(t, head, d)] by the tables [t][d/2], half-split pairing (i, i + d/2); every
+    product and every sum is rounded to float32 on its own (no fused multiply-add)."""
+    half = x.shape[-1] // 2
+    c, s = cos[:, None, :], sin[:, None, :]
     x1, x2 = x[..., :half], x[..., half:]
     out = np.empty_like(x)
-    out[..., :half] = x1 * cos - x2 * sin
-    out[..., half:] = x2 * cos + x1 * sin
+    out[..., :half] = x1 * c - x2 * s
+    out[..., half:] = x2 * c + x1 * s
     return out
 
 
+def _rope(x: np.ndarray, t0: int, theta: float) -> np.ndarray:
+    """Rotate x[(t, head, d)] at positions t0 + t, half-split pairing."""
+    cos, sin = rope_tables(t0, x.shape[0], x.shape[-1], theta)
+    return apply_rope(x, cos, sin)
+
+
 def make_layer(w: Workload, seed: int, layer: int = 0, seq: int = 0,
-               t0: int = 0, t1: int | None = None):
-    """Tokens [t0, t1) of one layer of one sequence.
+               t0: int = 0, t1: int | None = None, rotate: bool = True):
+    """Tokens [t0, t1) of one layer of one sequence.  rotate=False leaves q and k as they are before
+    the rotary embedding (for the entry point that applies it itself).
 
     Returns a dict of bf16 bit patterns (uint16), token-major:
       q [t][n_q_heads][d], k [t][n_kv_heads][d], v [t][n_kv_heads][d]
@@ -118,7 +131,7 @@ def make_layer(w: Workload, seed: int, layer: int = 0, seq: int = 0,
     q += np.float32(0.5) * np.repeat(m, G, axis=0)[None]
     v = _normals(seed, layer, seq, _KIND_V, t0, t1, (Hkv, d))
 
-    if w.rope_theta is not None:
+    if w.rope_theta is not None and rotate:
         q = _rope(q, t0, w.rope_theta)
         k = _rope(k, t0, w.rope_theta)
 

@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2504_15364_amd as kd
 from helpers import (ATTN_ATOL, SCORE_ATOL, SCORE_RTOL, bf16_out_to_f32, blocks, rows_by_position, to_dev)
-from synth import block_of, f32_to_bf16_bits, get_config, make_layer
+from synth import apply_rope, bf16_bits_to_f32, block_of, f32_to_bf16_bits, get_config, make_layer, rope_tables
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -489,6 +489,66 @@ def test_deferred_eviction_single_cache_and_other_entry_points():
         cache.prefill_block_deferred(to_dev(q), to_dev(k), to_dev(v), t + Bt, carry=cache)
     assert cache.status() == 0
     cache.close()
+
+
+# ---- rotary embedding inside the call (Fig. 1 step 1, the part of it behind this boundary) ----
+def rotated_reference(w, data_u, T):
+    """What the rope entry points must produce from unrotated bf16 q / k: the input recipe's rotation
+    (float32, every product and sum rounded on its own) of those very values, rounded once to bf16."""
+    cos, sin = rope_tables(0, T, w.head_dim, w.rope_theta)
+    ref = dict(data_u)
+    for x in ("q", "k"):
+        ref[x] = f32_to_bf16_bits(apply_rope(bf16_bits_to_f32(data_u[x]), cos, sin))
+    return ref, torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+
+
+@pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
+@pytest.mark.parametrize("hq,hkv,d,N,B,T", [(6, 2, 128, 200, 48, 500), (8, 2, 64, 130, 100, 650)])
+def test_rope_entry_point_rotates_like_the_input_recipe(layout, hq, hkv, d, N, B, T):
+    # the oracle gets the block rotated by the recipe's own routine; the library gets it unrotated plus the
+    # tables.  The rotated keys are compared bit for bit through the cache rows they become (check_state),
+    # the rotated queries through the attention output.
+    w = get_config("llama32_3b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
+    data_u = make_layer(w, seed=77, rotate=False)
+    ref, cos, sin = rotated_reference(w, data_u, T)
+    assert not np.array_equal(ref["k"], data_u["k"])
+    cache, oc = make_pair(w, N, B, layout=layout)
+    for (t, Bt, q, k, v), (_, _, qr, kr, _) in zip(blocks(data_u, B), blocks(ref, B)):
+        out = cache.prefill_block_rope(to_dev(q), to_dev(k), to_dev(v), t, cos, sin)
+        want, _, _ = oc.prefill_block(qr, kr, v, t)
+        err = float(np.abs(bf16_out_to_f32(out) - want).max())
+        assert err <= ATTN_ATOL, f"attention error {err} in block at token {t}"
+        check_state(cache, oc, f"rope, block at token {t}")
+    assert cache.status() == 0
+    # a block that runs past the tables is refused before anything is enqueued
+    with pytest.raises(kd.KeyDiffError) as e:
+        cache.prefill_block_rope(to_dev(q), to_dev(k), to_dev(v), T, cos, sin)
+    assert e.value.code == -2
+    check_state(cache, oc, "after the refused call")
+    cache.close()
+
+
+def test_rope_through_the_layers_call():
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=1280)
+    N, B, L = 512, 128, 3
+    raws = [make_layer(w, seed=81 + l, layer=l, rotate=False) for l in range(L)]
+    refs = []
+    for r in raws:
+        ref, cos, sin = rotated_reference(w, r, w.prompt_T)
+        refs.append(ref)
+    pairs = [make_pair(w, N, B, layout=kd.LAYOUT_FILL) for _ in range(L)]
+    for steps_u, steps_r in zip(zip(*(blocks(r, B) for r in raws)), zip(*(blocks(r, B) for r in refs))):
+        t = steps_u[0][0]
+        outs = kd.prefill_block_layers([c for c, _ in pairs], [to_dev(s_[2]) for s_ in steps_u], [to_dev(s_[3]) for s_ in steps_u],
+                                       [to_dev(s_[4]) for s_ in steps_u], t, rope=(cos, sin))
+        for l, (c, oc) in enumerate(pairs):
+            want, _, _ = oc.prefill_block(steps_r[l][2], steps_r[l][3], steps_r[l][4], t)
+            err = float(np.abs(bf16_out_to_f32(outs[l]) - want).max())
+            assert err <= ATTN_ATOL, f"attention error {err}, layer {l}, block at token {t}"
+    for l, (c, oc) in enumerate(pairs):
+        check_state(c, oc, f"layer {l} at the end")
+        assert c.status() == 0
+        c.close()
 
 
 def test_very_large_logits_stay_finite():
