@@ -361,8 +361,11 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         // fold the lanes that hold the same unit (bu), then the waves
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if constexpr (UPR == 16) bacc[i] = sum_over_rows_f64(bacc[i]);
+            else {
 #pragma unroll
-            for (int off = UPR; off < 64; off <<= 1) bacc[i] += shfl_xor_f64(bacc[i], off);
+                for (int off = UPR; off < 64; off <<= 1) bacc[i] += shfl_xor_f64(bacc[i], off);
+            }
         }
         if (lane < UPR) {
 #pragma unroll
@@ -522,6 +525,22 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     // the bf16 values, rounded once to float.  The query-row tiles of a head share the K tiles, so
     // tile t is scored by the workgroup with mt == t % mtiles.  UPR lanes share a row.
     int staged = 0;   // rows this wave has staged (wave uniform)
+    // Generation phase (p.argmax_rec): the row to evict is the arg-max of the scores, so every lane keeps
+    // the best of the rows it finishes as (orderable score bits << 32 | row), and whether it met the
+    // same score bits on another row (then the token position has to decide, which the selection does
+    // from all scores as before); the workgroup leaves one such record for the selection.
+    unsigned long long am_best = 0;
+    bool am_tie = false;
+    auto am_merge = [](unsigned long long &best, bool &tie, unsigned long long ob, bool ot) {
+        const uint32_t hb = (uint32_t)(best >> 32), ho = (uint32_t)(ob >> 32);
+        if (ho > hb) {
+            best = ob;
+            tie = ot;
+        } else if (ho == hb && ob != 0) {
+            tie = tie || ot || ob != best;
+            best = ob > best ? ob : best;
+        }
+    };
     auto flush_scores = [&]() {
         // same wave wrote and reads: the LDS accesses of one wave complete in order; the fences only
         // keep the compiler from moving the reads above the writes, and later writes above the reads
@@ -535,6 +554,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 const float sc = finish_score(st_dot[wave][lane], st_k2[wave][lane], sqrt(nmu2), p.eps);
                 p.scores[(size_t)bh * p.cap + row] = sc;
                 if (p.scores_out) p.scores_out[(size_t)bh * p.n + row] = sc;
+                if constexpr (HELP) am_merge(am_best, am_tie, ((unsigned long long)orderable(sc) << 32) | (uint32_t)row, false);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1037,6 +1057,31 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     if (writer && tid < D) p.ksum_next[(size_t)bh * D + tid] = ksum_after;
 
     if (scoring) flush_scores();   // last: the square roots and divisions run while the stores above complete
+    if constexpr (HELP) {
+        if (scoring && p.argmax_rec) {   // uniform
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t lo = __shfl_xor((uint32_t)am_best, off), hi = __shfl_xor((uint32_t)(am_best >> 32), off);
+                const bool ot = __shfl_xor((int)am_tie, off) != 0;
+                am_merge(am_best, am_tie, ((unsigned long long)hi << 32) | lo, ot);
+            }
+            unsigned long long *wrec = reinterpret_cast<unsigned long long *>(&st_dot[0][0]);   // staging is over
+            __syncthreads();
+            if (lane == 0) {
+                wrec[2 * wave] = am_best;
+                wrec[2 * wave + 1] = am_tie ? 1ull : 0ull;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                unsigned long long b0 = 0;
+                bool t0_ = false;
+                for (int w = 0; w < NW; ++w) am_merge(b0, t0_, wrec[2 * w], wrec[2 * w + 1] != 0);
+                unsigned long long *rec = p.argmax_rec + ((size_t)bh * p.splits + sp) * 2;
+                rec[0] = b0;
+                rec[1] = t0_ ? 1ull : 0ull;
+            }
+        }
+    }
     KD_TL(11);  // append stored, scores flushed
 #ifdef KD_TIMELINE
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores of this wave have been acknowledged
@@ -1151,7 +1196,7 @@ hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hip
 #ifdef KD_TIMELINE
     cyl.timeline = p.timeline;   // one record per workgroup of the launch, passengers first
 #endif
-    const int res = carry_need(cy, true) <= CARRY_DYN_MAX ? 1 : 0;
+    const int res = carry_need(cy, true) <= CARRY_DYN_MAX && !cy.argmax_rec ? 1 : 0;
     const size_t need = carry_need(cy, res != 0);
     const size_t lds = need > main_lds_bytes(p.D) ? need : main_lds_bytes(p.D);
     const bool help = main_runs_help(p);

@@ -499,7 +499,7 @@ hipError_t launch_step_post(const StepParams &p, hipStream_t s)
         return hipGetLastError();
     }
     if (p.n > 32 * POST_THREADS) return hipErrorInvalidValue;   // a thread owns one word of the eviction bitmap
-    const bool res = post_resident(p);
+    const bool res = post_resident(p) && !p.argmax_rec;   // (the arg-max records make the copies of the scores unnecessary)
     const size_t lds = select_dyn_bytes(p.n, p.N, p.cap, p.lists_in_lds != 0, res);
     if (p.D == 128 && res) hipLaunchKernelGGL((step_post_kernel<128, true>), dim3(grid), dim3(POST_THREADS), lds, s, p);
     else if (p.D == 128) hipLaunchKernelGGL((step_post_kernel<128, false>), dim3(grid), dim3(POST_THREADS), lds, s, p);

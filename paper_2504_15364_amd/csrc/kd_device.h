@@ -74,6 +74,24 @@ __device__ __forceinline__ double row_allreduce_f64(double x)
 }
 
 
+// x + (x of lane ^ 16) + (x of lane ^ 32) + (x of lane ^ 48): the sum over the four 16-lane rows of a
+// wave, position by position, without a trip through LDS (every lane gets the total).
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second:
+// given x twice, the pair it returns holds {x of the even row, x of the odd row} of the lane's row
+// pair in every lane; v_permlane32_swap does the same with the two halves of the wave.
+__device__ __forceinline__ double sum_over_rows_f64(double x)
+{
+    auto pair_sum = [](double v, bool halves) {
+        const uint32_t lo = (uint32_t)__double2loint(v), hi = (uint32_t)__double2hiint(v);
+        const auto a = halves ? __builtin_amdgcn_permlane32_swap(lo, lo, false, false)
+                              : __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto b = halves ? __builtin_amdgcn_permlane32_swap(hi, hi, false, false)
+                              : __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+    };
+    return pair_sum(pair_sum(x, false), true);
+}
+
 // the double another lane holds, fetched by a DPP control word (rows of 16 lanes)
 template <int CTRL>
 __device__ __forceinline__ double dpp_fetch_f64(double x)

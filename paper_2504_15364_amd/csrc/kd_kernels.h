@@ -50,6 +50,9 @@ struct StepParams {
     float *scores;                   // [BH][cap]
     int32_t *dstmap;                 // [BH][cap] ORDERED layout: destination row or -1
     int32_t *lists;                  // [BH][4 * B] evicted rows | holes | movers | mover rank of each tail row
+    unsigned long long *argmax_rec;  // nullable [BH][splits][2]: the generation phase (one row to evict, no window):
+                                     // per step_main workgroup the largest (orderable score bits << 32 | row) among the
+                                     // rows it scored, and whether another of its rows has the same score bits
     // sizes
     int batch, hq, hkv, G, D, Bt, len, n, N, B, cap;
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup

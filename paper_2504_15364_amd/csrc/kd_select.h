@@ -291,7 +291,15 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, unsigned
         }
     }
     for (int i = tid; i < nwords; i += THREADS) evbits[i] = 0;
-    for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
+    const bool use_rec = E == 1 && p.argmax_rec != nullptr && p.window_W == 0 && 4 * p.splits <= HIST_BINS;   // uniform
+    if (use_rec) {
+        // the arg-max records of the attention launch travel with the loads above (the histogram's space
+        // holds them: a single eviction builds no histogram)
+        uint64_t *recs = reinterpret_cast<uint64_t *>(sh.hist);
+        for (int s_ = tid; s_ < 2 * p.splits; s_ += THREADS) recs[s_] = p.argmax_rec[(size_t)bh * p.splits * 2 + s_];
+    } else {
+        for (int i = tid; i < HIST_BINS; i += THREADS) sh.hist[i] = 0;
+    }
     if (tid == 0) {
         sh.ncand = 0;
         sh.nev = 0;
@@ -306,6 +314,37 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, unsigned
     if (E == 1) {
         // ---- 1'. a single row to evict (the generation phase): the arg-max by (score bits, position)
         // replaces histogram, threshold and ranking
+        // The attention launch may have left the arg-max by (score bits, row) of every workgroup's rows
+        // (p.argmax_rec): unless two rows share the largest score bits -- then the lower position has to
+        // win, and positions are not row numbers -- the row to evict is read off those few records.
+        uint64_t gbest = 0;
+        bool known = false;
+        if (use_rec) {
+            if (tid == 0) {
+                const uint64_t *recs = reinterpret_cast<const uint64_t *>(sh.hist);
+                uint64_t b0 = 0;
+                bool tie = false;
+                for (int s_ = 0; s_ < p.splits; ++s_) {
+                    const uint64_t ob = recs[2 * s_];
+                    const bool ot = recs[2 * s_ + 1] != 0;
+                    const uint32_t hb = (uint32_t)(b0 >> 32), ho = (uint32_t)(ob >> 32);
+                    if (ho > hb) {
+                        b0 = ob;
+                        tie = ot;
+                    } else if (ho == hb && ob != 0) {
+                        tie = true;
+                        b0 = ob > b0 ? ob : b0;
+                    }
+                }
+                sh.sel_cnt = (b0 != 0 && !tie) ? 1u : 0u;
+                sh.tb = (int)(uint32_t)b0;
+                if (b0 != 0 && !tie) evbits[(uint32_t)b0 >> 5] |= 1u << ((uint32_t)b0 & 31);
+            }
+            __syncthreads();
+            known = sh.sel_cnt != 0;   // uniform
+            gbest = known ? 1 : 0;
+        }
+        if (!known) {
         uint64_t best = 0;   // 0: no row (every real key is larger: orderable() of a finite score is > 0)
         int besti = -1;
 #pragma unroll 2
@@ -328,7 +367,6 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, unsigned
         }
         if (lane == 0) sh.wave_tot64[wave] = wbest;
         __syncthreads();
-        uint64_t gbest = 0;
 #pragma unroll
         for (int w = 0; w < NWAVES; ++w) gbest = sh.wave_tot64[w] > gbest ? sh.wave_tot64[w] : gbest;
         // positions are unique within a head, so exactly one thread holds the winning key
@@ -337,6 +375,7 @@ __device__ void select_and_compact(const StepParams &p, PostShared &sh, unsigned
             sh.tb = besti;
         }
         __syncthreads();
+        }   // !known
         if (p.layout == 1 && tail_regs && gbest != 0) {
             // FILL with the one tail row (row N, this step's token) in registers: the rest of the work
             // is one row read and at most one row moved, done here without lists

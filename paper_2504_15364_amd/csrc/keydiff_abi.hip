@@ -29,7 +29,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct Layout {
     size_t k_bytes, meta_bytes, scratch_bytes;
     size_t off_pos, off_ksum, off_status, off_oflags;                                 // in meta
-    size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part, off_q_rot, off_k_rot;  // in scratch
+    size_t off_part_o, off_part_ml, off_scores, off_dstmap, off_lists, off_ksum_part, off_q_rot, off_k_rot, off_argmax;  // in scratch
     int cap, max_part_rows;
     int target_wgs;   // bound used to size the partial buffers: twice the compute units of the chip
 };
@@ -137,6 +137,7 @@ Layout make_layout(const keydiff_config_t *c)
     L.off_ksum_part = off;  off += align256(BH * chunks * D * 8);
     L.off_q_rot = off;      off += align256((size_t)c->batch * c->n_q_heads * c->block_B * D * 2);   // rotated block (rope entry points)
     L.off_k_rot = off;      off += align256(BH * c->block_B * D * 2);
+    L.off_argmax = off;     off += align256((size_t)(kTargetWorkgroups + BH) * 16);   // one arg-max record per step_main workgroup
     L.scratch_bytes = off;
     return L;
 }
@@ -386,6 +387,11 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
                  p.batch * p.hkv * p.mtiles * p.splits + seats <= c->L.target_wgs / 2;
     }
     if (!riding) plan_attention(c, p);
+    // Generation phase: the attention launch's scoring waves (the kernels with helper waves) leave the
+    // arg-max of the scores per workgroup, and the selection reads the row to evict off those records.
+    if (evict && n - N == 1 && cf.window_W == 0 && cf.layout == KEYDIFF_LAYOUT_FILL &&
+        p.mtiles * 32 * p.NW - p.G * p.Bt >= 32 && (size_t)p.batch * p.hkv * p.splits <= (size_t)c->L.target_wgs + p.batch * p.hkv)
+        p.argmax_rec = reinterpret_cast<unsigned long long *>(work + c->L.off_argmax);
 
     // ---- launches from here on
     if (rope) {

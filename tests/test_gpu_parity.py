@@ -209,6 +209,26 @@ def test_decode_steps_unit_anchor_and_window(kw):
     assert cache.status() == 0
 
 
+def test_decode_ties_are_decided_by_position_not_by_row():
+    # generation phase, FILL layout: the attention launch hands the selection the arg-max by (score, row) of
+    # every workgroup; where several rows share the largest score the lower POSITION must stay, and after a
+    # few hole fills positions are no longer in row order.  Half of the tokens repeat one key exactly.
+    w = get_config("decode_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=260, batch=2)
+    N = 160
+    seqs = [make_layer(w, seed=29, seq=s) for s in range(w.batch)]
+    for s_ in seqs:
+        s_["k"][1::2] = s_["k"][1]          # every odd token carries the key of token 1
+    cache, oc = make_pair(w, N, 1, batch=w.batch, layout=kd.LAYOUT_FILL)
+    for t in range(w.prompt_T):
+        q, k, v = (np.stack([s_[x][t][:, None, :] for s_ in seqs]) for x in ("q", "k", "v"))
+        out = cache.decode_step(to_dev(q), to_dev(k), to_dev(v), t)
+        ref, _, ev = oc.decode_step(q, k, v, t)
+        assert np.abs(bf16_out_to_f32(out) - ref).max() <= ATTN_ATOL, t
+        if t >= N:
+            check_state(cache, oc, f"decode step {t}")
+    assert cache.status() == 0
+
+
 @pytest.mark.parametrize("layout", [kd.LAYOUT_ORDERED, kd.LAYOUT_FILL])
 def test_ties_keep_the_lower_position(layout):
     # identical keys: every score is equal, so each step must evict the highest positions
