@@ -165,10 +165,15 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     const int sp = id / p.mtiles;
     const int b = bh / p.hkv, kvh = bh % p.hkv;
     const int Mtot = p.G * p.Bt;
-    // Key range of this split: the 64-key tiles are dealt out evenly (in-kernel stamps: a tile that
-    // holds rows of the block -- causal mask, a second source -- takes as long as a tile of cached keys).
+    // Key range of this split.  A tile that takes rows of the block (causal mask, a second source,
+    // decisions per copy) costs more than a plain tile of cached keys -- about 1.4 times by the
+    // in-kernel stamps -- and the split that holds them would end last: the ranges are balanced with
+    // such a tile counted as edge_cost (1 or 2) plain ones.
+    const int tplain = min(p.ntiles, p.len / TILE_KEYS);
+    const int ctotal = tplain + (p.ntiles - tplain) * p.edge_cost;
     auto tile_at = [&](int i) {   // first tile of split i
-        return (int)(((unsigned)i * (unsigned)p.ntiles) / (unsigned)p.splits);   // < 2^31: at most 512 splits x 512 tiles
+        const int c = (int)(((unsigned)i * (unsigned)ctotal) / (unsigned)p.splits);   // < 2^31: at most 512 splits x 1024 cost units
+        return c <= tplain ? c : tplain + (c - tplain) / p.edge_cost;
     };
     const int t0 = tile_at(sp);
     const int t1 = sp + 1 == p.splits ? p.ntiles : tile_at(sp + 1);

@@ -58,6 +58,8 @@ struct StepParams {
     int splits, mtiles, ntiles, NW;      // NW: waves (of 32 query rows) per step_main workgroup
     int psplits;                     // partials per output row the merge adds up: splits, or 2 * splits when two
                                      // waves of a workgroup take alternate tiles of its key range (decode)
+    int edge_cost;                   // weight (in plain tiles: 1 or 2) of a tile holding rows of the block when
+                                     // the key tiles are divided over the splits
     int score_chunks;                // step_score workgroups per head
     int lists_in_lds;                // selection lists live in LDS (else in `lists`)
     int merge_wgs;                   // merge workgroups in step_post (0 when psplits == 1)

@@ -244,6 +244,7 @@ kd::StepParams base_params(const keydiff_cache *c, int n, unsigned char *scratch
     p.cap = c->L.cap;
     p.splits = 1;
     p.psplits = 1;
+    p.edge_cost = 1;
     p.score_chunks = (n + kd::SCORE_ROWS - 1) / kd::SCORE_ROWS;
     if (p.score_chunks < 1) p.score_chunks = 1;
     p.lists_in_lds = kd::lists_fit_lds(n, cf.budget_N) ? 1 : 0;
@@ -299,6 +300,11 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     while (splits > 1 && (long)per * splits * BH * Mpad > c->L.max_part_rows) --splits;
     p.splits = splits;
     p.psplits = per * splits;
+    // a tile with rows of the block counts as two plain ones when the tiles are dealt out (it takes
+    // about 1.4 times as long, and an equal share would make its split the last to end); every split
+    // must still span at least one tile, which a span of 2 * edge_cost cost units guarantees
+    const int tplain = p.len / kd::TILE_KEYS < p.ntiles ? p.len / kd::TILE_KEYS : p.ntiles;
+    p.edge_cost = (tplain + 2 * (p.ntiles - tplain)) / splits >= 4 ? 2 : 1;
     const size_t merge_threads = (size_t)BH * (Mpad / 32) * (p.D / 8) * 64;
     p.merge_wgs = p.psplits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
