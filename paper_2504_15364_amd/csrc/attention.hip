@@ -115,6 +115,47 @@ __device__ __forceinline__ void wait_copies()  // at most N of this wave's copie
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// the same for a count known only at run time (wave uniform, at most 24)
+__device__ __forceinline__ void wait_copies_upto(int n)
+{
+    switch (n) {
+#define KD_WAIT_CASE(N) case N: wait_copies<N>(); break;
+        KD_WAIT_CASE(1) KD_WAIT_CASE(2) KD_WAIT_CASE(3) KD_WAIT_CASE(4) KD_WAIT_CASE(5) KD_WAIT_CASE(6)
+        KD_WAIT_CASE(7) KD_WAIT_CASE(8) KD_WAIT_CASE(9) KD_WAIT_CASE(10) KD_WAIT_CASE(11) KD_WAIT_CASE(12)
+        KD_WAIT_CASE(13) KD_WAIT_CASE(14) KD_WAIT_CASE(15) KD_WAIT_CASE(16) KD_WAIT_CASE(17) KD_WAIT_CASE(18)
+        KD_WAIT_CASE(19) KD_WAIT_CASE(20) KD_WAIT_CASE(21) KD_WAIT_CASE(22) KD_WAIT_CASE(23) KD_WAIT_CASE(24)
+#undef KD_WAIT_CASE
+        default: wait_copies<0>(); break;
+    }
+}
+
+// Loads into registers that the compiler is not told are loads: it neither counts them nor waits
+// for them.  The registers hold the data only after an explicit wait (wait_copies: these loads and
+// the copies complete in issue order) followed by loads_landed() on them, which is where the code
+// that reads them takes them from.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 load16_async(const void *g)
+{
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(g) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x2 load8_async(const void *g)
+{
+    u32x2 v;
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(g) : "memory");
+    return v;
+}
+template <int A, int B>
+__device__ __forceinline__ void loads_landed(u32x2 &x, u32x4 (&w)[A][B])
+{
+    asm volatile("" : "+v"(x) : : "memory");
+#pragma unroll
+    for (int i = 0; i < A; ++i)
+#pragma unroll
+        for (int j = 0; j < B; ++j) asm volatile("" : "+v"(w[i][j]) : : "memory");
+}
+
 // A workgroup is NW = 8 waves of NQ = 1 block of 32 query rows each (two waves per SIMD: with one wave
 // of 64 rows per SIMD every vector, LDS and copy-issue latency lay open and the kernel was slower).
 // HELP: some waves of a workgroup may have no query row at all (few query rows: decode); such a
@@ -178,6 +219,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
     const int t0 = tile_at(sp);
     const int t1 = sp + 1 == p.splits ? p.ntiles : tile_at(sp + 1);
     const int ntl = t1 - t0;
+    KD_TL(13);  // arguments read, key range known
 
     const uint16_t *kcache = p.k + (size_t)bh * p.cap * D;
     const uint16_t *vcache = p.v + (size_t)bh * p.cap * D;
@@ -244,8 +286,55 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             for (int c = 0; c < LPW; ++c) issue_copy(t, c);
         }
     };
-    // tile t0 first, then the queries, then tile t0 + 1: one memory round trip covers all three
-    if (ntl > 0) issue_tile(t0);
+    auto issue_half = [&](int t, bool vhalf) {   // the K tile (copies [0, CPW)) or the V tile (copies [CPW, LPW)) alone
+        if ((t + 1) * TILE_KEYS <= p.len) {   // uniform: the whole tile lies in the cache
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) issue_copy_cached(t, c + (vhalf ? CPW : 0));
+        } else {
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) issue_copy(t, c + (vhalf ? CPW : 0));
+        }
+    };
+
+    // ---- anchor, part 1 (Method, "Efficient Variant"): key sum after this step = key sum before it +
+    // the block's keys.  Every workgroup that scores forms it by itself (the block is 32 KB in L2); one
+    // workgroup per head also stores it for step_post and the next step.  The block's rows are
+    // requested first and consumed while the copies below fly.  These loads are written out as
+    // instructions of their own: for a load of its own the compiler waits by counting the loads it
+    // knows of, so with the copies (which it does not know of) issued behind it, it would wait for all
+    // of them.  Their registers are handed to the code that reads them by loads_landed(), after an
+    // explicit wait.
+    const bool writer = sp == 0 && mt == 0;
+    const bool need_sum = p.do_score != 0 || writer;
+    constexpr int BROWS = NT / UPR;    // block rows per pass: UPR consecutive lanes share a row
+    constexpr int BPASS = 4;           // passes loaded together (one batch)
+    constexpr int BBATCH = 2;          // batches requested up front
+    const int bu = tid % UPR, brl = tid / UPR;
+    const int nbatch = !need_sum ? 0 : min(BBATCH, (p.Bt + BPASS * BROWS - 1) / (BPASS * BROWS));   // uniform
+    u32x4 kw[BBATCH][BPASS];
+    u32x2 ksum_raw = {0u, 0u};
+#pragma unroll
+    for (int bt = 0; bt < BBATCH; ++bt)
+#pragma unroll
+        for (int ps = 0; ps < BPASS; ++ps) kw[bt][ps] = u32x4{0u, 0u, 0u, 0u};
+    auto request_rows = [&]() {
+        ksum_raw = load8_async(p.ksum + (size_t)bh * D + (tid & (D - 1)));
+#pragma unroll
+        for (int bt = 0; bt < BBATCH; ++bt) {
+            if (bt < nbatch) {
+#pragma unroll
+                for (int ps = 0; ps < BPASS; ++ps) {
+                    const int j = min((bt * BPASS + ps) * BROWS + brl, p.Bt - 1);   // rows past the block: masked below
+                    kw[bt][ps] = load16_async(knew + (size_t)j * D + bu * 8);
+                }
+            }
+        }
+    };
+    if (need_sum) request_rows();
+    // then the K half of tile t0 and the queries (what the first S^T reads), then the V half and tile
+    // t0 + 1: one memory round trip covers all of it, and the order of arrival is the order of use
+    if (ntl > 0) issue_half(t0, false);
+    KD_TL(14);  // block rows and first K tile requested
 
     // ---- query rows of this lane (one per block): B operands of S^T = K Q^T, kept in registers.
     // Row m of a head is query (m / Bt, m % Bt) and the rows are contiguous in memory, so a wave's
@@ -300,38 +389,27 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             }
         }
     }
+    KD_TL(15);  // queries requested
+    if (ntl > 0) issue_half(t0, true);
     if (ntl > 1) issue_tile(t0 + 1);
     KD_TL(1);   // first two tiles and the queries requested
 
-    // ---- anchor (Method, "Efficient Variant"): key sum after this step = key sum before it + the
-    // block's keys.  Every workgroup that scores forms it by itself (the block is 32 KB in L2); one
-    // workgroup per head also stores it for step_post and the next step.  The loads go out with
-    // the queries and are consumed before any further tile copy is issued: the compiler counts
-    // only its own loads when it waits for them.
-    const bool writer = sp == 0 && mt == 0;
-    const bool need_sum = p.do_score != 0 || writer;
-    constexpr int BROWS = NT / UPR;    // block rows per pass: UPR consecutive lanes share a row
-    constexpr int BPASS = 4;           // passes loaded together
-    const int bu = tid % UPR, brl = tid / UPR;
+    // ---- anchor, part 2: the block's rows have landed when only the copies issued behind them remain
+    constexpr int QCOPIES = 32 * NQ * ROWB / 1024;   // copies of a wave's query rows
+    const int behind_rows = (ntl > 0 ? LPW : 0) + QCOPIES + (ntl > 1 ? LPW : 0);   // uniform
     double bacc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) bacc[i] = 0.0;
-    const double ksum_before = (need_sum && tid < D) ? p.ksum[(size_t)bh * D + tid] : 0.0;
-    auto block_rows = [&](int j0) {   // rows j0 + pass * BROWS + brl of the block, BPASS passes
-        u32x4 kw[BPASS];
+    auto add_rows = [&](const u32x4 (&w)[BPASS], int j0) {   // rows j0 + pass * BROWS + brl of the block
 #pragma unroll
         for (int ps = 0; ps < BPASS; ++ps) {
-            const int j = j0 + ps * BROWS + brl;
-            kw[ps] = u32x4{0u, 0u, 0u, 0u};
-            if (j < p.Bt) kw[ps] = *reinterpret_cast<const u32x4 *>(knew + (size_t)j * D + bu * 8);
-        }
-#pragma unroll
-        for (int ps = 0; ps < BPASS; ++ps) {
+            const bool live = j0 + ps * BROWS + brl < p.Bt;
             double x[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[2 * i] = bf16_lo(kw[ps][i]);
-                x[2 * i + 1] = bf16_hi(kw[ps][i]);
+                const uint32_t wi = w[ps][i];
+                x[2 * i] = live ? bf16_lo(wi) : 0.0;
+                x[2 * i + 1] = live ? bf16_hi(wi) : 0.0;
             }
             double inv = 1.0;
             if (p.anchor_mode == 1) {  // unit keys (Eq. 7): x / |k_j|, a zero key adds nothing
@@ -346,23 +424,24 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             for (int i = 0; i < 8; ++i) bacc[i] += (p.anchor_mode == 1) ? x[i] * inv : x[i];
         }
     };
-    if (need_sum) block_rows(0);   // the first BPASS * BROWS rows: their loads fly with the queries
-    KD_TL(2);   // block rows summed (their loads have landed)
-
-    // everything issued so far has landed: the queries go from LDS to registers (a wave reads only
-    // what its own copies wrote)
-    wait_copies<0>();
-    KD_TL(3);   // every copy of this wave has landed
-#pragma unroll
-    for (int a = 0; a < NQ; ++a)
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-            qreg[a][c] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                qwave + (32 * a + l32) * ROWB + (((2 * c + h) ^ (l32 & (UPR - 1))) * 16)));
-
-    double ksum_after = 0.0;   // element tid of the new key sum (tid < D), stored at the end by the writer
+    double ksum_before = 0.0;
     if (need_sum) {
-        for (int j0 = BPASS * BROWS; j0 < p.Bt; j0 += BPASS * BROWS) block_rows(j0);   // uniform
+        wait_copies_upto(behind_rows);
+        loads_landed(ksum_raw, kw);
+        ksum_before = __hiloint2double((int)ksum_raw[1], (int)ksum_raw[0]);
+#pragma unroll
+        for (int bt = 0; bt < BBATCH; ++bt)
+            if (bt < nbatch) add_rows(kw[bt], bt * BPASS * BROWS);
+        // a block of more rows than were requested up front (rare): batch by batch, each waiting for
+        // everything in flight
+        for (int j0 = BBATCH * BPASS * BROWS; j0 < p.Bt; j0 += BPASS * BROWS) {   // uniform
+#pragma unroll
+            for (int ps = 0; ps < BPASS; ++ps)
+                kw[0][ps] = load16_async(knew + (size_t)min(j0 + ps * BROWS + brl, p.Bt - 1) * D + bu * 8);
+            wait_copies<0>();
+            loads_landed(ksum_raw, kw);
+            add_rows(kw[0], j0);
+        }
         // fold the lanes that hold the same unit (bu), then the waves
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -378,6 +457,21 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         }
         // (the per-wave sums are published by the barrier of the prologue below and added up after it)
     }
+    KD_TL(2);   // block rows landed, summed and folded
+
+    // ---- the queries go from LDS to registers (a wave reads only what its own copies wrote) once
+    // they and the K half of tile t0 have landed.  With two tiles or more the V half and tile t0 + 1
+    // may still fly: the first step of the loop waits for them.  A single tile has no such step.
+    if (ntl > 1) wait_copies<CPW + LPW>();
+    else wait_copies<0>();
+    KD_TL(3);   // queries and first K tile landed
+#pragma unroll
+    for (int a = 0; a < NQ; ++a)
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            qreg[a][c] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                qwave + (32 * a + l32) * ROWB + (((2 * c + h) ^ (l32 & (UPR - 1))) * 16)));
+    double ksum_after = 0.0;   // element tid of the new key sum (tid < D), stored at the end by the writer
 
     KD_TL(4);   // queries in registers, block sum folded
     f32x16 oacc[NQ][NDB];

@@ -22,10 +22,13 @@ os.environ["KEYDIFF_LIBRARY"] = os.path.join(HERE, "libkeydiff_timeline.so")
 sys.path.insert(0, os.path.dirname(HERE))
 
 ATTN_PHASES = [
+    (13, "  arguments read, key range known"),
+    (14, "  block rows and first K tile requested"),
+    (15, "  queries requested"),
     (1, "first two tiles + queries requested"),
-    (2, "block rows arrived and summed (fp64)"),
-    (3, "every copy of the wave landed"),
-    (4, "queries in registers, block sum folded"),
+    (2, "block rows landed, summed (fp64) and folded"),
+    (3, "queries and first K tile landed"),
+    (4, "queries in registers"),
     (5, "first barrier passed"),
     (6, "anchor formed"),
     (7, "logits of first tile ready (loop starts)"),
