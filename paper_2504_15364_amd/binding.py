@@ -122,6 +122,49 @@ def _stream_ptr(stream):
     return getattr(stream, "cuda_stream", stream)
 
 
+def check_block_shapes(cfg, q, k_new, v_new, out=None, Bt=None):
+    """The tensors of one block against the cache's configuration: q (and out) [batch][Hq][Bt][d],
+    k_new / v_new [batch][Hkv][Bt][d].  The C ABI takes bare pointers and cannot know how much memory
+    lies behind them: a tensor smaller than the configuration says would be read past its end by the
+    kernels, so the wrapper refuses it here, before anything is enqueued.  Returns Bt."""
+    if Bt is None:
+        Bt = int(k_new.shape[-2])
+    want_q = (cfg.batch, cfg.n_q_heads, Bt, cfg.head_dim)
+    want_kv = (cfg.batch, cfg.n_kv_heads, Bt, cfg.head_dim)
+    for name, t, want in (("q", q, want_q), ("k_new", k_new, want_kv), ("v_new", v_new, want_kv), ("out", out, want_q)):
+        if t is None:
+            continue
+        if tuple(t.shape) != want:
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, the cache's configuration needs {want}")
+    return Bt
+
+
+def check_load_shapes(cfg, cap, k, v, pos):
+    """Tensors handed to keydiff_cache_load: k, v [batch][Hkv][len][d] bf16, pos [batch][Hkv][len] int32."""
+    import torch
+    if k.dim() != 4:
+        raise ValueError(f"k has shape {tuple(k.shape)}, expected [batch][Hkv][len][d]")
+    ln = int(k.shape[2])
+    want = (cfg.batch, cfg.n_kv_heads, ln, cfg.head_dim)
+    if ln > cap:
+        raise ValueError(f"{ln} rows do not fit a cache of {cap} rows per head")
+    for name, t in (("k", k), ("v", v)):
+        if tuple(t.shape) != want or t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous bf16 tensor of shape {want}, got {tuple(t.shape)} {t.dtype}")
+    if tuple(pos.shape) != want[:3] or pos.dtype != torch.int32 or not pos.is_contiguous():
+        raise ValueError(f"pos must be a contiguous int32 tensor of shape {want[:3]}, got {tuple(pos.shape)} {pos.dtype}")
+    return ln
+
+
+def check_rope_tables(cfg, cos, sin):
+    import torch
+    for name, t in (("cos", cos), ("sin", sin)):
+        if t.dtype != torch.float32 or not t.is_contiguous() or t.dim() != 2 or t.shape[1] != cfg.head_dim // 2:
+            raise ValueError(f"{name} must be a contiguous float32 table [positions][{cfg.head_dim // 2}], got {tuple(t.shape)} {t.dtype}")
+    if cos.shape != sin.shape:
+        raise ValueError("cos and sin tables differ in shape")
+
+
 def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=None, rope=None):
     """One block through the layers of a model: `caches`, `q`, `k_new`, `v_new` (and `out`) are
     sequences with one entry per layer; every layer's eviction rides in the next layer's launch.
@@ -134,14 +177,18 @@ def prefill_block_layers(caches, q, k_new, v_new, pos0: int, out=None, stream=No
     for c, tq, tk, tv in zip(caches, q, k_new, v_new):
         for t in (tq, tk, tv):
             assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == c.device
-        assert tk.shape[-2] == Bt
+        check_block_shapes(c.cfg, tq, tk, tv, Bt=Bt)
     if out is None:
         out = [torch.empty_like(t) for t in q]
+    assert len(out) == n
+    for c, to in zip(caches, out):
+        assert to.is_contiguous() and to.dtype == torch.bfloat16 and to.device == c.device
+        check_block_shapes(c.cfg, None, None, None, out=to, Bt=Bt)
     arr = lambda ptrs: (C.c_void_p * n)(*ptrs)
     L = caches[0]._L
     if rope is not None:
         cos, sin = rope
-        assert cos.dtype == torch.float32 and sin.dtype == torch.float32 and cos.is_contiguous() and sin.is_contiguous()
+        check_rope_tables(caches[0].cfg, cos, sin)
         _check(L.keydiff_prefill_block_layers_rope(arr([c._h.value for c in caches]), n,
                                                    arr([t.data_ptr() for t in q]), arr([t.data_ptr() for t in k_new]),
                                                    arr([t.data_ptr() for t in v_new]), Bt, int(pos0), cos.data_ptr(),
@@ -184,15 +231,28 @@ class KeyDiffCache:
 
     __del__ = close
 
+    def _block_args(self, q, k_new, v_new, out, scores_out, allocate=True):
+        """Checks the tensors of one block (dtype, device, layout, shape) and returns (Bt, out)."""
+        import torch
+        for t in (q, k_new, v_new) + ((out,) if out is not None else ()):
+            if not (t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device):
+                raise ValueError("block tensors must be contiguous bf16 tensors on the cache's device")
+        Bt = check_block_shapes(self.cfg, q, k_new, v_new, out)
+        if out is None:
+            if not allocate:
+                raise ValueError("this call needs the caller's `out`")
+            out = torch.empty_like(q)
+        if scores_out is not None:
+            need = self.cfg.batch * self.cfg.n_kv_heads * (self.len + Bt)
+            if not (scores_out.is_contiguous() and scores_out.dtype == torch.float32 and scores_out.device == self.device
+                    and scores_out.numel() >= need):
+                raise ValueError(f"scores_out must be a contiguous float32 device tensor of at least {need} elements")
+        return Bt, out
+
     # -- the calls of the C ABI ------------------------------------------------
     def prefill_block(self, q, k_new, v_new, pos0: int, out=None, scores_out=None, stream=None):
         """q [batch][Hq][Bt][d], k_new/v_new [batch][Hkv][Bt][d] bf16 device tensors."""
-        import torch
-        Bt = k_new.shape[-2]
-        for t in (q, k_new, v_new):
-            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
-        if out is None:
-            out = torch.empty_like(q)
+        Bt, out = self._block_args(q, k_new, v_new, out, scores_out)
         _check(self._L.keydiff_prefill_block(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
                                              int(pos0), out.data_ptr(),
                                              scores_out.data_ptr() if scores_out is not None else None,
@@ -202,13 +262,8 @@ class KeyDiffCache:
     def prefill_block_rope(self, q, k_new, v_new, pos0: int, cos, sin, out=None, scores_out=None, stream=None):
         """prefill_block on a block whose q and k_new are not rotated yet: cos, sin float32 device
         tables [positions][head_dim / 2]."""
-        import torch
-        Bt = k_new.shape[-2]
-        for t in (q, k_new, v_new):
-            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
-        assert cos.dtype == torch.float32 and sin.dtype == torch.float32 and cos.is_contiguous() and sin.is_contiguous()
-        if out is None:
-            out = torch.empty_like(q)
+        Bt, out = self._block_args(q, k_new, v_new, out, scores_out)
+        check_rope_tables(self.cfg, cos, sin)
         _check(self._L.keydiff_prefill_block_rope(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
                                                   int(pos0), cos.data_ptr(), sin.data_ptr(), cos.shape[0], out.data_ptr(),
                                                   scores_out.data_ptr() if scores_out is not None else None,
@@ -218,10 +273,7 @@ class KeyDiffCache:
     def prefill_block_static(self, q, k_new, v_new, pos0: int, out, scores_out=None, stream=None):
         """prefill_block with the step's temporaries in the library's static device array; `out` is
         the caller's (this wrapper allocates nothing either)."""
-        import torch
-        Bt = k_new.shape[-2]
-        for t in (q, k_new, v_new, out):
-            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
+        Bt, out = self._block_args(q, k_new, v_new, out, scores_out, allocate=False)
         _check(self._L.keydiff_prefill_block_static(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
                                                     int(pos0), out.data_ptr(),
                                                     scores_out.data_ptr() if scores_out is not None else None,
@@ -231,12 +283,7 @@ class KeyDiffCache:
     def prefill_block_deferred(self, q, k_new, v_new, pos0: int, out=None, carry=None, stream=None):
         """The block step with its eviction left pending; `carry` is another KeyDiffCache whose
         pending eviction this call takes along."""
-        import torch
-        Bt = k_new.shape[-2]
-        for t in (q, k_new, v_new):
-            assert t.is_contiguous() and t.dtype == torch.bfloat16 and t.device == self.device
-        if out is None:
-            out = torch.empty_like(q)
+        Bt, out = self._block_args(q, k_new, v_new, out, None)
         _check(self._L.keydiff_prefill_block_deferred(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), Bt,
                                                       int(pos0), out.data_ptr(),
                                                       carry._h if carry is not None else None, _stream_ptr(stream)))
@@ -246,9 +293,9 @@ class KeyDiffCache:
         _check(self._L.keydiff_finish(self._h, _stream_ptr(stream)))
 
     def decode_step(self, q, k_new, v_new, pos: int, out=None, stream=None):
-        import torch
-        if out is None:
-            out = torch.empty_like(q)
+        Bt, out = self._block_args(q, k_new, v_new, out, None)
+        if Bt != 1:
+            raise ValueError("decode_step takes one token per sequence")
         _check(self._L.keydiff_decode_step(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), int(pos),
                                            out.data_ptr(), _stream_ptr(stream)))
         return out
@@ -279,7 +326,9 @@ class KeyDiffCache:
         return out
 
     def load(self, k, v, pos, stream=None):
-        ln = k.shape[2]
+        ln = check_load_shapes(self.cfg, self.cap, k, v, pos)
+        if not (k.device == v.device == pos.device == self.device):
+            raise ValueError("k, v and pos must live on the cache's device")
         _check(self._L.keydiff_cache_load(self._h, k.data_ptr(), v.data_ptr(), pos.data_ptr(), ln,
                                           _stream_ptr(stream)))
 

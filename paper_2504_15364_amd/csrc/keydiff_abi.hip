@@ -262,9 +262,9 @@ kd::StepParams base_params(const keydiff_cache *c, int n, unsigned char *scratch
 constexpr int kTimelineWgs = 512;
 unsigned long long *g_tl_buf = nullptr;
 long g_tl_slots = 0, g_tl_count = 0;
-unsigned long long *timeline_slot()
+unsigned long long *timeline_slot(long wgs)   // wgs: workgroups of the launch that store a record
 {
-    if (!g_tl_buf || g_tl_slots < 1) return nullptr;
+    if (!g_tl_buf || g_tl_slots < 1 || wgs > kTimelineWgs) return nullptr;   // a slot holds kTimelineWgs records
     return g_tl_buf + (size_t)(g_tl_count++ % g_tl_slots) * kTimelineWgs * 32;
 }
 #endif
@@ -415,7 +415,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     if (carry && carry->pending && !riding)
         if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
 #ifdef KD_TIMELINE
-    p.timeline = timeline_slot();
+    p.timeline = timeline_slot((long)p.batch * p.hkv * p.mtiles * p.splits + (riding ? carry->pend.batch * carry->pend.hkv : 0));
 #endif
     {
         ProfScope ps(c, KEYDIFF_K_MAIN, s);
@@ -439,7 +439,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
         c->pend_stream = s;
     } else if (evict || p.merge_wgs > 0) {
 #ifdef KD_TIMELINE
-        p.timeline = timeline_slot();   // the selection inside step_post records into the next slot
+        p.timeline = timeline_slot((long)p.batch * p.hkv);   // the selection inside step_post records into the next slot
 #endif
         ProfScope ps(c, KEYDIFF_K_POST, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");

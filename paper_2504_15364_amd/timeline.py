@@ -87,23 +87,26 @@ def main():
     fill = N // B
     nsteps = args.warmup + args.steps
     T = (fill + nsteps) * B
-    layers = [make_layer(w, seed=args.seed + 300 + l, layer=l, t1=T) for l in range(L)]
+    # one seeded token stream per (layer, sequence of the batch)
+    layers = [[make_layer(w, seed=args.seed + 300 + l, layer=l, seq=sq, t1=T) for sq in range(w.batch)] for l in range(L)]
 
-    def to_blocks(bits):
-        t = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-        Tn, H, d = bits.shape
-        return t.view(Tn // B, B, H, d).permute(0, 2, 1, 3).contiguous().unsqueeze(1)
+    def to_blocks(seqs, name):   # -> [block][batch][heads][B][d]
+        bits = np.stack([sq[name] for sq in seqs])                       # [batch][T][heads][d]
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+        nb, Tn, H, d = bits.shape
+        return t.view(nb, Tn // B, B, H, d).permute(1, 0, 3, 2, 4).contiguous()
 
     caches, dq, dk, dv, outs = [], [], [], [], []
     for l in range(L):
         caches.append(kd.KeyDiffCache(kd.KeyDiffConfig(w.batch, Hq, Hkv, D, N, B, layout=kd.LAYOUT_FILL)))
-        dq.append(to_blocks(layers[l]["q"]))
-        dk.append(to_blocks(layers[l]["k"]))
-        dv.append(to_blocks(layers[l]["v"]))
+        dq.append(to_blocks(layers[l], "q"))
+        dk.append(to_blocks(layers[l], "k"))
+        dv.append(to_blocks(layers[l], "v"))
         outs.append(torch.empty_like(dq[l][0]))
-        k0 = dk[l][:fill, 0].permute(1, 0, 2, 3).reshape(1, Hkv, N, D).contiguous()
-        v0 = dv[l][:fill, 0].permute(1, 0, 2, 3).reshape(1, Hkv, N, D).contiguous()
-        p0 = torch.arange(N, dtype=torch.int32, device="cuda").repeat(1, Hkv, 1).contiguous()
+        # the first N tokens of every sequence, [batch][heads][N][d]
+        k0 = dk[l][:fill].permute(1, 2, 0, 3, 4).reshape(w.batch, Hkv, N, D).contiguous()
+        v0 = dv[l][:fill].permute(1, 2, 0, 3, 4).reshape(w.batch, Hkv, N, D).contiguous()
+        p0 = torch.arange(N, dtype=torch.int32, device="cuda").repeat(w.batch, Hkv, 1).contiguous()
         caches[l].load(k0, v0, p0)
 
     def run_block(i):

@@ -78,3 +78,39 @@ def test_static_scratch_array_is_visible_to_the_runtime(tmp_path):
                           capture_output=True, text=True).stdout
     rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch")]
     assert rows and all(r[4] == "GLOBAL" and int(r[2]) == 40 << 20 for r in rows), syms
+
+
+def test_wrapper_refuses_tensors_smaller_than_the_configuration():
+    """The C ABI takes bare pointers, so the wrapper checks every tensor's shape against the cache's
+    configuration before a call: a tensor of a smaller batch or head count would be read past its end."""
+    import torch
+
+    from paper_2504_15364_amd.binding import check_block_shapes, check_load_shapes, check_rope_tables
+
+    cfg = kd.KeyDiffConfig(2, 8, 2, 64, 256, 32)
+    q = torch.zeros((2, 8, 32, 64), dtype=torch.bfloat16)
+    k = torch.zeros((2, 2, 32, 64), dtype=torch.bfloat16)
+    assert check_block_shapes(cfg, q, k, k, out=q) == 32
+    assert check_block_shapes(cfg, q[:, :, :5].contiguous(), k[:, :, :5].contiguous(), k[:, :, :5].contiguous()) == 5
+    with pytest.raises(ValueError, match="q has shape"):
+        check_block_shapes(cfg, q[:1], k, k)                      # one sequence instead of two
+    with pytest.raises(ValueError, match="k_new has shape"):
+        check_block_shapes(cfg, q, k[:, :1], k)                   # one KV head instead of two
+    with pytest.raises(ValueError, match="v_new has shape"):
+        check_block_shapes(cfg, q, k, k[:, :, :16])               # fewer rows than k_new
+    with pytest.raises(ValueError, match="out has shape"):
+        check_block_shapes(cfg, q, k, k, out=q[:, :4])
+    cap = 288
+    k0 = torch.zeros((2, 2, 100, 64), dtype=torch.bfloat16)
+    p0 = torch.zeros((2, 2, 100), dtype=torch.int32)
+    assert check_load_shapes(cfg, cap, k0, k0, p0) == 100
+    with pytest.raises(ValueError):
+        check_load_shapes(cfg, cap, k0[:1], k0[:1], p0[:1])       # the mistake that reads 2x past the end
+    with pytest.raises(ValueError):
+        check_load_shapes(cfg, cap, k0, k0, p0.to(torch.int64))
+    with pytest.raises(ValueError):
+        check_load_shapes(cfg, cap, torch.zeros((2, 2, 300, 64), dtype=torch.bfloat16), k0, p0)
+    cos = torch.zeros((128, 32), dtype=torch.float32)
+    check_rope_tables(cfg, cos, cos)
+    with pytest.raises(ValueError):
+        check_rope_tables(cfg, cos[:, :16].contiguous(), cos)
