@@ -406,7 +406,7 @@ def main():
             torch.cuda.synchronize()
             us = (time.perf_counter() - t0_) / (args.mode_steps * L) * 1e6
             prof = None
-            if lay == kd.LAYOUT_ORDERED and defer:      # per-kernel times of the stable layout (HIP events)
+            if lay == kd.LAYOUT_ORDERED and not defer:  # per-kernel times of the stable layout (HIP events; deferred, the shift rides in the merge launch)
                 for c in cs:
                     c.profile_enable(True)
                 for i in range(fill_blocks + 3 + args.mode_steps, fill_blocks + 7 + args.mode_steps):

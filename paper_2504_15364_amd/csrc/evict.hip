@@ -134,7 +134,8 @@ __device__ __forceinline__ void score_rows(const StepParams &p, ScoreShared &sh,
 // Thread gid takes four output values: step_main leaves a partial in its accumulator layout -- per
 // 32-row block D/8 slabs of 512 bytes, slab 4 db + jj holding for lane (h, l32) the values
 // d = 32 db + 8 jj + 4 h .. + 3 of row l32 -- and consecutive threads read consecutive lanes of a slab.
-template <int D>
+// MB: splits requested together
+template <int D, int MB = 16>
 __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
 {
     constexpr int SLABS = D / 8;
@@ -153,7 +154,6 @@ __device__ __forceinline__ void merge_rows(const StepParams &p, size_t gid)
     // One memory round trip: the (max, sum) pairs and the partial rows of a batch of splits are
     // requested together; only with more splits than a batch holds does a second batch follow, and
     // the running result is then rescaled to the larger reference (as inside the attention).
-    constexpr int MB = 16;
     float mx = -INFINITY;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float Lsum = 0.f;
@@ -252,13 +252,13 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 // stores.  Workgroups are numbered chunk-major, so a workgroup only ever waits for lower-numbered
 // ones; the wait is bounded and reports a timeout in the status word instead of hanging.
 template <int D>
-__global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p, int32_t *flags, int nchunks, int32_t epoch)
+__device__ __forceinline__ void shift_chunk(const StepParams &p, int32_t *flags, int nchunks, int32_t epoch, int block)
 {
     constexpr int UPR = D / 8;
-    constexpr int UPT = ORD_ROWS * UPR * 2 / 1024;   // 16-byte units (K and V) per thread
-    static_assert(UPT * 1024 == ORD_ROWS * UPR * 2, "the chunk must divide over the threads");
+    constexpr int UPT = ORD_ROWS * UPR * 2 / ORD_THREADS;   // 16-byte units (K and V) per thread
+    static_assert(UPT * ORD_THREADS == ORD_ROWS * UPR * 2, "the chunk must divide over the threads");
     const int BH = p.batch * p.hkv;
-    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH, tid = threadIdx.x;
+    const int bh = block % BH, chunk = block / BH, tid = threadIdx.x;
     uint16_t *kb = p.k + (size_t)bh * p.cap * D;
     uint16_t *vb = p.v + (size_t)bh * p.cap * D;
     const int32_t *dst = p.dstmap + (size_t)bh * p.cap;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p, int
     int drow[UPT];
 #pragma unroll
     for (int q = 0; q < UPT; ++q) {
-        const int w = q * 1024 + tid;
+        const int w = q * ORD_THREADS + tid;
         const int which = w >= ORD_ROWS * UPR, rem = w - which * ORD_ROWS * UPR;
         const int row = r0 + rem / UPR, u = rem % UPR;
         // the row is requested together with its destination, not after it: one memory round trip
@@ -299,11 +299,37 @@ __global__ __launch_bounds__(1024) void compact_ordered_kernel(StepParams p, int
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < UPT; ++q) {
-        const int w = q * 1024 + tid;
+        const int w = q * ORD_THREADS + tid;
         const int which = w >= ORD_ROWS * UPR, rem = w - which * ORD_ROWS * UPR;
         if (drow[q] >= 0)
             *reinterpret_cast<u32x4 *>((which ? vb : kb) + (size_t)drow[q] * D + (rem % UPR) * 8) = val[q];
     }
+}
+
+template <int D>
+__global__ __launch_bounds__(ORD_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void compact_ordered_kernel(StepParams p, int32_t *flags, int nchunks, int32_t epoch)
+{
+    shift_chunk<D>(p, flags, nchunks, epoch, (int)blockIdx.x);
+}
+
+// The merge of one cache's attention partials and the ordered shift of another cache in one launch
+// (eviction deferred, ORDERED layout: the selection of the other cache rode in the attention launch
+// just before, and its rows have no reader until that cache's next step).  The merge is a memory
+// round trip on a chip it leaves mostly idle; the shift is bound by HBM traffic: together they take
+// what the shift takes alone.  Workgroups [0, merge_wgs) merge -- they are dispatched first and
+// the caller waits for their output -- the others shift one chunk each, numbered chunk-major
+// behind them, so a shifting workgroup still only ever waits for lower-numbered ones.
+template <int D>
+__global__ __launch_bounds__(ORD_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void merge_shift_kernel(StepParams pm, StepParams ps, int32_t *flags, int nchunks,
+                                                                  int32_t epoch, int merge_wgs)
+{
+    if ((int)blockIdx.x < merge_wgs) {
+        // (few splits per round trip: the launch lasts as long as the shift does, and the registers
+        // decide how many of its workgroups a compute unit holds)
+        merge_rows<D, 4>(pm, (size_t)blockIdx.x * ORD_THREADS + threadIdx.x);
+        return;
+    }
+    shift_chunk<D>(ps, flags, nchunks, epoch, (int)blockIdx.x - merge_wgs);
 }
 
 // --------------------------------------------------- key sum from scratch (cache load)
@@ -513,9 +539,23 @@ hipError_t launch_compact_ordered(const StepParams &p, int32_t *flags, int32_t e
 {
     const int nchunks = (p.n + ORD_ROWS - 1) / ORD_ROWS;
     const int grid = p.batch * p.hkv * nchunks;
-    if (p.n - p.N > 1024 * ORD_ROWS) return hipErrorInvalidValue;   // one waiting thread per chunk in reach
-    if (p.D == 128) hipLaunchKernelGGL((compact_ordered_kernel<128>), dim3(grid), dim3(1024), 0, s, p, flags, nchunks, epoch);
-    else if (p.D == 64) hipLaunchKernelGGL((compact_ordered_kernel<64>), dim3(grid), dim3(1024), 0, s, p, flags, nchunks, epoch);
+    if (p.n - p.N > ORD_THREADS * ORD_ROWS) return hipErrorInvalidValue;   // one waiting thread per chunk in reach
+    if (p.D == 128) hipLaunchKernelGGL((compact_ordered_kernel<128>), dim3(grid), dim3(ORD_THREADS), 0, s, p, flags, nchunks, epoch);
+    else if (p.D == 64) hipLaunchKernelGGL((compact_ordered_kernel<64>), dim3(grid), dim3(ORD_THREADS), 0, s, p, flags, nchunks, epoch);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// pm: the step whose partials are merged; ps: the step of the other cache whose destination map is applied
+hipError_t launch_merge_shift(const StepParams &pm, const StepParams &ps, int32_t *flags, int32_t epoch, hipStream_t s)
+{
+    const int nchunks = (ps.n + ORD_ROWS - 1) / ORD_ROWS;
+    const size_t merge_threads = (size_t)pm.batch * pm.hkv * ((pm.G * pm.Bt + 31) / 32) * (pm.D / 8) * 64;
+    const int mw = (int)((merge_threads + ORD_THREADS - 1) / ORD_THREADS);
+    const int grid = mw + ps.batch * ps.hkv * nchunks;
+    if (ps.n - ps.N > ORD_THREADS * ORD_ROWS || pm.D != ps.D || pm.psplits < 2) return hipErrorInvalidValue;
+    if (pm.D == 128) hipLaunchKernelGGL((merge_shift_kernel<128>), dim3(grid), dim3(ORD_THREADS), 0, s, pm, ps, flags, nchunks, epoch, mw);
+    else if (pm.D == 64) hipLaunchKernelGGL((merge_shift_kernel<64>), dim3(grid), dim3(ORD_THREADS), 0, s, pm, ps, flags, nchunks, epoch, mw);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

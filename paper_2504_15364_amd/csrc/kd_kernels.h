@@ -23,6 +23,7 @@ constexpr int SCORE_ROWS = 128;     // rows per step_score workgroup: 32 per wav
 constexpr int HIST_BINS = 4096;     // score histogram resolution in step_post (bins over [-1, 1])
 constexpr int CHUNK_ROWS = 128;     // rows per workgroup in the from-scratch key-sum pass
 constexpr int ORD_ROWS = 128;       // rows per workgroup of the ordered compaction
+constexpr int ORD_THREADS = 1024;   // ... and its threads: 4 16-byte units each
 constexpr int ORD_SPIN_LIMIT = 1 << 20;  // polls of a predecessor's flag before giving up
 constexpr int MAX_CAP = 32768;      // budget_N + block_B limit (selection bitmaps, ownership)
 
@@ -84,6 +85,8 @@ hipError_t launch_step_score(const StepParams &p, hipStream_t s);
 hipError_t launch_step_post(const StepParams &p, hipStream_t s);
 // flags: [BH][ceil(cap / ORD_ROWS)] int32 in zero-initialised device memory; epoch: a value no earlier launch used
 hipError_t launch_compact_ordered(const StepParams &p, int32_t *flags, int32_t epoch, hipStream_t s);
+// the merge of pm's partials and the ordered shift of ps's cache in one launch (same head_dim)
+hipError_t launch_merge_shift(const StepParams &pm, const StepParams &ps, int32_t *flags, int32_t epoch, hipStream_t s);
 hipError_t launch_ksum_rebuild(const StepParams &p, double *partials, hipStream_t s);
 // rotary embedding of the block's queries (q_rows rows) and keys (k_rows rows), Bt tokens per (sequence,
 // head) at positions pos0 + j, by the caller's float tables [position][D / 2]

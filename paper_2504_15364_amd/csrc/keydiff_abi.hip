@@ -427,12 +427,24 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
         }
     }
     const bool deferred = defer && evict;
+    // a selection that rode in this step's attention launch wrote its destination map: the rows of an
+    // ORDERED carrier's cache are shifted after that launch -- inside this step's merge launch where
+    // there is one (the shift is bound by memory traffic, the merge leaves the memory system idle)
+    bool shift_owed = riding && carry->cfg.layout == KEYDIFF_LAYOUT_ORDERED;
     if (deferred) {
         if (p.merge_wgs > 0) {
             kd::StepParams pm = p;
             pm.do_evict = 0;   // the merge half of step_post only
             ProfScope ps(c, KEYDIFF_K_POST, s);
-            KD_LAUNCH(kd::launch_step_post(pm, s), "step_post kernel (merge)");
+            if (shift_owed && carry->pend.D == p.D) {
+                carry->epoch = carry->epoch == 0x7fffffff ? 1 : carry->epoch + 1;
+                KD_LAUNCH(kd::launch_merge_shift(pm, carry->pend, reinterpret_cast<int32_t *>(carry->meta + carry->L.off_oflags),
+                                                 carry->epoch, s),
+                          "merge + ordered compaction kernel");
+                shift_owed = false;
+            } else {
+                KD_LAUNCH(kd::launch_step_post(pm, s), "step_post kernel (merge)");
+            }
         }
         c->pending = true;
         c->pend = p;
@@ -446,9 +458,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     }
     if (evict && !deferred && cf.layout == KEYDIFF_LAYOUT_ORDERED)
         if (int rc = compact_ordered(c, p, s)) return rc;
-    // a selection that rode in this step's launch wrote its destination map: the rows of an ORDERED
-    // carrier's cache are shifted now, after this step's output is complete
-    if (riding && carry->cfg.layout == KEYDIFF_LAYOUT_ORDERED)
+    if (shift_owed)   // ... else in a launch of its own
         if (int rc = compact_ordered(carry, carry->pend, s)) return rc;
     if (c->profiling) ProfScope ps(c, KEYDIFF_K_EVENT_PAIR, s);
     c->plan[0] = p.psplits;
