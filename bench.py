@@ -254,12 +254,12 @@ def main():
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     w = get_config(args.workload)
-    if w.block_B == 1:
-        return bench_decode(args, w)
     if args.budget:
         if args.budget % w.block_B or args.budget < w.block_B:
             sys.exit(f"--budget must be a positive multiple of the block size {w.block_B}")
         w = w.small(budget_N=args.budget, prompt_T=max(w.prompt_T, 4 * args.budget))
+    if w.block_B == 1:
+        return bench_decode(args, w)
     L = args.layers or w.n_layers
     B, N, D, Hq, Hkv = w.block_B, w.budget_N, w.head_dim, w.n_q_heads, w.n_kv_heads
     fill_blocks = N // B

@@ -14,10 +14,24 @@ FLAGS = [
     "-ffp-contract=off",   # the deciding score is plain IEEE double arithmetic
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage",   # the compiler reports every kernel's registers and scratch: checked below
 ]
 
 
 TIMELINE_LIB = os.path.join(HERE, "libkeydiff_timeline.so")
+
+
+def scratch_users(remarks):
+    """(kernel, bytes per lane) of every kernel whose resource-usage remarks report scratch memory."""
+    found, name = [], None
+    for l in remarks:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l:
+            n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if n:
+                found.append((name, n))
+    return found
 
 
 def build(verbose: bool = False, timeline: bool = False) -> str:
@@ -36,9 +50,20 @@ def build(verbose: bool = False, timeline: bool = False) -> str:
         objs.append(obj)
     for src, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "not a recognized feature" not in l)
+        lines = out.splitlines()
+        spilled = scratch_users(lines)
+        out = "\n".join(l for l in lines if "not a recognized feature" not in l and "kernel-resource-usage" not in l)
         if p.returncode:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        if spilled and timeline:
+            # (the stamps cost registers: tolerated in the profiling build, whose timings of such a kernel do not count)
+            print(f"warning: {src}: kernels that use scratch memory in the profiling build: "
+                  + ", ".join(f"{k} ({b} bytes/lane)" for k, b in spilled), file=sys.stderr)
+        elif spilled:
+            # A kernel that touches scratch memory (spilled registers, or a parameter block the compiler
+            # could not keep in registers) runs several times slower on this chip (measured: 4x on the
+            # generation-phase attention, 30x on the ordered shift): refuse to build one.
+            raise RuntimeError(f"{src}: kernels that use scratch memory: " + ", ".join(f"{k} ({b} bytes/lane)" for k, b in spilled))
         if verbose and out.strip():
             print(out)
     lib = TIMELINE_LIB if timeline else LIB

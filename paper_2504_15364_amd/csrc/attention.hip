@@ -915,12 +915,16 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 #pragma unroll
                         for (int db = 0; db < NDB; ++db) vfr[(kc + 1) & 1][db] = read_v(tV, (kc + 1) * NDB + db);
                     }
+                    // the chunk's slices step by step, not slice by slice: the SPK instructions of a step
+                    // are independent of each other, so none waits for the one before it (this wave is
+                    // alone on its SIMD for the length of the chain)
+                    float fa[SPK][SL], fe[SPK][SL];
 #pragma unroll
-                    for (int g = kc * SPK; g < (kc + 1) * SPK; ++g) {
-                        slice_F(s, g, arg[g & 1][0]);
-                        slice_E(arg[g & 1][0], ex[g & 1][0]);
-                        slice_C(ex[g & 1][0], g, pk);
-                    }
+                    for (int i = 0; i < SPK; ++i) slice_F(s, kc * SPK + i, fa[i]);
+#pragma unroll
+                    for (int i = 0; i < SPK; ++i) slice_E(fa[i], fe[i]);
+#pragma unroll
+                    for (int i = 0; i < SPK; ++i) slice_C(fe[i], kc * SPK + i, pk);
 #pragma unroll
                     for (int db = 0; db < NDB; ++db)
                         oacc[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kc & 1][db], pk[0][kc], oacc[0][db], 0, 0, 0);
@@ -933,6 +937,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 tile_max(s, mloc);
                 new_reference(mloc);
             }
+#ifdef KD_TIMELINE
+            if (t == t0 + 2) KD_TL(17);   // wave 0: weights and product with V of its tile done
+            if (t == t0 + 3) KD_TL(21);   // wave 0: logits of its next tile done
+#endif
             return;
         } else {
         if (NEXT) {

@@ -114,3 +114,18 @@ def test_wrapper_refuses_tensors_smaller_than_the_configuration():
     check_rope_tables(cfg, cos, cos)
     with pytest.raises(ValueError):
         check_rope_tables(cfg, cos[:, :16].contiguous(), cos)
+
+
+def test_build_refuses_kernels_that_use_scratch_memory():
+    """The build reads the compiler's per-kernel resource remarks and fails on any kernel with scratch
+    memory (such a kernel runs several times slower on this chip): the parser on remarks as hipcc prints them."""
+    from paper_2504_15364_amd.build import scratch_users
+
+    remarks = """evict.hip:387:1: remark: Function Name: _ZN2kd17ksum_final_kernelEPKdPdii [-Rpass-analysis=kernel-resource-usage]
+evict.hip:387:1: remark:     VGPRs: 12 [-Rpass-analysis=kernel-resource-usage]
+evict.hip:387:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+evict.hip:255:1: remark: Function Name: _ZN2kd22compact_ordered_kernelILi128EEEvNS_10StepParamsEPiii [-Rpass-analysis=kernel-resource-usage]
+evict.hip:255:1: remark:     ScratchSize [bytes/lane]: 700 [-Rpass-analysis=kernel-resource-usage]
+evict.hip:255:1: remark:     Occupancy [waves/SIMD]: 4 [-Rpass-analysis=kernel-resource-usage]""".splitlines()
+    assert scratch_users(remarks) == [("_ZN2kd22compact_ordered_kernelILi128EEEvNS_10StepParamsEPiii", 700)]
+    assert scratch_users(remarks[:3]) == []
