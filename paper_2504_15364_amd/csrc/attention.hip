@@ -407,9 +407,9 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
             double x[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint32_t wi = w[ps][i];
-                x[2 * i] = live ? bf16_lo(wi) : 0.0;
-                x[2 * i + 1] = live ? bf16_hi(wi) : 0.0;
+                const uint32_t wi = live ? w[ps][i] : 0u;   // (a row past the block adds zeros)
+                x[2 * i] = bf16_lo(wi);
+                x[2 * i + 1] = bf16_hi(wi);
             }
             double inv = 1.0;
             if (p.anchor_mode == 1) {  // unit keys (Eq. 7): x / |k_j|, a zero key adds nothing
