@@ -272,6 +272,15 @@ def test_block_larger_than_the_budget(layout):
     run_prompt(w, data, 16, 64, layout=layout)
 
 
+@pytest.mark.parametrize("d,N,B,T", [(128, 640, 600, 1900), (64, 768, 700, 2200)], ids=["d128", "d64"])
+def test_blocks_longer_than_the_rows_requested_up_front(d, N, B, T):
+    # the attention kernel requests the first 256 (d = 128) or 512 (d = 64) rows of a block ahead of its
+    # tile copies for the key sum; longer blocks take further batches, and a ragged last one
+    w = get_config("toy").small(n_q_heads=2, n_kv_heads=1, head_dim=d, prompt_T=T)
+    data = make_layer(w, seed=16 + d)
+    run_prompt(w, data, N, B, layout=kd.LAYOUT_FILL)
+
+
 def test_single_tokens_from_an_empty_cache():
     # B = 1 from the first token on: one-key attention, then one eviction per step once full
     w = get_config("toy").small(n_q_heads=4, n_kv_heads=2, head_dim=128, prompt_T=40)
