@@ -160,8 +160,8 @@ KEYDIFF_API int keydiff_prefill_block_static(keydiff_cache_t *cache, const void 
  * before it), so after the call `carry` has none.  Until its eviction is enqueued the rows of
  * `cache` are the n = len + Bt rows before compaction and its scratch buffer is in use: a
  * cache used this way needs a scratch buffer of its own.  In the ORDERED layout only the
- * selection rides; the stable row shift of `carry` follows as a launch of its own, enqueued by
- * the same call.  The scores and the retained set are those
+ * selection rides; the stable row shift of `carry` follows in the same call, inside this step's
+ * merge launch (or in a launch of its own where the step has none).  The scores and the retained set are those
  * of keydiff_prefill_block bit for bit; `out` may differ in the last bf16 bit, because the
  * keys are cut into a different number of ranges when passengers take part of the chip.    */
 KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const void *q, const void *k_new,
@@ -176,7 +176,13 @@ KEYDIFF_API int keydiff_prefill_block_deferred(keydiff_cache_t *cache, const voi
  * pending): every layer's selection and compaction runs inside the next layer's attention
  * launch, and the last layer's stays pending until the next block (or keydiff_finish, or any
  * other call on that cache).  With n_layers == 1 nothing can be carried and the eviction is
- * enqueued at the start of the next call on the cache.  All pointers are checked before
+ * enqueued at the start of the next call on the cache.  ORDERED layout with three layers or more:
+ * the stable row shift of layer l, whose selection rode in the launch of layer l + 1, rides in the
+ * attention launch of layer l + 2 where the shapes allow it (a block that evicts at most 128 rows,
+ * 256-row query tiles that are full, the same head_dim), so after the call the shifts of the last
+ * two layers may still be pending as well; like a pending eviction, a pending shift is enqueued
+ * first by any other call on its cache, and the rows of such a cache are not in position order
+ * until then.  All pointers are checked before
  * anything is enqueued; an error met later (a state error of one layer) leaves the layers
  * before it enqueued and returns that layer's code.  The caches must be distinct.          */
 KEYDIFF_API int keydiff_prefill_block_layers(keydiff_cache_t *const *caches, int32_t n_layers,
@@ -223,8 +229,9 @@ KEYDIFF_API int keydiff_cache_len(const keydiff_cache_t *cache, int32_t *len);
 
 /* How the last block step on `cache` was cut up for the chip (host values, no sync): plan_out[0] the
  * number of key ranges (split-KV partials per output row the merge adds up; 1 = no merge launch),
- * [1] workgroups of 256 query rows per KV head, [2] 64-key tiles of the step, [3] 1 if the step's
- * launch carried another cache's pending eviction.  For byte and launch accounting by a benchmark.  */
+ * [1] workgroups of 256 query rows per KV head, [2] 64-key tiles of the step, [3] bit 0: the step's
+ * launch carried another cache's pending eviction, bit 1: it carried another cache's pending row
+ * shift (ORDERED layout).  For byte and launch accounting by a benchmark.  */
 KEYDIFF_API int keydiff_cache_plan(const keydiff_cache_t *cache, int32_t plan_out[4]);
 
 /* Token position of every cached row: pos_out int32 [batch][n_kv_heads][len] (device). */

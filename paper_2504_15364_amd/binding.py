@@ -313,7 +313,7 @@ class KeyDiffCache:
         return n.value
 
     def plan(self):
-        """(key ranges, row tiles per head, key tiles, carried a passenger) of the last block step."""
+        """(key ranges, row tiles per head, key tiles, passengers: bit 0 a selection, bit 1 a row shift) of the last block step."""
         out = (C.c_int32 * 4)()
         _check(self._L.keydiff_cache_plan(self._h, out))
         return tuple(out)

@@ -43,6 +43,7 @@
 #include "kd_kernels.h"
 #include "kd_device.h"
 #include "kd_select.h"
+#include "kd_shift.h"
 
 namespace kd {
 
@@ -1230,6 +1231,31 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepPara
     step_main_body<D, HELP, false>(p, (int)blockIdx.x - ncarry);
 }
 
+// The same with a third kind of workgroup behind the selection's: `ride.nshift` workgroups that shift
+// the rows of an ORDERED cache whose selection ran in an earlier launch (kd_shift.h).  The shift is
+// bound by memory traffic the attention leaves unused; it holds the compute units the plan left to
+// it for about as long as the attention holds the others.  A kernel of its own, so that the
+// launches without a shift keep their code as it is.  (Not for launches with helper waves: their
+// attention body leaves no registers to spare, and with this kernel's larger argument block it spilled.)
+template <int D>
+__global__ __launch_bounds__(CARRY_THREADS) void step_main_ride_kernel(StepParams p, StepParams cy, int ncarry, int cy_res, ShiftRide ride)
+{
+    if ((int)blockIdx.x < ncarry) {
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+        PostShared &sh = *reinterpret_cast<PostShared *>(smem);
+        unsigned char *dyn = smem + carry_shared_bytes();
+        if (cy_res) select_and_compact<D, true, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
+        else select_and_compact<D, false, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
+        return;
+    }
+    if ((int)blockIdx.x < ncarry + ride.nshift) {
+        const int i = (int)blockIdx.x - ncarry, heads = ride.p.batch * ride.p.hkv;
+        shift_range<D, CARRY_THREADS>(ride.p, ride.flags, ride.nchunks, ride.epoch, i % heads, i / heads, ride.parts);
+        return;
+    }
+    step_main_body<D, false, false>(p, (int)blockIdx.x - ncarry - ride.nshift);
+}
+
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
 // dynamic LDS the carrying kernel may ask for: what 160 KB per compute unit leaves next to the
 // static tables of the attention body (below 20 KB)
@@ -1261,6 +1287,8 @@ hipError_t configure_main_kernels()
     KD_SET((step_main_carry_kernel<128, true>))
     KD_SET((step_main_carry_kernel<64, false>))
     KD_SET((step_main_carry_kernel<64, true>))
+    KD_SET((step_main_ride_kernel<128>))
+    KD_SET((step_main_ride_kernel<64>))
 #undef KD_SET
     return hipSuccess;
 }
@@ -1313,6 +1341,31 @@ hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hip
     if (p.D == 128) { KD_GO(128) }
     else if (p.D == 64) { KD_GO(64) }
 #undef KD_GO
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+bool can_host_shift(const StepParams &p, const StepParams &shifted)
+{
+    const int E = shifted.n - shifted.N;
+    return p.NW == 8 && p.psplits == p.splits && !main_runs_help(p) && p.D == shifted.D && E > 0 && E <= ORD_ROWS;
+}
+
+hipError_t launch_step_main_ride(const StepParams &p, const StepParams *cy, const ShiftRide &ride, hipStream_t s)
+{
+    if (!can_host_shift(p, ride.p) || ride.nshift < 1 || ride.parts < 1) return hipErrorInvalidValue;
+    if (cy && !can_carry(p, *cy)) return hipErrorInvalidValue;
+    const int ncarry = cy ? cy->batch * cy->hkv : 0;
+    const int grid = ncarry + ride.nshift + p.batch * p.hkv * p.mtiles * p.splits;
+    StepParams cyl = cy ? *cy : p;
+#ifdef KD_TIMELINE
+    cyl.timeline = p.timeline;   // one record per workgroup of the launch that stamps (the shifting ones do not)
+#endif
+    const int res = cy && carry_need(*cy, true) <= CARRY_DYN_MAX && !cy->argmax_rec ? 1 : 0;
+    const size_t need = cy ? carry_need(*cy, res != 0) : 0;
+    const size_t lds = need > main_lds_bytes(p.D) ? need : main_lds_bytes(p.D);
+    if (p.D == 128) hipLaunchKernelGGL((step_main_ride_kernel<128>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res, ride);
+    else if (p.D == 64) hipLaunchKernelGGL((step_main_ride_kernel<64>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res, ride);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -81,6 +81,18 @@ hipError_t launch_step_main(const StepParams &p, hipStream_t s);
 // the row shift afterwards); can_carry says whether the pair fits
 bool can_carry(const StepParams &p, const StepParams &cy);
 hipError_t launch_step_main_carry(const StepParams &p, const StepParams &cy, hipStream_t s);
+// An ORDERED cache's row shift riding in an attention launch: `p` is the step whose selection wrote the
+// destination map, `parts` workgroups per head share the head's chunks (flags, epoch: as for
+// launch_compact_ordered).  can_host_shift says whether the attention step `p` can take it along.
+struct ShiftRide {
+    StepParams p;
+    int32_t *flags;
+    int nchunks, parts, nshift;
+    int32_t epoch;
+};
+bool can_host_shift(const StepParams &p, const StepParams &shifted);
+// step_main of `p` with passengers: the selection `cy` (or none: nullptr) and the shift `ride`
+hipError_t launch_step_main_ride(const StepParams &p, const StepParams *cy, const ShiftRide &ride, hipStream_t s);
 hipError_t launch_step_score(const StepParams &p, hipStream_t s);
 hipError_t launch_step_post(const StepParams &p, hipStream_t s);
 // flags: [BH][ceil(cap / ORD_ROWS)] int32 in zero-initialised device memory; epoch: a value no earlier launch used

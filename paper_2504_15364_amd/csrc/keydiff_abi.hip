@@ -165,6 +165,12 @@ struct keydiff_cache {
     bool pending;         // a deferred eviction (selection + compaction) has not been enqueued yet
     kd::StepParams pend;  // ... the parameters of the step it belongs to
     hipStream_t pend_stream;
+    // ORDERED layout, eviction deferred through keydiff_prefill_block_layers: the selection has run (it
+    // rode in another layer's attention launch) and the row shift by its destination map has not yet; it
+    // rides in a later attention launch, or is enqueued alone by the first call that touches this cache
+    bool shift_pending;
+    kd::StepParams shift_p;
+    hipStream_t shift_stream;
     int32_t plan[4];      // of the last block step: key ranges, row tiles per head, key tiles, carried a passenger
     bool profiling;
     std::vector<ProfEvent> events;
@@ -309,6 +315,35 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     p.merge_wgs = p.psplits > 1 ? (int)((merge_threads + kd::POST_THREADS - 1) / kd::POST_THREADS) : 0;
 }
 
+// Whether an attention launch shaped like `p` (of cache c) should take along the row shift `sp` describes,
+// next to `seats_sel` workgroups of a carried selection: returns the workgroups per head to give the
+// shift (0: do not), and leaves in p the plan of the attention that goes with the answer.
+// The shift gets about 7/32 of the compute units (56 of 256: measured alone, 56 workgroups of this
+// shape move the 66 MB of the 8192-row Llama-3.1-8B cache in 25 us, 40 in 33 us, i.e. ~48 GB/s each);
+// the attention gives up key ranges for it and runs longer (12 us + 2.2 us per 64-key tile of its
+// longest workgroup, from the in-kernel stamps).  Taking the shift along pays when that costs less
+// than the ~12 us the shift adds to the merge launch otherwise.
+int plan_with_shift(const keydiff_cache *c, kd::StepParams &p, const kd::StepParams &sp, int seats_sel)
+{
+    const int target = c->L.target_wgs / 2;
+    plan_attention(c, p, seats_sel);
+    const double att_alone = 12.0 + 2.2 * ((p.ntiles + p.splits - 1) / p.splits);
+    const int heads = sp.batch * sp.hkv;
+    const int nchunks = (sp.n + kd::ORD_ROWS - 1) / kd::ORD_ROWS;
+    int parts = (target * 7 / 32) / heads;
+    if (parts > nchunks) parts = nchunks;
+    if (parts < 1 || !kd::can_host_shift(p, sp)) return 0;
+    kd::StepParams ph = p;
+    plan_attention(c, ph, seats_sel + parts * heads);
+    if (!kd::can_host_shift(ph, sp) || ph.batch * ph.hkv * ph.mtiles * ph.splits + seats_sel + parts * heads > target) return 0;
+    const double att_host = 12.0 + 2.2 * ((ph.ntiles + ph.splits - 1) / ph.splits);
+    const double bytes = 2.0 * 2.0 * heads * (double)sp.n * sp.D * 2.0;   // K and V, read and written
+    const double shift_us = 4.0 + bytes / (parts * heads * 48e3);
+    if ((att_host > shift_us ? att_host : shift_us) >= att_alone + 12.0) return 0;
+    p = ph;
+    return parts;
+}
+
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
 // ORDERED layout: the stable row shift that follows a selection, by the destination map it wrote
@@ -324,6 +359,10 @@ int compact_ordered(keydiff_cache *c, const kd::StepParams &p, hipStream_t s)
 // the pending selection and compaction of `c` as a launch of its own
 int finish_pending(keydiff_cache *c, hipStream_t s)
 {
+    if (c->shift_pending) {   // (never together with a pending selection: a new step of the cache comes through here first)
+        c->shift_pending = false;
+        if (int rc = compact_ordered(c, c->shift_p, c->shift_stream)) return rc;
+    }
     if (!c->pending) return KEYDIFF_OK;
     kd::StepParams p = c->pend;
     p.merge_wgs = 0;
@@ -350,8 +389,11 @@ struct Rope {
 
 int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v_new, int32_t Bt, int64_t pos0,
                void *out, float *scores_out, bool defer, keydiff_cache *carry, unsigned char *work, hipStream_t s,
-               const Rope *rope = nullptr)
+               const Rope *rope = nullptr, keydiff_cache *shifted = nullptr, bool later_launches_take_shifts = false)
 {
+    // shifted: another ORDERED cache whose pending row shift this step's attention launch may take along;
+    // later_launches_take_shifts: the caller goes on to steps that will be offered this step's carry as
+    // `shifted`, so its shift may stay pending instead of running inside this step's merge launch
     if (!c || !q || !k_new || !v_new || !out) return fail(KEYDIFF_EINVAL, "null pointer");
     if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(out))
         return fail(KEYDIFF_EINVAL, "tensors must be 16-byte aligned");
@@ -386,13 +428,24 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
 
     // a passenger rides only if the attention still fits the chip in one round beside it
     bool riding = false;
-    if (carry && carry->pending && carry->pend_stream == s) {
-        const int seats = carry->cfg.batch * carry->cfg.n_kv_heads;
+    const bool sel_offered = carry && carry->pending && carry->pend_stream == s;
+    const int seats = sel_offered ? carry->cfg.batch * carry->cfg.n_kv_heads : 0;
+    // ... first the row shift of `shifted` (with the selection, if one is offered and fits as well)
+    int shift_parts = 0;
+    if (shifted && shifted != c && shifted != carry && shifted->shift_pending && shifted->shift_stream == s) {
+        shift_parts = plan_with_shift(c, p, shifted->shift_p, seats);
+        if (shift_parts > 0 && sel_offered) {
+            if (kd::can_carry(p, carry->pend)) riding = true;
+            else shift_parts = 0;   // (the selection is the passenger that must not be left behind)
+        }
+    }
+    if (shift_parts == 0 && sel_offered) {
         plan_attention(c, p, seats);
         riding = kd::can_carry(p, carry->pend) &&
                  p.batch * p.hkv * p.mtiles * p.splits + seats <= c->L.target_wgs / 2;
     }
-    if (!riding) plan_attention(c, p);
+    if (shift_parts == 0 && !riding) plan_attention(c, p);
+    const int shift_wgs = shift_parts > 0 ? shift_parts * shifted->shift_p.batch * shifted->shift_p.hkv : 0;
     // Generation phase: the attention launch's scoring waves (the kernels with helper waves) leave the
     // arg-max of the scores per workgroup, and the selection reads the row to evict off those records.
     if (evict && n - N == 1 && cf.window_W == 0 && cf.layout == KEYDIFF_LAYOUT_FILL &&
@@ -415,11 +468,24 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     if (carry && carry->pending && !riding)
         if (int rc = finish_pending(carry, carry->pend_stream)) return rc;
 #ifdef KD_TIMELINE
-    p.timeline = timeline_slot((long)p.batch * p.hkv * p.mtiles * p.splits + (riding ? carry->pend.batch * carry->pend.hkv : 0));
+    p.timeline = timeline_slot((long)p.batch * p.hkv * p.mtiles * p.splits + (riding ? carry->pend.batch * carry->pend.hkv : 0) + shift_wgs);
 #endif
     {
         ProfScope ps(c, KEYDIFF_K_MAIN, s);
-        if (riding) {
+        if (shift_parts > 0) {
+            kd::ShiftRide ride;
+            ride.p = shifted->shift_p;
+            ride.flags = reinterpret_cast<int32_t *>(shifted->meta + shifted->L.off_oflags);
+            ride.nchunks = (ride.p.n + kd::ORD_ROWS - 1) / kd::ORD_ROWS;
+            ride.parts = shift_parts;
+            ride.nshift = shift_wgs;
+            shifted->epoch = shifted->epoch == 0x7fffffff ? 1 : shifted->epoch + 1;
+            ride.epoch = shifted->epoch;
+            KD_LAUNCH(kd::launch_step_main_ride(p, riding ? &carry->pend : nullptr, ride, s),
+                      "step_main kernel (with carried selection and row shift)");
+            shifted->shift_pending = false;
+            if (riding) carry->pending = false;
+        } else if (riding) {
             KD_LAUNCH(kd::launch_step_main_carry(p, carry->pend, s), "step_main kernel (with carried selection)");
             carry->pending = false;
         } else {
@@ -431,6 +497,16 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     // ORDERED carrier's cache are shifted after that launch -- inside this step's merge launch where
     // there is one (the shift is bound by memory traffic, the merge leaves the memory system idle)
     bool shift_owed = riding && carry->cfg.layout == KEYDIFF_LAYOUT_ORDERED;
+    // ... or, when the caller goes on to launches that can take it along, inside one of those
+    if (shift_owed && later_launches_take_shifts) {
+        kd::StepParams probe = p;
+        if (plan_with_shift(c, probe, carry->pend, seats) > 0) {   // (a later launch is taken to look like this one)
+            carry->shift_pending = true;
+            carry->shift_p = carry->pend;
+            carry->shift_stream = s;
+            shift_owed = false;
+        }
+    }
     if (deferred) {
         if (p.merge_wgs > 0) {
             kd::StepParams pm = p;
@@ -464,7 +540,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     c->plan[0] = p.psplits;
     c->plan[1] = p.mtiles;
     c->plan[2] = p.ntiles;
-    c->plan[3] = riding ? 1 : 0;
+    c->plan[3] = (riding ? 1 : 0) | (shift_parts > 0 ? 2 : 0);
     c->kpar ^= 1;   // step_main wrote the new key sum into the other half
     c->len = evict ? N : n;
     c->contiguous = contiguous;
@@ -528,6 +604,7 @@ int keydiff_init_cache(const keydiff_config_t *cfg, void *k_cache, void *v_cache
     c->kpar = 0;
     c->epoch = 0;
     c->pending = false;
+    c->shift_pending = false;
     c->pend_stream = nullptr;
     for (int32_t &x : c->plan) x = 0;
     static hipError_t configured = kd::configure_kernels();  // once per process
@@ -624,8 +701,11 @@ static int block_layers(keydiff_cache_t *const *caches, int32_t n_layers, const 
     for (int l = 0; l < n_layers; ++l) {
         // layer 0 takes along what the last layer left pending at the previous block
         keydiff_cache *carry = n_layers > 1 ? caches[(l + n_layers - 1) % n_layers] : nullptr;
+        // ... and, ORDERED layout, the row shift of the layer before that one, whose selection rode in the
+        // launch of the layer between them
+        keydiff_cache *shifted = n_layers > 2 ? caches[(l + n_layers - 2) % n_layers] : nullptr;
         if (int rc = block_step(caches[l], q[l], k_new[l], v_new[l], Bt, pos0, out[l], nullptr, true, carry,
-                                caches[l]->scratch, s, rope))
+                                caches[l]->scratch, s, rope, shifted, n_layers > 2))
             return rc;
     }
     return KEYDIFF_OK;

@@ -189,6 +189,52 @@ def test_llama31_8b_shape_whole_prompt_through_the_layers_call_with_the_bench_se
     assert alone == evicting // 16, f"{alone} evictions ran alone; expected the {evicting // 16} the test forced"
 
 
+def test_llama31_8b_shape_ordered_layout_through_the_layers_call():
+    # the ORDERED layout the way bench.py's "deferred_ordered" mode runs it: caches loaded at the budget,
+    # steady-state blocks through four layers in one call per block; the row shift of layer l rides in the
+    # attention launch of layer l + 2 (56 workgroups next to 192 of the attention and 8 of a selection)
+    w = get_config("llama31_8b")
+    B, N, L, steps = w.block_B, w.budget_N, 4, 6
+    T = N + steps * B
+    caches, ocs, datas, dev = [], [], [], []
+    for l in range(L):
+        data = make_layer(w, seed=BENCH_SEED + l, layer=l, t1=T)
+        cache = kd.KeyDiffCache(kd.KeyDiffConfig(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B, layout=kd.LAYOUT_ORDERED))
+        oc = oracle.OracleCache(1, w.n_q_heads, w.n_kv_heads, w.head_dim, N, B)
+        K0 = data["k"][:N].transpose(1, 0, 2)[None].copy()
+        V0 = data["v"][:N].transpose(1, 0, 2)[None].copy()
+        P0 = np.broadcast_to(np.arange(N, dtype=np.int32), (1, w.n_kv_heads, N)).copy()
+        cache.load(to_dev(K0), to_dev(V0), torch.from_numpy(P0).cuda())
+        oc.load(K0, V0, P0)
+        caches.append(cache), ocs.append(oc), datas.append(data)
+        dev.append(tuple(dev_blocks(data[x][N:], B) for x in ("q", "k", "v")))
+    sampled = {(0, 0), (1, 2), (3, 1), (steps - 1, L - 1)}
+    hosted = 0
+    for i in range(steps):
+        t = N + i * B
+        outs = kd.prefill_block_layers(caches, [d[0][i] for d in dev], [d[1][i] for d in dev], [d[2][i] for d in dev], t)
+        plans = [c.plan() for c in caches]
+        hosted += sum(1 for pl in plans if pl[3] & 2)
+        if i >= 1:
+            assert all(pl[3] & 2 for pl in plans), f"block {i}: a launch took no row shift along: {plans}"
+            assert all(pl[0] == 12 for pl in plans), plans     # 12 key ranges x 16 + 8 + 56 workgroups = 256
+        for l in range(L):
+            q = block_of(datas[l]["q"], t, B)[None] if (i, l) in sampled else None
+            ref, _, ev = ocs[l].prefill_block(q, block_of(datas[l]["k"], t, B)[None], block_of(datas[l]["v"], t, B)[None], t)
+            assert ev == B
+            if q is not None:
+                err = float(np.abs(bf16_out_to_f32(outs[l]) - ref).max())
+                assert err <= ATTN_ATOL, f"attention error {err}, step {i}, layer {l}"
+    for l in range(L):
+        pos, K, V = rows_by_position(caches[l])   # finishes what is still pending
+        assert np.array_equal(pos, ocs[l].positions()), f"retained set of layer {l} differs"
+        assert np.array_equal(K, ocs[l].keys()) and np.array_equal(V, ocs[l].values())
+        assert np.all(np.diff(caches[l].positions().cpu().numpy(), axis=-1) > 0), "rows not in position order"
+        assert caches[l].status() == 0
+        caches[l].close()
+    assert hosted >= (steps - 1) * L
+
+
 @pytest.mark.parametrize("layout", [kd.LAYOUT_FILL, kd.LAYOUT_ORDERED], ids=["fill", "ordered"])
 def test_llama31_8b_shape_deferred_eviction_across_layers(layout):
     # the headline workload the way bench.py runs it by default: caches loaded at the budget, then

@@ -451,6 +451,39 @@ def test_block_through_all_layers_in_one_call():
     cache.close()
 
 
+@pytest.mark.parametrize("check_every", [0, 3], ids=["undisturbed", "states-read-in-between"])
+def test_ordered_layers_call_shifts_inside_later_attention_launches(check_every):
+    # ORDERED layout through keydiff_prefill_block_layers with three layers or more: the selection of layer
+    # l rides in the attention launch of layer l + 1 and the stable row shift by its destination map in
+    # that of layer l + 2 (workgroups that own a range of 128-row chunks each).  Reading a cache's state
+    # in between runs whatever is still pending for it in launches of its own.
+    w = get_config("llama31_8b").small(n_q_heads=8, n_kv_heads=2, prompt_T=2048)
+    N, B, nl = 1024, 128, 4      # 9 chunks per head: ranges of one and of two chunks
+    layers = [make_pair(w, N, B, layout=kd.LAYOUT_ORDERED) for _ in range(nl)]
+    datas = [make_layer(w, seed=131 + l) for l in range(nl)]
+    caches = [c for c, _ in layers]
+    hosted = 0
+    for bi, steps in enumerate(zip(*(blocks(d, B) for d in datas))):
+        t = steps[0][0]
+        outs = kd.prefill_block_layers(caches, [to_dev(s[2]) for s in steps], [to_dev(s[3]) for s in steps],
+                                       [to_dev(s[4]) for s in steps], t)
+        hosted += sum(1 for c in caches if c.plan()[3] & 2)
+        for (cache, oc), (_, Bt, q, k, v), out in zip(layers, steps, outs):
+            ref, _, _ = oc.prefill_block(q, k, v, t)
+            err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+            assert err <= ATTN_ATOL, f"attention error {err} in block at token {t}"
+        if check_every and bi % check_every == check_every - 1:
+            for li, (cache, oc) in enumerate(layers):
+                check_state(cache, oc, f"layer {li} after block {bi}")
+                assert np.all(np.diff(cache.positions().cpu().numpy(), axis=-1) > 0), "rows not in position order"
+    for li, (cache, oc) in enumerate(layers):
+        check_state(cache, oc, f"layer {li} at the end")
+        assert np.all(np.diff(cache.positions().cpu().numpy(), axis=-1) > 0), "rows not in position order"
+        assert cache.status() == 0
+        cache.close()
+    assert hosted >= 8, f"only {hosted} attention launches took a row shift along"
+
+
 def test_deferred_eviction_rides_a_launch_with_helper_waves():
     # G * B = 384 rows per KV head: 8-wave workgroups of which the second row tile fills only half,
     # so the attention runs its helper-wave variant; passengers ride in that one too
