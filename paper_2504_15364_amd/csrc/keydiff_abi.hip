@@ -330,7 +330,7 @@ int plan_with_shift(const keydiff_cache *c, kd::StepParams &p, const kd::StepPar
     const double att_alone = 12.0 + 2.2 * ((p.ntiles + p.splits - 1) / p.splits);
     const int heads = sp.batch * sp.hkv;
     const int nchunks = (sp.n + kd::ORD_ROWS - 1) / kd::ORD_ROWS;
-    int parts = (target * 7 / 32) / heads;
+    int parts = (target * 7 / 32) / heads;   // (measured at the headline shape: 5/32 42.3, 6/32 39.2, 7/32 38.6, 8/32 39.8 us per step)
     if (parts > nchunks) parts = nchunks;
     if (parts < 1 || !kd::can_host_shift(p, sp)) return 0;
     kd::StepParams ph = p;
