@@ -1237,9 +1237,15 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepPara
 // it for about as long as the attention holds the others.  A kernel of its own, so that the
 // launches without a shift keep their code as it is.  (Not for launches with helper waves: their
 // attention body leaves no registers to spare, and with this kernel's larger argument block it spilled.)
+// (The workgroup counts come first in the argument block, in one cache line: a workgroup finds its role
+// with a single trip to the freshly written, cold argument memory instead of one per count.)
+struct RideCounts {
+    int ncarry, cy_res, nshift;
+};
 template <int D>
-__global__ __launch_bounds__(CARRY_THREADS) void step_main_ride_kernel(StepParams p, StepParams cy, int ncarry, int cy_res, ShiftRide ride)
+__global__ __launch_bounds__(CARRY_THREADS) void step_main_ride_kernel(RideCounts cnt, StepParams p, StepParams cy, ShiftRide ride)
 {
+    const int ncarry = cnt.ncarry, cy_res = cnt.cy_res, nshift = cnt.nshift;
     if ((int)blockIdx.x < ncarry) {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
         PostShared &sh = *reinterpret_cast<PostShared *>(smem);
@@ -1248,12 +1254,12 @@ __global__ __launch_bounds__(CARRY_THREADS) void step_main_ride_kernel(StepParam
         else select_and_compact<D, false, CARRY_THREADS>(cy, sh, dyn, (int)blockIdx.x);
         return;
     }
-    if ((int)blockIdx.x < ncarry + ride.nshift) {
+    if ((int)blockIdx.x < ncarry + nshift) {
         const int i = (int)blockIdx.x - ncarry, heads = ride.p.batch * ride.p.hkv;
         shift_range<D, CARRY_THREADS>(ride.p, ride.flags, ride.nchunks, ride.epoch, i % heads, i / heads, ride.parts);
         return;
     }
-    step_main_body<D, false, false>(p, (int)blockIdx.x - ncarry - ride.nshift);
+    step_main_body<D, false, false>(p, (int)blockIdx.x - ncarry - nshift);
 }
 
 static size_t main_lds_bytes(int D) { return (size_t)STAGES * 2 * TILE_KEYS * D * 2; }
@@ -1364,8 +1370,9 @@ hipError_t launch_step_main_ride(const StepParams &p, const StepParams *cy, cons
     const int res = cy && carry_need(*cy, true) <= CARRY_DYN_MAX && !cy->argmax_rec ? 1 : 0;
     const size_t need = cy ? carry_need(*cy, res != 0) : 0;
     const size_t lds = need > main_lds_bytes(p.D) ? need : main_lds_bytes(p.D);
-    if (p.D == 128) hipLaunchKernelGGL((step_main_ride_kernel<128>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res, ride);
-    else if (p.D == 64) hipLaunchKernelGGL((step_main_ride_kernel<64>), dim3(grid), dim3(CARRY_THREADS), lds, s, p, cyl, ncarry, res, ride);
+    const RideCounts cnt{ncarry, res, ride.nshift};
+    if (p.D == 128) hipLaunchKernelGGL((step_main_ride_kernel<128>), dim3(grid), dim3(CARRY_THREADS), lds, s, cnt, p, cyl, ride);
+    else if (p.D == 64) hipLaunchKernelGGL((step_main_ride_kernel<64>), dim3(grid), dim3(CARRY_THREADS), lds, s, cnt, p, cyl, ride);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
