@@ -1205,6 +1205,7 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
 template <int D, bool HELP, bool ALT>
 __global__ __launch_bounds__(64 * MAIN_WAVES) void step_main_kernel(StepParams p)
 {
+    warm_arguments<sizeof(StepParams)>();
     step_main_body<D, HELP, ALT>(p, (int)blockIdx.x);
 }
 
@@ -1220,6 +1221,7 @@ __global__ __launch_bounds__(64 * MAIN_WAVES) void step_main_kernel(StepParams p
 template <int D, bool HELP>
 __global__ __launch_bounds__(CARRY_THREADS) void step_main_carry_kernel(StepParams p, StepParams cy, int ncarry, int cy_res)
 {
+    warm_arguments<2 * sizeof(StepParams) + 8>();   // both parameter blocks: the role is not known yet
     if ((int)blockIdx.x < ncarry) {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
         PostShared &sh = *reinterpret_cast<PostShared *>(smem);
@@ -1245,6 +1247,7 @@ struct RideCounts {
 template <int D>
 __global__ __launch_bounds__(CARRY_THREADS) void step_main_ride_kernel(RideCounts cnt, StepParams p, StepParams cy, ShiftRide ride)
 {
+    warm_arguments<sizeof(RideCounts) + 2 * sizeof(StepParams)>();
     const int ncarry = cnt.ncarry, cy_res = cnt.cy_res, nshift = cnt.nshift;
     if ((int)blockIdx.x < ncarry) {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem[];

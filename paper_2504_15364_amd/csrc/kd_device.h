@@ -29,6 +29,25 @@
 
 namespace kd {
 
+// The argument block of a launch was written by the host just before it and lies in no cache: every 64
+// bytes of it that a workgroup touches for the first time cost a trip to memory, and the compiler reads
+// the fields of a parameter structure where they are needed, one such trip after another (measured on
+// the attention launch: 1 us).  warm_arguments<BYTES>() requests one word of each cache line of the
+// first BYTES bytes at once, ahead of everything else, and waits for them: later reads find the lines
+// in the scalar cache.  (At most 8 lines; the words themselves are not used.)
+template <size_t BYTES>
+__device__ __forceinline__ void warm_arguments()
+{
+    constexpr int LINES = (int)((BYTES + 63) / 64) < 8 ? (int)((BYTES + 63) / 64) : 8;
+    const char *ka = (const char *)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t d[LINES];
+#pragma unroll
+    for (int i = 0; i < LINES; ++i) asm volatile("s_load_dword %0, %1, %2" : "=s"(d[i]) : "s"(ka), "n"(64 * i));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < LINES; ++i) asm volatile("" : : "s"(d[i]));   // the destination registers stay reserved until here
+}
+
 // Asynchronous 16-byte-per-lane copy global -> LDS (no registers).  `lds_base` is uniform over the
 // active lanes; lane i writes bytes [16 i, 16 i + 16) above it.  Issued through asm, so the compiler
 // does not count it: completion is awaited with an explicit s_waitcnt vmcnt (copies complete in
