@@ -234,6 +234,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void step_score_kernel(StepParams p)
 template <int D, bool RES>
 __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
 {
+    warm_arguments<sizeof(StepParams)>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __shared__ PostShared sh;
     const int n_select = p.do_evict ? p.batch * p.hkv : 0;
