@@ -239,7 +239,23 @@ __global__ __launch_bounds__(POST_THREADS) void step_post_kernel(StepParams p)
     __shared__ PostShared sh;
     const int n_select = p.do_evict ? p.batch * p.hkv : 0;
     if ((int)blockIdx.x >= n_select) {
+#ifdef KD_TIMELINE
+        unsigned long long *tl = reinterpret_cast<unsigned long long *>(&sh);   // (the selection's tables are not in use here)
+        if (threadIdx.x < 32) tl[threadIdx.x] = 0;
+        __syncthreads();
+        if (threadIdx.x == 0) tl[0] = wall_clock64();
+#endif
         merge_rows<D>(p, (size_t)(blockIdx.x - n_select) * POST_THREADS + threadIdx.x);
+#ifdef KD_TIMELINE
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            tl[12] = wall_clock64();
+            tl[31] = 4;   // record kind: merging workgroup
+        }
+        __syncthreads();
+        if (p.timeline && threadIdx.x < 32) p.timeline[(size_t)blockIdx.x * 32 + threadIdx.x] = tl[threadIdx.x];
+#endif
         return;
     }
     select_and_compact<D, RES, POST_THREADS>(p, sh, smem_raw, (int)blockIdx.x);

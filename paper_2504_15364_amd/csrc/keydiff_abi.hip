@@ -527,7 +527,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
         c->pend_stream = s;
     } else if (evict || p.merge_wgs > 0) {
 #ifdef KD_TIMELINE
-        p.timeline = timeline_slot((long)p.batch * p.hkv);   // the selection inside step_post records into the next slot
+        p.timeline = timeline_slot((long)(evict ? p.batch * p.hkv : 0) + p.merge_wgs);   // step_post records into the next slot
 #endif
         ProfScope ps(c, KEYDIFF_K_POST, s);
         KD_LAUNCH(kd::launch_step_post(p, s), "step_post kernel");

@@ -173,6 +173,8 @@ def main():
     summarise(1, ATTN_PHASES, "attention workgroups")
     summarise(2, SEL_PHASES, "carried selection workgroups" if args.eviction == "deferred"
               else "selection workgroups of step_post (a launch of its own after the attention)")
+    summarise(4, [(12, "partials merged, output stored and acknowledged (workgroup ends)")],
+              "merging workgroups of step_post")
     # when the attention workgroups end, by position in the grid: key split (workgroups of a split take
     # consecutive key tiles; the last split holds the block's own rows) and KV head
     BH = w.batch * Hkv
