@@ -272,6 +272,34 @@ def test_block_larger_than_the_budget(layout):
     run_prompt(w, data, 16, 64, layout=layout)
 
 
+def _random_configs(count, seed):
+    """Seeded draws of small shapes: group sizes 1-7, both head sizes, block sizes from 1 to a few tiles, budgets
+    from below one key tile to a dozen, ragged prompts, both layouts, both anchors, an occasional window."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        hkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 3, 4, 7]))
+        d = int(rng.choice([64, 128]))
+        B = int(rng.choice([1, 3, 16, 40, 64, 100, 128, 160]))
+        N = int(rng.integers(max(B // 2, 8), 700))
+        steps = int(rng.integers(3, 7)) if B > 1 else int(rng.integers(20, 40))
+        T = N + steps * B + int(rng.integers(0, B))
+        layout = int(rng.choice([kd.LAYOUT_FILL, kd.LAYOUT_ORDERED]))
+        anchor = int(rng.choice([kd.ANCHOR_MEAN_KEY, kd.ANCHOR_MEAN_UNIT_KEY]))
+        window = int(rng.integers(1, max(2, N // 4))) if rng.random() < 0.25 else 0
+        out.append(pytest.param(hkv * G, hkv, d, N, B, T, layout, anchor, window, 9000 + i,
+                                id=f"{i}-hq{hkv * G}-hkv{hkv}-d{d}-N{N}-B{B}-T{T}-l{layout}-a{anchor}-w{window}"))
+    return out
+
+
+@pytest.mark.parametrize("hq,hkv,d,N,B,T,layout,anchor,window,seed", _random_configs(16, 20250415))
+def test_seeded_random_small_configs(hq, hkv, d, N, B, T, layout, anchor, window, seed):
+    w = get_config("llama32_3b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
+    data = make_layer(w, seed=seed)
+    run_prompt(w, data, N, B, layout=layout, anchor_mode=anchor, window_W=window)
+
+
 @pytest.mark.parametrize("d,N,B,T", [(128, 640, 600, 1900), (64, 768, 700, 2200)], ids=["d128", "d64"])
 def test_blocks_longer_than_the_rows_requested_up_front(d, N, B, T):
     # the attention kernel requests the first 256 (d = 128) or 512 (d = 64) rows of a block ahead of its
@@ -484,6 +512,50 @@ def test_ordered_layers_call_shifts_inside_later_attention_launches(check_every)
         assert cache.status() == 0
         cache.close()
     assert hosted >= 8, f"only {hosted} attention launches took a row shift along"
+
+
+def _random_layer_configs(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        hkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 4, 7]))
+        d = int(rng.choice([64, 128]))
+        B = int(rng.choice([16, 64, 128, 256]))
+        N = B * int(rng.integers(1, 6)) + int(rng.choice([0, 0, 24]))
+        T = N + int(rng.integers(3, 6)) * B + int(rng.integers(0, B))
+        nl = int(rng.integers(2, 6))
+        layout = int(rng.choice([kd.LAYOUT_FILL, kd.LAYOUT_ORDERED]))
+        every = int(rng.choice([0, 2]))
+        out.append(pytest.param(hkv * G, hkv, d, N, B, T, nl, layout, every, 9500 + 10 * i,
+                                id=f"{i}-hq{hkv * G}-hkv{hkv}-d{d}-N{N}-B{B}-T{T}-layers{nl}-l{layout}-every{every}"))
+    return out
+
+
+@pytest.mark.parametrize("hq,hkv,d,N,B,T,nl,layout,every,seed", _random_layer_configs(10, 20250416))
+def test_seeded_random_configs_through_the_layers_call(hq, hkv, d, N, B, T, nl, layout, every, seed):
+    # keydiff_prefill_block_layers over drawn shapes: whichever way an eviction (and, ORDERED, its row shift) ends up
+    # being run -- riding in a later launch, inside a merge launch, or alone when a state is read -- the
+    # results are the oracle's
+    w = get_config("llama32_3b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
+    layers = [make_pair(w, N, B, layout=layout) for _ in range(nl)]
+    datas = [make_layer(w, seed=seed + l) for l in range(nl)]
+    caches = [c for c, _ in layers]
+    for bi, steps in enumerate(zip(*(blocks(dd, B) for dd in datas))):
+        t = steps[0][0]
+        outs = kd.prefill_block_layers(caches, [to_dev(s_[2]) for s_ in steps], [to_dev(s_[3]) for s_ in steps],
+                                       [to_dev(s_[4]) for s_ in steps], t)
+        for (cache, oc), (_, Bt, q, k, v), out in zip(layers, steps, outs):
+            ref, _, _ = oc.prefill_block(q, k, v, t)
+            err = float(np.abs(bf16_out_to_f32(out) - ref).max())
+            assert err <= ATTN_ATOL, f"attention error {err} in block at token {t}"
+        if every and bi % every == every - 1:
+            for li, (cache, oc) in enumerate(layers):
+                check_state(cache, oc, f"layer {li} after block {bi}")
+    for li, (cache, oc) in enumerate(layers):
+        check_state(cache, oc, f"layer {li} at the end")
+        assert cache.status() == 0
+        cache.close()
 
 
 def test_deferred_eviction_rides_a_launch_with_helper_waves():
