@@ -894,13 +894,15 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
         if constexpr (ALT) {
             // this wave's half of the step: the tile after this one is mine -> its logits; this tile is
             // mine -> its weights and the product with V
-            if (NEXT) {
+            auto fetch_ahead = [&]() {
+                if (NEXT) {
 #pragma unroll
-                for (int c = 0; c < LPW; ++c) {
-                    if (COPY == 1) issue_copy_cached(t + STAGES - 1, c);
-                    if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
+                    for (int c = 0; c < LPW; ++c) {
+                        if (COPY == 1) issue_copy_cached(t + STAGES - 1, c);
+                        if (COPY == 2 && t + STAGES - 1 < t1) issue_copy(t + STAGES - 1, c);
+                    }
                 }
-            }
+            };
             const bool mine = ((t - t0) & 1) == wave;   // wave uniform
             if (mine) {
                 // per 16-key chunk: its V^T fragments are requested, its weights formed (the MFMAs of
@@ -938,6 +940,10 @@ __device__ __forceinline__ void step_main_body(const StepParams &p, const int bl
                 tile_max(s, mloc);
                 new_reference(mloc);
             }
+            // the wave's share of the copies of tile t + 3 goes out after its half of the step, not before it: a
+            // copy can sit in front of a full memory queue for a third of the time the half takes, and the
+            // step ends when the slower of the two waves is done (the tile is not needed for two more steps)
+            fetch_ahead();
 #ifdef KD_TIMELINE
             if (t == t0 + 2) KD_TL(17);   // wave 0: weights and product with V of its tile done
             if (t == t0 + 3) KD_TL(21);   // wave 0: logits of its next tile done
