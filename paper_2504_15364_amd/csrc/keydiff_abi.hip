@@ -292,10 +292,10 @@ void plan_attention(const keydiff_cache *c, kd::StepParams &p, int reserved = 0)
     p.ntiles = (p.n + kd::TILE_KEYS - 1) / kd::TILE_KEYS;
     const int target = c->L.target_wgs / 2;   // the compute units of the chip
     // 8-wave workgroups run one per compute unit: rounding the split count up would push the last
-    // workgroups into a second round that doubles the kernel's duration
+    // workgroups into a second pass over the chip that doubles the kernel's duration
     int splits = target / (BH * p.mtiles);
     // one workgroup of 8 waves fills a compute unit: with passengers on board the attention takes
-    // what is left of the chip in a single round
+    // what is left of the chip in a single pass
     if (reserved > 0 && splits * BH * p.mtiles + reserved > target)
         splits = (target - reserved) / (BH * p.mtiles);
     if (splits > p.ntiles) splits = p.ntiles;
@@ -426,7 +426,7 @@ int block_step(keydiff_cache *c, const void *q, const void *k_new, const void *v
     p.do_score = evict || scores_out != nullptr;
     if (cf.window_W > 0) p.window_pos_min = (int32_t)(pos0 + Bt - cf.window_W);
 
-    // a passenger rides only if the attention still fits the chip in one round beside it
+    // a passenger rides only if the attention still fits the chip in one pass beside it
     bool riding = false;
     const bool sel_offered = carry && carry->pending && carry->pend_stream == s;
     const int seats = sel_offered ? carry->cfg.batch * carry->cfg.n_kv_heads : 0;
