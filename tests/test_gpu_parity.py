@@ -4,6 +4,8 @@ Bars: attention within 2e-2 absolute (bf16 I/O, fp32 softmax against the fp64
 oracle); scores within 1e-5 relative; retained position sets and the K/V row
 behind every retained position bit-exact.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -293,7 +295,11 @@ def _random_configs(count, seed):
     return out
 
 
-@pytest.mark.parametrize("hq,hkv,d,N,B,T,layout,anchor,window,seed", _random_configs(16, 20250415))
+# (KEYDIFF_FUZZ multiplies the number of drawn configurations, for an occasional longer run)
+FUZZ = max(1, int(os.environ.get("KEYDIFF_FUZZ", "1")))
+
+
+@pytest.mark.parametrize("hq,hkv,d,N,B,T,layout,anchor,window,seed", _random_configs(16 * FUZZ, 20250415))
 def test_seeded_random_small_configs(hq, hkv, d, N, B, T, layout, anchor, window, seed):
     w = get_config("llama32_3b").small(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prompt_T=T)
     data = make_layer(w, seed=seed)
@@ -532,7 +538,7 @@ def _random_layer_configs(count, seed):
     return out
 
 
-@pytest.mark.parametrize("hq,hkv,d,N,B,T,nl,layout,every,seed", _random_layer_configs(10, 20250416))
+@pytest.mark.parametrize("hq,hkv,d,N,B,T,nl,layout,every,seed", _random_layer_configs(10 * FUZZ, 20250416))
 def test_seeded_random_configs_through_the_layers_call(hq, hkv, d, N, B, T, nl, layout, every, seed):
     # keydiff_prefill_block_layers over drawn shapes: whichever way an eviction (and, ORDERED, its row shift) ends up
     # being run -- riding in a later launch, inside a merge launch, or alone when a state is read -- the
